@@ -1,0 +1,244 @@
+"""ctypes front end of the CPU oracle (w2v_oracle.cpp).
+
+Test infrastructure only: importable from tests/, from the smoke check and from the benchmark's
+cpu_baseline leg.  Nothing here touches the GPU library, and the GPU library never imports this.
+
+Every function takes and returns numpy arrays; shapes follow the paper's routines:
+``rows`` is [n, k+1] with the positive output word in column 0 and the negatives after it.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "w2v_oracle.cpp")
+_SO = os.path.join(_HERE, "libw2v_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with g++ (no GPU toolchain involved)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-Wall",
+               "-o", _SO, _SRC]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_SO)
+        L.orc_minibatch_seed.restype = ctypes.c_uint64
+        L.orc_minibatch_seed.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        L.orc_make_pairs.restype = ctypes.c_uint64
+        L.orc_lazy_create.restype = ctypes.c_void_p
+        L.orc_lazy_rows_held.restype = ctypes.c_uint64
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u32(a):
+    return np.ascontiguousarray(a, dtype=np.uint32)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+U64 = ctypes.c_uint64
+U32 = ctypes.c_uint32
+
+
+def philox(ctr, key):
+    c = _u32(ctr)
+    k = _u32(key)
+    out = np.zeros(4, np.uint32)
+    lib().orc_philox(_p(c), _p(k), _p(out))
+    return out
+
+
+def minibatch_seed(master_seed, h):
+    return int(lib().orc_minibatch_seed(U64(master_seed), U64(h)))
+
+
+def init_rows(seed, d_total, col_begin, d_slice, matrix, rows):
+    rows = _u32(rows)
+    out = np.empty((rows.size, d_slice), np.float32)
+    lib().orc_init_rows(U64(seed), U32(d_total), U32(col_begin), U32(d_slice), U32(matrix),
+                        _p(rows), U64(rows.size), _p(out))
+    return out
+
+
+def noise_probs(counts):
+    counts = np.ascontiguousarray(counts, dtype=np.uint64)
+    out = np.empty(counts.size, np.float64)
+    lib().orc_noise_probs(_p(counts), U32(counts.size), _p(out))
+    return out
+
+
+def build_alias(counts):
+    counts = np.ascontiguousarray(counts, dtype=np.uint64)
+    thresh = np.empty(counts.size, np.uint32)
+    alias = np.empty(counts.size, np.uint32)
+    lib().orc_build_alias(_p(counts), U32(counts.size), _p(thresh), _p(alias))
+    return thresh, alias
+
+
+def build_keep(counts, t):
+    counts = np.ascontiguousarray(counts, dtype=np.uint64)
+    out = np.empty(counts.size, np.uint64)
+    lib().orc_build_keep(_p(counts), U32(counts.size), ctypes.c_double(t), _p(out))
+    return out
+
+
+def negatives(out_idx, k, seed, thresh, alias, pair_ids=None):
+    out_idx = _u32(out_idx)
+    n = out_idx.size
+    pid = None if pair_ids is None else _u32(pair_ids)
+    neg = np.empty((n, k), np.uint32)
+    lib().orc_negatives(_p(out_idx), _p(pid), U64(n), U32(k), U64(seed), U32(thresh.size),
+                        _p(thresh), _p(alias), _p(neg))
+    return neg
+
+
+def dots(U, W, in_idx, rows):
+    U = _f32(U)
+    W = _f32(W)
+    in_idx = _u32(in_idx)
+    rows = _u32(rows)
+    n, T = rows.shape
+    out = np.empty((n, T), np.float32)
+    lib().orc_dots(_p(U), _p(W), U32(U.shape[1]), _p(in_idx), _p(rows), U64(n), U32(T), _p(out))
+    return out
+
+
+def dotprod(U, W, in_idx, out_idx, k, seed, thresh, alias):
+    U = _f32(U)
+    W = _f32(W)
+    in_idx = _u32(in_idx)
+    out_idx = _u32(out_idx)
+    n = in_idx.size
+    out = np.empty((n, k + 1), np.float32)
+    lib().orc_dotprod(_p(U), _p(W), U32(U.shape[0]), U32(U.shape[1]), _p(in_idx), _p(out_idx),
+                      U64(n), U32(k), U64(seed), _p(thresh), _p(alias), _p(out))
+    return out
+
+
+def coeffs(partials, want_loss=False):
+    """partials: list of S arrays [n, T] -> coefficient array [n, T] (and the minibatch loss)."""
+    parts = [_f32(a) for a in partials]
+    n, T = parts[0].shape
+    arr = (ctypes.c_void_p * len(parts))(*[a.ctypes.data for a in parts])
+    out = np.empty((n, T), np.float32)
+    loss = ctypes.c_double(0.0)
+    lib().orc_coeffs(arr, U32(len(parts)), U64(n), U32(T), _p(out), ctypes.byref(loss))
+    return (out, loss.value) if want_loss else out
+
+
+def adjust_rows(U, W, in_idx, rows, coeffs_, alpha, sequential_fp32=False):
+    """In place on U and W (float32, C-contiguous)."""
+    assert U.dtype == np.float32 and W.dtype == np.float32
+    assert U.flags.c_contiguous and W.flags.c_contiguous
+    in_idx = _u32(in_idx)
+    rows = _u32(rows)
+    g = _f32(coeffs_)
+    n, T = rows.shape
+    lib().orc_adjust_rows(_p(U), _p(W), U32(U.shape[1]), _p(in_idx), _p(rows), U64(n), U32(T),
+                          _p(g), ctypes.c_float(alpha), ctypes.c_int(int(sequential_fp32)))
+
+
+def adjust(U, W, in_idx, out_idx, k, seed, thresh, alias, coeffs_, alpha):
+    assert U.dtype == np.float32 and W.dtype == np.float32
+    assert U.flags.c_contiguous and W.flags.c_contiguous
+    in_idx = _u32(in_idx)
+    out_idx = _u32(out_idx)
+    g = _f32(coeffs_)
+    lib().orc_adjust(_p(U), _p(W), U32(U.shape[0]), U32(U.shape[1]), _p(in_idx), _p(out_idx),
+                     U64(in_idx.size), U32(k), U64(seed), _p(thresh), _p(alias), _p(g),
+                     ctypes.c_float(alpha))
+
+
+def train_minibatch(Us, Ws, in_idx, out_idx, k, seed, thresh, alias, alpha):
+    """One client step over S in-process column shards (lists of float32 arrays); returns loss."""
+    S = len(Us)
+    for a in list(Us) + list(Ws):
+        assert a.dtype == np.float32 and a.flags.c_contiguous
+    in_idx = _u32(in_idx)
+    out_idx = _u32(out_idx)
+    up = (ctypes.c_void_p * S)(*[a.ctypes.data for a in Us])
+    wp = (ctypes.c_void_p * S)(*[a.ctypes.data for a in Ws])
+    ds = np.array([a.shape[1] for a in Us], np.uint32)
+    loss = ctypes.c_double(0.0)
+    lib().orc_train_minibatch(up, wp, _p(ds), U32(S), U32(Us[0].shape[0]), _p(in_idx), _p(out_idx),
+                              U64(in_idx.size), U32(k), U64(seed), _p(thresh), _p(alias),
+                              ctypes.c_float(alpha), ctypes.byref(loss))
+    return loss.value
+
+
+class LazyShard:
+    """Rows created on first touch from the initialisation function; for large vocabularies."""
+
+    def __init__(self, V, d_total, col_begin, d_slice, seed, w_uniform):
+        self.d = d_slice
+        self.h = ctypes.c_void_p(lib().orc_lazy_create(U32(V), U32(d_total), U32(col_begin),
+                                                       U32(d_slice), U64(seed),
+                                                       ctypes.c_int(int(w_uniform))))
+
+    def close(self):
+        if self.h:
+            lib().orc_lazy_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        self.close()
+
+    def row(self, which, w):
+        out = np.empty(self.d, np.float32)
+        lib().orc_lazy_get_row(self.h, ctypes.c_int(which), U32(w), _p(out))
+        return out
+
+    def rows_held(self):
+        return int(lib().orc_lazy_rows_held(self.h))
+
+    def train_minibatch(self, in_idx, out_idx, k, seed, thresh, alias, alpha):
+        in_idx = _u32(in_idx)
+        out_idx = _u32(out_idx)
+        loss = ctypes.c_double(0.0)
+        lib().orc_lazy_train_minibatch(self.h, _p(in_idx), _p(out_idx), U64(in_idx.size), U32(k),
+                                       U64(seed), _p(thresh), _p(alias), ctypes.c_float(alpha),
+                                       ctypes.byref(loss))
+        return loss.value
+
+
+def make_pairs(tokens, sent_off, token_base, epoch, corpus_seed, B, keep_thresh, capacity=None):
+    tokens = _u32(tokens)
+    sent_off = np.ascontiguousarray(sent_off, dtype=np.uint64)
+    kt = None if keep_thresh is None else np.ascontiguousarray(keep_thresh, dtype=np.uint64)
+    if capacity is None:
+        capacity = int(tokens.size) * 2 * B
+    a = np.empty(capacity, np.uint32)
+    b = np.empty(capacity, np.uint32)
+    cnt = lib().orc_make_pairs(_p(tokens), _p(sent_off), U64(sent_off.size - 1), U64(token_base),
+                               U32(epoch), U64(corpus_seed), U32(B), _p(kt), _p(a), _p(b),
+                               U64(capacity))
+    cnt = int(cnt)
+    m = min(cnt, capacity)
+    return a[:m].copy(), b[:m].copy(), cnt
+
+
+def token_draws(tokens, token_base, epoch, corpus_seed, B, keep_thresh):
+    tokens = _u32(tokens)
+    kt = None if keep_thresh is None else np.ascontiguousarray(keep_thresh, dtype=np.uint64)
+    keep = np.empty(tokens.size, np.uint8)
+    b = np.empty(tokens.size, np.uint32)
+    lib().orc_token_draws(_p(tokens), U64(tokens.size), U64(token_base), U32(epoch),
+                          U64(corpus_seed), U32(B), _p(kt), _p(keep), _p(b))
+    return keep, b
