@@ -1,0 +1,169 @@
+/*
+ * w2v_shard.h -- C ABI of the MI355X shard library (libw2v_shard.so).
+ *
+ * One `w2v_shard` is one parameter-server shard of the column-partitioned word2vec system of
+ * Ordentlich et al., arXiv 1606.08495 (Section 5.1): it holds d_slice consecutive columns of EVERY
+ * input vector u(w) and output vector v(w), w = 0..V-1 (word index = rank in the vocabulary
+ * ordering), as two fp32 matrices U and W in the HBM of the current HIP device, plus the noise
+ * table the negatives are drawn from.  The calls below are the paper's remote procedure calls
+ * (dotprod, adjust, get), the client's aggregation between them, and the client's pair formation.
+ *
+ * Conventions for every call
+ *   - returns 0 on success and a negative W2V_ERR_* code otherwise; w2v_last_error() gives the text
+ *     of the calling thread's last failure.  Nothing throws across this boundary.
+ *   - "dev" pointers are device memory of the shard's GPU, owned by the caller, read or written only
+ *     by work queued on `stream` (a hipStream_t passed as void*, NULL = the default stream).  The
+ *     library keeps none of them after the call.  "host" pointers are ordinary host memory, used
+ *     before the call returns.
+ *   - calls that take a stream only queue work on it; they return before the work has run.  Calls on
+ *     one shard share that shard's scratch memory and must be stream-ordered with one another (same
+ *     stream, or the caller orders them).  Scratch grows to the largest request seen and is then
+ *     reused, so a steady-state training loop allocates nothing (cf. Section 6.1.3: the paper's
+ *     shards also create no objects in steady state).
+ *   - index arrays are uint32 word indices < V.  An index >= V never causes an out-of-range access:
+ *     the kernel substitutes word 0 and raises a sticky flag that w2v_shard_status() reports.
+ *   - layouts are row-major and dense: partial_dots / coeffs are [n][k+1] with the positive output
+ *     word in column 0 and the k negatives in columns 1..k (the paper's F+ / F- and G+ / G-
+ *     arrays, interleaved per pair).
+ *
+ * Limits: 2 <= V <= 2^31-1 (V = 1 is accepted when k = 0), 1 <= d_slice <= W2V_D_MAX,
+ * 0 <= k <= W2V_K_MAX, n*(k+1) < 2^31, S <= W2V_S_MAX.
+ */
+#ifndef W2V_SHARD_H
+#define W2V_SHARD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define W2V_K_MAX 64
+#define W2V_D_MAX 1024
+#define W2V_S_MAX 32
+
+#define W2V_OK             0
+#define W2V_ERR_NULL      -1   /* a required pointer is NULL */
+#define W2V_ERR_ARG       -2   /* a size or mode outside the limits above */
+#define W2V_ERR_ALLOC     -3   /* device or host allocation failed */
+#define W2V_ERR_HIP       -4   /* a HIP runtime call failed (text in w2v_last_error) */
+#define W2V_ERR_STATE     -5   /* the noise table has not been set (w2v_shard_set_counts) */
+#define W2V_ERR_INDEX     -6   /* some earlier call saw a word index >= V */
+#define W2V_ERR_MISMATCH  -7   /* shards passed together differ in V, device or noise table */
+
+typedef struct w2v_shard w2v_shard;
+
+const char* w2v_last_error(void);
+
+/* ---- shard life cycle (Section 5.1: column-wise partition; word2vec-style initial values) ------
+ * Allocates U and W ([V][d_slice] fp32 each, kept with an internal row stride) on the current HIP
+ * device and fills them on the device: every component is a pure function of (seed, word, GLOBAL
+ * column, matrix), uniform on [-0.5/d_total, 0.5/d_total), so the S slices of one vector agree with
+ * the unsliced vector.  init_mode 0: U uniform, W zero (the word2vec default).  init_mode 1: both
+ * uniform.  w2v_shard_create(V, d, seed) is create_ex(V, d, 0, d, seed, 0).
+ * The shard is bound to the device that was current at creation.  *out is owned by the caller until
+ * w2v_shard_destroy, which synchronises the device and frees everything the shard holds. */
+int w2v_shard_create(uint32_t V, uint32_t d_slice, uint64_t seed, w2v_shard** out);
+int w2v_shard_create_ex(uint32_t V, uint32_t d_total, uint32_t col_begin, uint32_t d_slice,
+                        uint64_t seed, int init_mode, w2v_shard** out);
+int w2v_shard_destroy(w2v_shard* shard);
+
+/* ---- vocabulary histogram -> noise table and subsample thresholds ---------------------------------
+ * Section 3 defers to the word2vec paper for the noise distribution of the negatives (count^0.75)
+ * and for the subsampling of frequent words.  counts_host[V] are occurrence counts.
+ * Builds, on the host, a Vose alias table {keep threshold, alias}[V] for the count^0.75 law and the
+ * per-word keep thresholds floor(min(1, sqrt(t/f)+t/f) * 2^32) (f = count share; subsample_t <= 0
+ * disables subsampling), and uploads them.  Synchronous.  Must be called before any call that draws
+ * negatives or forms pairs.  w2v_shard_get_tables copies the tables back (any pointer may be NULL). */
+int w2v_shard_set_counts(w2v_shard* shard, const uint64_t* counts_host, double subsample_t);
+int w2v_shard_get_tables(w2v_shard* shard, uint32_t* thresh_host, uint32_t* alias_host,
+                         uint64_t* keep_host);
+
+/* ---- get (Section 6.1.4, vector export) and its inverse ------------------------------------------
+ * which: 0 = input vectors U, 1 = output vectors W.  rows_dev[m] word indices; dst_dev/src_dev is
+ * [m][d_slice] dense.  set_rows with a word listed twice leaves one of the two values. */
+int w2v_shard_get_rows(w2v_shard* shard, int which, const uint32_t* rows_dev, uint32_t m,
+                       float* dst_dev, void* stream);
+int w2v_shard_set_rows(w2v_shard* shard, int which, const uint32_t* rows_dev, uint32_t m,
+                       const float* src_dev, void* stream);
+
+/* Waits for `stream`, then reports and clears the sticky bad-index flag (W2V_ERR_INDEX) or a pending
+ * HIP error. */
+int w2v_shard_status(w2v_shard* shard, void* stream);
+
+/* ---- negatives (Appendix, dotprod / adjust: N word indices other than the positive output word) -
+ * neg_dev[n][k]: the negatives of pair p, slot j = 1..k, a pure function of (seed, p, j, out_idx[p])
+ * and the noise table; exactly the ones w2v_dotprod and w2v_adjust use for the same arguments. */
+int w2v_negatives(w2v_shard* shard, const uint32_t* out_idx_dev, uint32_t n, uint32_t k,
+                  uint64_t seed, uint32_t* neg_dev, void* stream);
+
+/* ---- dotprod (Appendix, "Server side computation - dotprod"; Section 5.1) ------------------------
+ * For every pair p: partial_dots[p][0] = u_s(in_idx[p]) . v_s(out_idx[p]) and, for the k negatives
+ * regenerated from `seed`, partial_dots[p][j] = u_s(in_idx[p]) . v_s(neg[p][j]), over this shard's
+ * columns.  Does not modify the shard. */
+int w2v_dotprod(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
+                uint32_t n, uint32_t k, uint64_t seed, float* partial_dots_dev, void* stream);
+
+/* ---- client aggregation (Appendix, "Grid based word2vec": F = sum_s F_s, then G+ and G-) ----------
+ * partials_host[S] are S device arrays [n][k+1].  coeffs[p][0] = 1 - sigma(f), coeffs[p][j>0] =
+ * -sigma(f), f the sum over shards in shard order.  The learning rate is NOT folded in; adjust takes
+ * it separately and the product is the paper's G.  loss_dev (device double, may be NULL) receives
+ * -sum[log sigma(f+) + sum log(1 - sigma(f-))], reduced in a fixed order.  Uses shard's scratch. */
+int w2v_coeffs(w2v_shard* shard, const float* const* partials_host, uint32_t S, uint32_t n,
+               uint32_t k, float* coeffs_dev, double* loss_dev, void* stream);
+
+/* ---- adjust (Appendix, "Server side computation - adjust"; Section 5.1 last paragraph) -----------
+ * Regenerates the negatives from `seed`, then for every pair p and slot j
+ *     du(in_idx[p]) += coeffs[p][j] * v_s(row[p][j]),   dv(row[p][j]) += coeffs[p][j] * u_s(in_idx[p])
+ * with every v_s, u_s read as it was when the call began, and finally adds alpha*du, alpha*dv to the
+ * stored vectors, each touched row written once.  Contributions to one row are summed in an order
+ * fixed by (n, k) alone, so results are bitwise reproducible. */
+int w2v_adjust(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
+               uint32_t n, uint32_t k, uint64_t seed, const float* coeffs_dev, float alpha,
+               void* stream);
+
+/* ---- one client step in this process (Appendix, "Grid based word2vec", body of the minibatch loop)
+ * dotprod on each of the S shards (shards_host[S], all on one device, same V and noise table),
+ * aggregation, adjust on each shard.  With S = 1 the three phases are fused where that changes no
+ * result beyond fp32 rounding.  loss_dev as in w2v_coeffs. */
+int w2v_train_minibatch(w2v_shard* const* shards_host, uint32_t S, const uint32_t* in_idx_dev,
+                        const uint32_t* out_idx_dev, uint32_t n, uint32_t k, uint64_t seed,
+                        float alpha, double* loss_dev, void* stream);
+
+/* ---- client-side pair formation (Eq.1 index sets; Section 3 footnote on "dirty" contexts) --------
+ * tokens_dev[n_tokens] word indices; sent_off_dev[n_sent+1] token offsets of the sentences
+ * (sent_off[0] = 0, sent_off[n_sent] = n_tokens); token_base = corpus position of tokens_dev[0].
+ * Each token is kept or dropped by the subsample rule; on the surviving tokens of each sentence every
+ * center draws a half-width b uniform on 1..B and pairs (center, context) are emitted for the
+ * survivors within b positions, centers in corpus order, contexts by increasing position.  All draws
+ * are functions of (corpus_seed, token position, epoch).  Writes at most `capacity` pairs to
+ * in_idx_dev/out_idx_dev and the full count to *n_pairs_host.  Synchronises `stream`.
+ * Requires n_tokens * 2B < 2^32. */
+int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t* sent_off_dev,
+                   uint32_t n_sent, uint32_t n_tokens, uint64_t token_base, uint32_t epoch,
+                   uint64_t corpus_seed, uint32_t B, uint32_t* in_idx_dev, uint32_t* out_idx_dev,
+                   uint64_t capacity, uint64_t* n_pairs_host, void* stream);
+
+/* Seed of minibatch number h (the client picks a fresh seed per minibatch), a function of a master seed. */
+uint64_t w2v_minibatch_seed(uint64_t master_seed, uint64_t h);
+
+/* ---- per-phase GPU timing ------------------------------------------------------------------------
+ * When enabled, the library brackets each phase it queues with HIP events on the caller's stream.
+ * w2v_shard_timing_read synchronises, adds the elapsed times into ms_host[W2V_PHASES] and the launch
+ * counts into launches_host[W2V_PHASES], and resets the accumulators.  Phase order: */
+#define W2V_PH_NEG     0   /* negatives + destination keys */
+#define W2V_PH_DOT     1   /* gather dot products */
+#define W2V_PH_COEFF   2   /* aggregation + coefficients */
+#define W2V_PH_SORT    3   /* radix sorts of destination keys */
+#define W2V_PH_USIDE   4   /* input-vector changes (and, fused, dots + coefficients) */
+#define W2V_PH_WSIDE   5   /* output-vector changes, applied in place */
+#define W2V_PH_APPLY   6   /* write-back of the input-vector changes and multi-level tails */
+#define W2V_PH_PAIRS   7   /* pair formation */
+#define W2V_PHASES     8
+int w2v_shard_timing_enable(w2v_shard* shard, int on);
+int w2v_shard_timing_read(w2v_shard* shard, double* ms_host, uint64_t* launches_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

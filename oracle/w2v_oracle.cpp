@@ -10,10 +10,10 @@
 //   * the adjust server routine   (Appendix, algorithm "Server side computation - adjust")
 //   * the client's aggregation    (Appendix, algorithm "Grid based word2vec", the two lines that
 //                                  sum the partial dots and form G+ / G-)
-//   * Eq.1 / Eq.3 (objective), Eq.4 (gradient), Eq.5 (update), Section 4.1 (column slices, the
-//     "values at the start of the call" rule of adjust).
-// Where the paper only says "random number generator initialized with seed", "distribution
-// proposed in [word2vec]" or "subsampling technique of [word2vec]", the readings taken are:
+//   * Eq.1 / Eq.3 (objective), Eq.4 (gradient), Eq.5 (update), Section 5.1 (column slices, and
+//     the rule that adjust reads the vectors as they stood when the call began).
+// Where the paper only names a seeded random number generator, or defers to the word2vec paper
+// for the noise distribution and the subsampling rule, the readings taken are:
 // Philox4x32-10 (Salmon et al., SC'11) as a counter-based generator, the unigram^0.75 noise
 // distribution held in a Vose alias table, and the keep probability sqrt(t/f)+t/f.
 //
@@ -62,7 +62,7 @@ Quad philox(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint64_t seed) {
 const uint32_t DOMAIN_INIT   = 1;   // initial vector components
 const uint32_t DOMAIN_TOKEN  = 2;   // per-token subsample decision and window width
 const uint32_t DOMAIN_NEG    = 4;   // negative examples
-const uint32_t DOMAIN_MBSEED = 5;   // the per-minibatch seed the client "randomly selects"
+const uint32_t DOMAIN_MBSEED = 5;   // the per-minibatch seed chosen by the client
 
 // One initial component: word w, global column c of the full d_total-wide vector, matrix 0=U, 1=W.
 // The draw depends on the global column so that column slices of a vector agree with the unsliced one.
@@ -107,14 +107,14 @@ void orc_philox(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
     for (int i = 0; i < 4; ++i) out[i] = q.r[i];
 }
 
-// Seed of minibatch number h (the client algorithm's "randomly select a seed").
+// Seed of minibatch number h (the client algorithm picks a fresh random seed per minibatch).
 uint64_t orc_minibatch_seed(uint64_t master_seed, uint64_t h) {
     Quad q = philox((uint32_t)h, (uint32_t)(h >> 32), 0, DOMAIN_MBSEED, master_seed);
     return ((uint64_t)q.r[1] << 32) | (uint64_t)q.r[0];
 }
 
 // ---------------------------------------------------------------------------------------------
-// Initial vectors (Section 4.1: "initialized ... as in [word2vec]"): input vectors uniform in
+// Initial vectors (Section 5.1 defers to word2vec for the initial values): input vectors uniform in
 // (-0.5/d, 0.5/d); the caller zeroes the output vectors when it wants the word2vec default.
 // rows[m] lists the words wanted; out is [m][d_slice].
 // ---------------------------------------------------------------------------------------------
@@ -183,7 +183,8 @@ void orc_build_keep(const uint64_t* counts, uint32_t V, double t, uint64_t* keep
 }
 
 // ---------------------------------------------------------------------------------------------
-// Negative examples (dotprod / adjust: "N negative word indices != w_O, generated using R").
+// Negative examples (dotprod / adjust: N word indices different from the positive output word,
+// drawn from the seeded generator).
 // pair_ids == NULL means pairs 0..n-1; otherwise the negatives of the listed pair numbers
 // (out_idx is then indexed by position in the list, not by pair number).
 // neg is [n][k].

@@ -1,0 +1,54 @@
+"""Builds libw2v_shard.so (HIP kernels + C ABI) for gfx950, in tree, with hipcc.
+
+Usage: ``python -m paper_1606_08495_amd.build`` or ``build()`` from Python.  Objects go to
+``_build/`` (not tracked); the shared library lands next to this file so that it travels with the
+source tree.  hipcc cross-compiles without a GPU.
+"""
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libw2v_shard.so")
+
+HIP_SOURCES = ["api.hip", "k_gather.hip", "k_sort.hip", "k_adjust.hip", "k_pairs.hip"]
+CPP_SOURCES = ["tables.cpp"]
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+CPP_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-ffp-contract=off"]
+
+
+def _run(cmd):
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("command failed: %s\n%s" % (" ".join(cmd), r.stdout))
+    return r.stdout
+
+
+def build(verbose=False, jobs=None):
+    os.makedirs(OBJ, exist_ok=True)
+    jobs = jobs or min(8, len(HIP_SOURCES) + len(CPP_SOURCES))
+    tasks = []
+    for s in HIP_SOURCES:
+        o = os.path.join(OBJ, s + ".o")
+        tasks.append(([HIPCC] + HIP_FLAGS + ["-c", os.path.join(CSRC, s), "-o", o], o))
+    for s in CPP_SOURCES:
+        o = os.path.join(OBJ, s + ".o")
+        tasks.append((["g++"] + CPP_FLAGS + ["-c", os.path.join(CSRC, s), "-o", o], o))
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        outs = list(ex.map(lambda t: _run(t[0]), tasks))
+    if verbose:
+        for o in outs:
+            if o.strip():
+                print(o)
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [t[1] for t in tasks])
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose="-v" in sys.argv))

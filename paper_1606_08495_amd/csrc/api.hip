@@ -1,0 +1,687 @@
+// C ABI of the shard library: argument checks, scratch planning and the order in which the
+// kernels of dotprod / adjust / train_minibatch are queued.  See include/w2v_shard.h for the
+// contract of every entry point.
+#include "../../include/w2v_shard.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace w2v {
+bool build_noise_table_host(const uint64_t* counts, uint32_t V, uint32_t* thresh, uint32_t* alias);
+void build_keep_thresholds_host(const uint64_t* counts, uint32_t V, double t, uint64_t* keep);
+}  // namespace w2v
+
+using namespace w2v;
+
+// ---------------------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------------------
+static thread_local std::string g_last_error;
+
+static int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                   \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess)                                                           \
+            return fail(e_ == hipErrorOutOfMemory ? W2V_ERR_ALLOC : W2V_ERR_HIP,        \
+                        "%s failed: %s", #expr, hipGetErrorString(e_));                 \
+    } while (0)
+
+extern "C" const char* w2v_last_error(void) { return g_last_error.c_str(); }
+
+// ---------------------------------------------------------------------------------------------
+// shard object
+// ---------------------------------------------------------------------------------------------
+struct TimedSpan { int phase; hipEvent_t a, b; };
+
+struct w2v_shard {
+    int device = 0;
+    uint32_t V = 0, d_total = 0, col_begin = 0, d_slice = 0;
+    uint64_t seed = 0;
+    int init_mode = 0;
+    RowGeom g{0, 0};
+    float* U = nullptr;
+    float* W = nullptr;
+    uint2* bins = nullptr;          // noise table
+    uint64_t* keep = nullptr;       // subsample thresholds (nullptr: keep everything)
+    bool has_tables = false;
+    uint64_t table_tag = 0;         // checksum of the noise table, to compare shards
+    uint32_t* err = nullptr;        // sticky device flag
+    // scratch: one region, carved per call
+    char* ws = nullptr;
+    size_t ws_cap = 0;
+    // timing
+    bool timing = false;
+    std::vector<TimedSpan> spans;
+    std::vector<hipEvent_t> pool;
+    double ms[W2V_PHASES] = {0};
+    uint64_t launches[W2V_PHASES] = {0};
+};
+
+namespace {
+
+struct Carver {
+    char* base; size_t off = 0;
+    explicit Carver(char* b) : base(b) {}
+    template <typename T> T* take(size_t count) {
+        off = (off + 255) & ~(size_t)255;
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+};
+
+int ensure_ws(w2v_shard* sh, size_t bytes) {
+    if (bytes <= sh->ws_cap) return W2V_OK;
+    if (sh->ws) { HIP_TRY(hipDeviceSynchronize()); HIP_TRY(hipFree(sh->ws)); sh->ws = nullptr; sh->ws_cap = 0; }
+    size_t want = bytes + bytes / 8 + 4096;
+    hipError_t e = hipMalloc((void**)&sh->ws, want);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        want = bytes;
+        e = hipMalloc((void**)&sh->ws, want);
+    }
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(W2V_ERR_ALLOC, "scratch allocation of %zu bytes failed: %s", want,
+                    hipGetErrorString(e));
+    }
+    sh->ws_cap = want;
+    return W2V_OK;
+}
+
+struct Phase {
+    w2v_shard* sh; int phase; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
+    Phase(w2v_shard* s, int ph, hipStream_t stream) : sh(s), phase(ph), st(stream) {
+        if (!sh->timing) return;
+        a = grab(); b = grab();
+        if (a && b) (void)hipEventRecord(a, st);
+    }
+    ~Phase() {
+        if (!sh->timing || !a || !b) return;
+        (void)hipEventRecord(b, st);
+        sh->spans.push_back(TimedSpan{phase, a, b});
+    }
+    hipEvent_t grab() {
+        if (!sh->pool.empty()) { hipEvent_t e = sh->pool.back(); sh->pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+};
+
+int check_device(const w2v_shard* sh) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != sh->device)
+        return fail(W2V_ERR_MISMATCH, "shard lives on device %d but device %d is current",
+                    sh->device, dev);
+    return W2V_OK;
+}
+
+int check_batch(const w2v_shard* sh, uint32_t n, uint32_t k, bool needs_tables) {
+    if (k > W2V_K_MAX) return fail(W2V_ERR_ARG, "k = %u exceeds W2V_K_MAX = %d", k, W2V_K_MAX);
+    if ((uint64_t)n * (k + 1) >= (1ull << 31))
+        return fail(W2V_ERR_ARG, "n*(k+1) = %llu must stay below 2^31",
+                    (unsigned long long)((uint64_t)n * (k + 1)));
+    if (k > 0 && sh->V < 2) return fail(W2V_ERR_ARG, "negatives need a vocabulary of at least 2 words");
+    if (needs_tables && k > 0 && !sh->has_tables)
+        return fail(W2V_ERR_STATE, "w2v_shard_set_counts has not been called on this shard");
+    return W2V_OK;
+}
+
+uint32_t key_bits(uint32_t V) {
+    uint32_t bits = 1;
+    while (bits < 32 && (1ull << bits) < (uint64_t)V) ++bits;
+    return bits;
+}
+
+uint32_t slots_after(uint32_t entries, uint32_t per_chunk) {
+    if (entries == 0) return 0;
+    uint32_t chunks = (entries + per_chunk - 1) / per_chunk;
+    return 2 * (chunks - 1);
+}
+
+// Everything one minibatch needs in scratch, carved in a fixed order.
+struct Plan {
+    uint32_t n, T, M;
+    uint32_t* keys; uint32_t* in_safe;
+    uint32_t *uk0, *uv0, *uk1, *uv1;       // sort buffers, input side (n)
+    uint32_t *wk0, *wv0, *wk1, *wv1;       // sort buffers, output side (M)
+    uint32_t* sort_tmp;
+    float* coeffs; float* dots; double* loss_tmp;
+    float* delta; uint32_t* dkey;
+    float* pa_rows; uint32_t* pa_keys;     // input side, level 1 slots
+    float* pb_rows; uint32_t* pb_keys;     // output side, level 1 slots
+    float* pc_rows; uint32_t* pc_keys;     // level 2 slots of either side
+    uint32_t slots_u1, slots_w1, slots_2;
+    size_t bytes;
+};
+
+Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_t S_dots,
+               bool want_adjust, bool want_coeffs) {
+    Plan p{};
+    p.n = n; p.T = k + 1; p.M = n * p.T;
+    Carver c(base);
+    p.keys = c.take<uint32_t>(p.M);
+    p.in_safe = c.take<uint32_t>(n);
+    if (want_coeffs) p.coeffs = c.take<float>(p.M);
+    if (S_dots) p.dots = c.take<float>((size_t)S_dots * p.M);
+    p.loss_tmp = c.take<double>(std::max<size_t>(coeffs_loss_scratch_doubles(n, p.T), n) + 8);
+    if (want_adjust) {
+        p.uk0 = c.take<uint32_t>(n); p.uv0 = c.take<uint32_t>(n);
+        p.uk1 = c.take<uint32_t>(n); p.uv1 = c.take<uint32_t>(n);
+        p.wk0 = c.take<uint32_t>(p.M); p.wv0 = c.take<uint32_t>(p.M);
+        p.wk1 = c.take<uint32_t>(p.M); p.wv1 = c.take<uint32_t>(p.M);
+        p.sort_tmp = c.take<uint32_t>(sort_scratch_u32(p.M ? p.M : 1));
+        const size_t row = (size_t)stride4_max * 4;
+        p.delta = c.take<float>((size_t)n * row);
+        p.dkey = c.take<uint32_t>(n);
+        p.slots_u1 = slots_after(n, useg_pairs_per_chunk(p.T));
+        p.slots_w1 = slots_after(p.M, wseg_entries_per_chunk());
+        uint32_t s2u = slots_after(p.slots_u1, tail_entries_per_chunk());
+        uint32_t s2w = slots_after(p.slots_w1, tail_entries_per_chunk());
+        p.slots_2 = std::max(s2u, s2w);
+        p.pa_rows = c.take<float>((size_t)p.slots_u1 * row); p.pa_keys = c.take<uint32_t>(p.slots_u1 + 1);
+        p.pb_rows = c.take<float>((size_t)p.slots_w1 * row); p.pb_keys = c.take<uint32_t>(p.slots_w1 + 1);
+        p.pc_rows = c.take<float>((size_t)p.slots_2 * row);  p.pc_keys = c.take<uint32_t>(p.slots_2 + 1);
+    }
+    p.bytes = c.off + 256;
+    return p;
+}
+
+// Reduce the partial slots of one side level by level into matrix M (in place).
+void run_tails(w2v_shard* sh, float* M, float alpha, float* rows_a, uint32_t* keys_a, uint32_t slots,
+               float* rows_b, uint32_t* keys_b, hipStream_t st) {
+    float* src_rows = rows_a; uint32_t* src_keys = keys_a;
+    float* dst_rows = rows_b; uint32_t* dst_keys = keys_b;
+    while (slots > 0) {
+        TailArgs t{M, sh->g, alpha, src_rows, src_keys, slots, dst_rows, dst_keys};
+        launch_tail(t, st);
+        slots = slots_after(slots, tail_entries_per_chunk());
+        std::swap(src_rows, dst_rows);
+        std::swap(src_keys, dst_keys);
+    }
+}
+
+void sort_both_sides(w2v_shard* sh, Plan& p, uint32_t** sku, uint32_t** perm, uint32_t** skw,
+                     uint32_t** sidx, hipStream_t st) {
+    Phase ph(sh, W2V_PH_SORT, st);
+    uint32_t bits = key_bits(sh->V);
+    launch_sort_pairs(p.in_safe, p.uk0, p.uv0, p.uk1, p.uv1, p.n, bits, p.sort_tmp, sku, perm, st);
+    launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp, skw, sidx, st);
+}
+
+// The update of one shard from given coefficients (or, fused, from its own dots).
+void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* sku,
+                  const uint32_t* perm, const uint32_t* skw, const uint32_t* sidx,
+                  const float* coeffs_in, float* coeffs_out, double* pair_loss, bool fused,
+                  float alpha, hipStream_t st) {
+    {
+        Phase ph(ws_owner, W2V_PH_USIDE, st);
+        USideArgs a{};
+        a.U = sh->U; a.W = sh->W; a.g = sh->g; a.skey = sku; a.perm = perm; a.keys = p.keys;
+        a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
+        a.dots_out = nullptr; a.pair_loss = pair_loss; a.delta = p.delta; a.dkey = p.dkey;
+        a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
+        launch_useg(a, st);
+    }
+    {
+        Phase ph(ws_owner, W2V_PH_WSIDE, st);
+        WSideArgs w{};
+        w.U = sh->U; w.W = sh->W; w.g = sh->g; w.skey = skw; w.sidx = sidx; w.M = p.M; w.T = p.T;
+        w.in_idx = p.in_safe; w.coeffs = fused ? coeffs_out : coeffs_in; w.alpha = alpha;
+        w.prows = p.pb_rows; w.pkeys = p.pb_keys;
+        launch_wseg(w, st);
+    }
+    {
+        Phase ph(ws_owner, W2V_PH_APPLY, st);
+        run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st);
+        launch_apply_delta(sh->U, sh->g, p.delta, p.dkey, p.n, alpha, st);
+        run_tails(sh, sh->U, alpha, p.pa_rows, p.pa_keys, p.slots_u1, p.pc_rows, p.pc_keys, st);
+    }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// life cycle
+// ---------------------------------------------------------------------------------------------
+extern "C" int w2v_shard_create_ex(uint32_t V, uint32_t d_total, uint32_t col_begin,
+                                   uint32_t d_slice, uint64_t seed, int init_mode,
+                                   w2v_shard** out) {
+    if (!out) return fail(W2V_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (V == 0 || V > 0x7FFFFFFFu) return fail(W2V_ERR_ARG, "V = %u outside 1..2^31-1", V);
+    if (d_slice == 0 || d_slice > W2V_D_MAX)
+        return fail(W2V_ERR_ARG, "d_slice = %u outside 1..%d", d_slice, W2V_D_MAX);
+    if (d_total == 0 || (uint64_t)col_begin + d_slice > d_total)
+        return fail(W2V_ERR_ARG, "columns [%u, %u) do not fit d_total = %u", col_begin,
+                    col_begin + d_slice, d_total);
+    if (init_mode != 0 && init_mode != 1) return fail(W2V_ERR_ARG, "init_mode must be 0 or 1");
+
+    w2v_shard* sh = new (std::nothrow) w2v_shard();
+    if (!sh) return fail(W2V_ERR_ALLOC, "host allocation failed");
+    HIP_TRY(hipGetDevice(&sh->device));
+    sh->V = V; sh->d_total = d_total; sh->col_begin = col_begin; sh->d_slice = d_slice;
+    sh->seed = seed; sh->init_mode = init_mode;
+    sh->g.d4 = (d_slice + 3) / 4;
+    uint32_t align4 = 1;                     // row stride granularity in float4
+    if (const char* env = getenv("W2V_ROW_ALIGN_FLOATS")) {
+        long v = atol(env);
+        if (v >= 4 && v <= 256 && (v % 4) == 0) align4 = (uint32_t)v / 4;
+    }
+    sh->g.stride4 = ((sh->g.d4 + align4 - 1) / align4) * align4;
+
+    size_t bytes = (size_t)V * sh->g.stride4 * 16;
+    hipError_t e = hipMalloc((void**)&sh->U, bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&sh->W, bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&sh->err, 256);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        int rc = fail(W2V_ERR_ALLOC, "allocating 2 x %zu bytes of vectors failed: %s", bytes,
+                      hipGetErrorString(e));
+        if (sh->U) (void)hipFree(sh->U);
+        if (sh->W) (void)hipFree(sh->W);
+        if (sh->err) (void)hipFree(sh->err);
+        delete sh;
+        return rc;
+    }
+    launch_init(sh->U, V, sh->g, d_slice, d_total, col_begin, seed, 0, false, nullptr);
+    launch_init(sh->W, V, sh->g, d_slice, d_total, col_begin, seed, 1, init_mode == 0, nullptr);
+    hipError_t le = hipGetLastError();
+    if (le == hipSuccess) le = hipMemset(sh->err, 0, 256);
+    hipError_t se = hipDeviceSynchronize();
+    if (le != hipSuccess || se != hipSuccess) {
+        int rc = fail(W2V_ERR_HIP, "initialisation kernels failed: %s",
+                      hipGetErrorString(le != hipSuccess ? le : se));
+        (void)hipFree(sh->U); (void)hipFree(sh->W); (void)hipFree(sh->err);
+        delete sh;
+        return rc;
+    }
+    *out = sh;
+    return W2V_OK;
+}
+
+extern "C" int w2v_shard_create(uint32_t V, uint32_t d_slice, uint64_t seed, w2v_shard** out) {
+    return w2v_shard_create_ex(V, d_slice, 0, d_slice, seed, 0, out);
+}
+
+extern "C" int w2v_shard_destroy(w2v_shard* sh) {
+    if (!sh) return W2V_OK;
+    (void)hipDeviceSynchronize();
+    for (auto& s : sh->spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+    for (auto e : sh->pool) (void)hipEventDestroy(e);
+    if (sh->U) (void)hipFree(sh->U);
+    if (sh->W) (void)hipFree(sh->W);
+    if (sh->bins) (void)hipFree(sh->bins);
+    if (sh->keep) (void)hipFree(sh->keep);
+    if (sh->err) (void)hipFree(sh->err);
+    if (sh->ws) (void)hipFree(sh->ws);
+    delete sh;
+    return W2V_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// tables
+// ---------------------------------------------------------------------------------------------
+extern "C" int w2v_shard_set_counts(w2v_shard* sh, const uint64_t* counts, double subsample_t) {
+    if (!sh || !counts) return fail(W2V_ERR_NULL, "shard or counts is NULL");
+    int rc = check_device(sh);
+    if (rc) return rc;
+    const uint32_t V = sh->V;
+    std::vector<uint32_t> thresh, alias;
+    std::vector<uint64_t> keep;
+    std::vector<uint2> packed;
+    try {
+        thresh.resize(V); alias.resize(V); keep.resize(V); packed.resize(V);
+    } catch (const std::bad_alloc&) {
+        return fail(W2V_ERR_ALLOC, "host allocation for the tables failed");
+    }
+    if (!build_noise_table_host(counts, V, thresh.data(), alias.data()))
+        return fail(W2V_ERR_ALLOC, "host allocation for the alias construction failed");
+    build_keep_thresholds_host(counts, V, subsample_t, keep.data());
+    uint64_t tag = 1469598103934665603ull;
+    for (uint32_t w = 0; w < V; ++w) {
+        packed[w] = make_uint2(thresh[w], alias[w]);
+        tag = (tag ^ thresh[w]) * 1099511628211ull;
+        tag = (tag ^ alias[w]) * 1099511628211ull;
+    }
+    HIP_TRY(hipDeviceSynchronize());
+    if (!sh->bins) HIP_TRY(hipMalloc((void**)&sh->bins, sizeof(uint2) * (size_t)V));
+    if (!sh->keep) HIP_TRY(hipMalloc((void**)&sh->keep, sizeof(uint64_t) * (size_t)V));
+    HIP_TRY(hipMemcpy(sh->bins, packed.data(), sizeof(uint2) * (size_t)V, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(sh->keep, keep.data(), sizeof(uint64_t) * (size_t)V, hipMemcpyHostToDevice));
+    sh->has_tables = true;
+    sh->table_tag = tag;
+    return W2V_OK;
+}
+
+extern "C" int w2v_shard_get_tables(w2v_shard* sh, uint32_t* thresh, uint32_t* alias,
+                                    uint64_t* keep) {
+    if (!sh) return fail(W2V_ERR_NULL, "shard is NULL");
+    if (!sh->has_tables) return fail(W2V_ERR_STATE, "no tables set");
+    int rc = check_device(sh);
+    if (rc) return rc;
+    const uint32_t V = sh->V;
+    if (thresh || alias) {
+        std::vector<uint2> packed(V);
+        HIP_TRY(hipMemcpy(packed.data(), sh->bins, sizeof(uint2) * (size_t)V, hipMemcpyDeviceToHost));
+        for (uint32_t w = 0; w < V; ++w) {
+            if (thresh) thresh[w] = packed[w].x;
+            if (alias) alias[w] = packed[w].y;
+        }
+    }
+    if (keep) HIP_TRY(hipMemcpy(keep, sh->keep, sizeof(uint64_t) * (size_t)V, hipMemcpyDeviceToHost));
+    return W2V_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// rows, status
+// ---------------------------------------------------------------------------------------------
+extern "C" int w2v_shard_get_rows(w2v_shard* sh, int which, const uint32_t* rows, uint32_t m,
+                                  float* dst, void* stream) {
+    if (!sh || (m && (!rows || !dst))) return fail(W2V_ERR_NULL, "NULL argument");
+    if (which != 0 && which != 1) return fail(W2V_ERR_ARG, "which must be 0 (U) or 1 (W)");
+    int rc = check_device(sh);
+    if (rc) return rc;
+    launch_gather_rows(which ? sh->W : sh->U, sh->g, sh->d_slice, rows, m, sh->V, dst, sh->err,
+                       (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+extern "C" int w2v_shard_set_rows(w2v_shard* sh, int which, const uint32_t* rows, uint32_t m,
+                                  const float* src, void* stream) {
+    if (!sh || (m && (!rows || !src))) return fail(W2V_ERR_NULL, "NULL argument");
+    if (which != 0 && which != 1) return fail(W2V_ERR_ARG, "which must be 0 (U) or 1 (W)");
+    int rc = check_device(sh);
+    if (rc) return rc;
+    launch_scatter_rows(which ? sh->W : sh->U, sh->g, sh->d_slice, rows, m, sh->V, src, sh->err,
+                        (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+extern "C" int w2v_shard_status(w2v_shard* sh, void* stream) {
+    if (!sh) return fail(W2V_ERR_NULL, "shard is NULL");
+    int rc = check_device(sh);
+    if (rc) return rc;
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    uint32_t flag = 0;
+    HIP_TRY(hipMemcpy(&flag, sh->err, sizeof(flag), hipMemcpyDeviceToHost));
+    if (flag) {
+        uint32_t zero = 0;
+        HIP_TRY(hipMemcpy(sh->err, &zero, sizeof(zero), hipMemcpyHostToDevice));
+        return fail(W2V_ERR_INDEX, "a word index >= V = %u was passed to an earlier call", sh->V);
+    }
+    return W2V_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// negatives, dotprod, coeffs
+// ---------------------------------------------------------------------------------------------
+extern "C" int w2v_negatives(w2v_shard* sh, const uint32_t* out_idx, uint32_t n, uint32_t k,
+                             uint64_t seed, uint32_t* neg, void* stream) {
+    if (!sh || (n && (!out_idx || (k && !neg)))) return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_device(sh);
+    if (!rc) rc = check_batch(sh, n, k, true);
+    if (rc) return rc;
+    if (n == 0 || k == 0) return W2V_OK;
+    hipStream_t st = (hipStream_t)stream;
+    Plan sz = make_plan(nullptr, n, k, sh->g.stride4, 0, false, false);
+    rc = ensure_ws(sh, sz.bytes);
+    if (rc) return rc;
+    Plan p = make_plan(sh->ws, n, k, sh->g.stride4, 0, false, false);
+    {
+        Phase ph(sh, W2V_PH_NEG, st);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, out_idx, n, k, seed, p.keys,
+                         p.in_safe, sh->err, st);
+        launch_copy_negatives(p.keys, n, k, neg, st);
+    }
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+extern "C" int w2v_dotprod(w2v_shard* sh, const uint32_t* in_idx, const uint32_t* out_idx,
+                           uint32_t n, uint32_t k, uint64_t seed, float* partial_dots,
+                           void* stream) {
+    if (!sh || (n && (!in_idx || !out_idx || !partial_dots)))
+        return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_device(sh);
+    if (!rc) rc = check_batch(sh, n, k, true);
+    if (rc) return rc;
+    if (n == 0) return W2V_OK;
+    hipStream_t st = (hipStream_t)stream;
+    Plan sz = make_plan(nullptr, n, k, sh->g.stride4, 0, false, false);
+    rc = ensure_ws(sh, sz.bytes);
+    if (rc) return rc;
+    Plan p = make_plan(sh->ws, n, k, sh->g.stride4, 0, false, false);
+    {
+        Phase ph(sh, W2V_PH_NEG, st);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, in_idx, out_idx, n, k, seed, p.keys,
+                         p.in_safe, sh->err, st);
+    }
+    {
+        Phase ph(sh, W2V_PH_DOT, st);
+        launch_dots(sh->U, sh->W, sh->g, p.in_safe, p.keys, n, p.T, partial_dots, st);
+    }
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+extern "C" int w2v_coeffs(w2v_shard* sh, const float* const* partials, uint32_t S, uint32_t n,
+                          uint32_t k, float* coeffs, double* loss, void* stream) {
+    if (!sh || !partials || (n && !coeffs)) return fail(W2V_ERR_NULL, "NULL argument");
+    if (S == 0 || S > W2V_S_MAX) return fail(W2V_ERR_ARG, "S = %u outside 1..%d", S, W2V_S_MAX);
+    int rc = check_device(sh);
+    if (!rc) rc = check_batch(sh, n, k, false);
+    if (rc) return rc;
+    PartialPtrs pp{};
+    for (uint32_t s = 0; s < S; ++s) {
+        if (n && !partials[s]) return fail(W2V_ERR_NULL, "partials[%u] is NULL", s);
+        pp.p[s] = partials[s];
+    }
+    hipStream_t st = (hipStream_t)stream;
+    size_t need = sizeof(double) * (coeffs_loss_scratch_doubles(n, k + 1) + 8) + 512;
+    rc = ensure_ws(sh, need);
+    if (rc) return rc;
+    {
+        Phase ph(sh, W2V_PH_COEFF, st);
+        launch_coeffs(pp, S, n, k + 1, coeffs, (double*)sh->ws, loss, st);
+    }
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// adjust
+// ---------------------------------------------------------------------------------------------
+extern "C" int w2v_adjust(w2v_shard* sh, const uint32_t* in_idx, const uint32_t* out_idx,
+                          uint32_t n, uint32_t k, uint64_t seed, const float* coeffs, float alpha,
+                          void* stream) {
+    if (!sh || (n && (!in_idx || !out_idx || !coeffs))) return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_device(sh);
+    if (!rc) rc = check_batch(sh, n, k, true);
+    if (rc) return rc;
+    if (n == 0) return W2V_OK;
+    hipStream_t st = (hipStream_t)stream;
+    Plan sz = make_plan(nullptr, n, k, sh->g.stride4, 0, true, false);
+    rc = ensure_ws(sh, sz.bytes);
+    if (rc) return rc;
+    Plan p = make_plan(sh->ws, n, k, sh->g.stride4, 0, true, false);
+    {
+        Phase ph(sh, W2V_PH_NEG, st);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, in_idx, out_idx, n, k, seed, p.keys,
+                         p.in_safe, sh->err, st);
+    }
+    uint32_t *sku, *perm, *skw, *sidx;
+    sort_both_sides(sh, p, &sku, &perm, &skw, &sidx, st);
+    queue_adjust(sh, sh, p, sku, perm, skw, sidx, coeffs, nullptr, nullptr, false, alpha, st);
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// one client step
+// ---------------------------------------------------------------------------------------------
+extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const uint32_t* in_idx,
+                                   const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed,
+                                   float alpha, double* loss, void* stream) {
+    if (!shards || (n && (!in_idx || !out_idx))) return fail(W2V_ERR_NULL, "NULL argument");
+    if (S == 0 || S > W2V_S_MAX) return fail(W2V_ERR_ARG, "S = %u outside 1..%d", S, W2V_S_MAX);
+    uint32_t stride_max = 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        if (!shards[s]) return fail(W2V_ERR_NULL, "shards[%u] is NULL", s);
+        if (shards[s]->V != shards[0]->V || shards[s]->device != shards[0]->device)
+            return fail(W2V_ERR_MISMATCH, "shard %u differs from shard 0 in V or device", s);
+        if (k > 0 && shards[s]->has_tables && shards[0]->has_tables &&
+            shards[s]->table_tag != shards[0]->table_tag)
+            return fail(W2V_ERR_MISMATCH, "shard %u holds a different noise table", s);
+        stride_max = std::max(stride_max, shards[s]->g.stride4);
+    }
+    w2v_shard* s0 = shards[0];
+    int rc = check_device(s0);
+    if (!rc) rc = check_batch(s0, n, k, true);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (n == 0) {
+        if (loss) launch_sum_pair_loss(nullptr, 0, loss, st);
+        return W2V_OK;
+    }
+    const bool fused = (S == 1);
+    Plan sz = make_plan(nullptr, n, k, stride_max, fused ? 0 : S, true, true);
+    rc = ensure_ws(s0, sz.bytes);
+    if (rc) return rc;
+    Plan p = make_plan(s0->ws, n, k, stride_max, fused ? 0 : S, true, true);
+    {
+        Phase ph(s0, W2V_PH_NEG, st);
+        launch_dest_keys(NoiseTable{s0->bins, s0->V}, in_idx, out_idx, n, k, seed, p.keys,
+                         p.in_safe, s0->err, st);
+    }
+    uint32_t *sku, *perm, *skw, *sidx;
+    if (fused) {
+        sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
+        queue_adjust(s0, s0, p, sku, perm, skw, sidx, nullptr, p.coeffs, loss ? p.loss_tmp : nullptr,
+                     true, alpha, st);
+        if (loss) launch_sum_pair_loss(p.loss_tmp, n, loss, st);
+    } else {
+        PartialPtrs pp{};
+        {
+            Phase ph(s0, W2V_PH_DOT, st);
+            for (uint32_t s = 0; s < S; ++s) {
+                float* d = p.dots + (size_t)s * p.M;
+                launch_dots(shards[s]->U, shards[s]->W, shards[s]->g, p.in_safe, p.keys, n, p.T, d, st);
+                pp.p[s] = d;
+            }
+        }
+        {
+            Phase ph(s0, W2V_PH_COEFF, st);
+            launch_coeffs(pp, S, n, p.T, p.coeffs, p.loss_tmp, loss, st);
+        }
+        sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
+        for (uint32_t s = 0; s < S; ++s)
+            queue_adjust(s0, shards[s], p, sku, perm, skw, sidx, p.coeffs, nullptr, nullptr, false,
+                         alpha, st);
+    }
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// pair formation
+// ---------------------------------------------------------------------------------------------
+extern "C" int w2v_make_pairs(w2v_shard* sh, const uint32_t* tokens, const uint64_t* sent_off,
+                              uint32_t n_sent, uint32_t n_tokens, uint64_t token_base,
+                              uint32_t epoch, uint64_t corpus_seed, uint32_t B, uint32_t* in_idx,
+                              uint32_t* out_idx, uint64_t capacity, uint64_t* n_pairs,
+                              void* stream) {
+    if (!sh || !n_pairs) return fail(W2V_ERR_NULL, "NULL argument");
+    *n_pairs = 0;
+    if (n_tokens && (!tokens || !sent_off)) return fail(W2V_ERR_NULL, "NULL argument");
+    if (capacity && (!in_idx || !out_idx)) return fail(W2V_ERR_NULL, "NULL output");
+    if (B == 0) return fail(W2V_ERR_ARG, "window B must be at least 1");
+    if (n_tokens && n_sent == 0) return fail(W2V_ERR_ARG, "tokens without sentences");
+    if ((uint64_t)n_tokens * 2 * B >= (1ull << 32))
+        return fail(W2V_ERR_ARG, "n_tokens * 2B must stay below 2^32; pass the corpus in blocks");
+    int rc = check_device(sh);
+    if (rc) return rc;
+    if (n_tokens == 0) return W2V_OK;
+    hipStream_t st = (hipStream_t)stream;
+    size_t need = sizeof(uint32_t) * (pairs_scratch_u32(n_tokens) + 64) + 512;
+    rc = ensure_ws(sh, need);
+    if (rc) return rc;
+    PairArgs a{};
+    a.tokens = tokens; a.sent_off = sent_off; a.n_sent = n_sent; a.n_tokens = n_tokens;
+    a.token_base = token_base; a.epoch = epoch; a.seed = corpus_seed; a.B = B;
+    a.keep = sh->has_tables ? sh->keep : nullptr; a.V = sh->V;
+    a.in_idx = in_idx; a.out_idx = out_idx; a.capacity = capacity;
+    a.total_pairs = (uint32_t*)sh->ws;
+    a.scratch = (uint32_t*)sh->ws + 64;
+    a.err = sh->err;
+    {
+        Phase ph(sh, W2V_PH_PAIRS, st);
+        launch_make_pairs(a, st);
+    }
+    HIP_TRY(hipGetLastError());
+    uint32_t total = 0;
+    HIP_TRY(hipMemcpyAsync(&total, a.total_pairs, sizeof(total), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    *n_pairs = total;
+    return W2V_OK;
+}
+
+extern "C" uint64_t w2v_minibatch_seed(uint64_t master_seed, uint64_t h) {
+    U4 r = philox4x32_10((uint32_t)h, (uint32_t)(h >> 32), 0, DOM_MBSEED, (uint32_t)master_seed,
+                         (uint32_t)(master_seed >> 32));
+    return ((uint64_t)r.y << 32) | (uint64_t)r.x;
+}
+
+// ---------------------------------------------------------------------------------------------
+// timing
+// ---------------------------------------------------------------------------------------------
+extern "C" int w2v_shard_timing_enable(w2v_shard* sh, int on) {
+    if (!sh) return fail(W2V_ERR_NULL, "shard is NULL");
+    sh->timing = on != 0;
+    return W2V_OK;
+}
+
+extern "C" int w2v_shard_timing_read(w2v_shard* sh, double* ms, uint64_t* launches) {
+    if (!sh || !ms || !launches) return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_device(sh);
+    if (rc) return rc;
+    HIP_TRY(hipDeviceSynchronize());
+    for (auto& s : sh->spans) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, s.a, s.b) == hipSuccess) {
+            sh->ms[s.phase] += (double)t;
+            sh->launches[s.phase] += 1;
+        } else {
+            (void)hipGetLastError();
+        }
+        sh->pool.push_back(s.a);
+        sh->pool.push_back(s.b);
+    }
+    sh->spans.clear();
+    for (int i = 0; i < W2V_PHASES; ++i) {
+        ms[i] = sh->ms[i]; launches[i] = sh->launches[i];
+        sh->ms[i] = 0; sh->launches[i] = 0;
+    }
+    return W2V_OK;
+}

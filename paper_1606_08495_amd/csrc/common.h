@@ -1,0 +1,152 @@
+// Shared declarations of the shard library's translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace w2v {
+
+// ---- counter-based generator (Philox4x32, 10 rounds; Salmon et al., SC'11) -----------------------
+// The fourth counter word separates the uses of the generator.
+enum : uint32_t { DOM_INIT = 1, DOM_TOKEN = 2, DOM_NEG = 4, DOM_MBSEED = 5 };
+
+struct U4 { uint32_t x, y, z, w; };
+
+__host__ __device__ inline uint32_t mulhi32(uint32_t a, uint32_t b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __umulhi(a, b);
+#else
+    return (uint32_t)(((uint64_t)a * (uint64_t)b) >> 32);
+#endif
+}
+
+__host__ __device__ inline U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                            uint32_t k0, uint32_t k1) {
+    const uint32_t MA = 0xD2511F53u, MB = 0xCD9E8D57u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t hiA = mulhi32(MA, c0), loA = MA * c0;
+        uint32_t hiB = mulhi32(MB, c2), loB = MB * c2;
+        uint32_t t0 = hiB ^ c1 ^ k0;
+        uint32_t t2 = hiA ^ c3 ^ k1;
+        c0 = t0; c1 = loB; c2 = t2; c3 = loA;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return U4{c0, c1, c2, c3};
+}
+
+// ---- row geometry ------------------------------------------------------------------------------
+// A row of either matrix is `stride4` float4 in memory, of which the first d4 = ceil(d_slice/4)
+// carry data (columns >= d_slice inside the last float4 are kept at zero).  A group of G lanes owns
+// one row at a time; lane l holds float4 number l, l+G, ..., l+(NV-1)G.
+struct RowGeom {
+    uint32_t d4;        // float4 per row that carry data
+    uint32_t stride4;   // float4 between consecutive rows
+};
+
+constexpr uint32_t KEY_NONE = 0xFFFFFFFFu;   // "no destination" in partial-sum key arrays
+constexpr uint32_t KEY_ZERO = 0x80000000u;   // flag: slot belongs to the row but holds no data
+constexpr uint32_t KEY_MASK = 0x7FFFFFFFu;
+
+// ---- launch wrappers (defined in the .hip files) -------------------------------------------------
+struct NoiseTable { const uint2* bins; uint32_t V; };   // {keep threshold, alias} per word
+
+void launch_init(float* M, uint32_t V, RowGeom g, uint32_t d_slice, uint32_t d_total,
+                 uint32_t col_begin, uint64_t seed, uint32_t matrix, bool zero, hipStream_t st);
+void launch_gather_rows(const float* M, RowGeom g, uint32_t d_slice, const uint32_t* rows,
+                        uint32_t m, uint32_t V, float* dst, uint32_t* err, hipStream_t st);
+void launch_scatter_rows(float* M, RowGeom g, uint32_t d_slice, const uint32_t* rows, uint32_t m,
+                         uint32_t V, const float* src, uint32_t* err, hipStream_t st);
+
+// keys[p*T + 0] = out_idx[p], keys[p*T + j] = negative j.  Indices >= V raise *err and are
+// replaced by 0; in_safe[p] is the checked copy of in_idx[p] that every later kernel uses.
+void launch_dest_keys(NoiseTable nt, const uint32_t* in_idx, const uint32_t* out_idx, uint32_t n,
+                      uint32_t k, uint64_t seed, uint32_t* keys, uint32_t* in_safe, uint32_t* err,
+                      hipStream_t st);
+void launch_copy_negatives(const uint32_t* keys, uint32_t n, uint32_t k, uint32_t* neg,
+                           hipStream_t st);
+
+void launch_dots(const float* U, const float* W, RowGeom g, const uint32_t* in_safe,
+                 const uint32_t* keys, uint32_t n, uint32_t T, float* dots, hipStream_t st);
+
+struct PartialPtrs { const float* p[32]; };
+void launch_coeffs(PartialPtrs parts, uint32_t S, uint32_t n, uint32_t T, float* coeffs,
+                   double* block_loss, double* loss_out, hipStream_t st);
+size_t coeffs_loss_scratch_doubles(uint32_t n, uint32_t T);
+
+// Stable least-significant-digit radix sort of (keys_in[i], i) on `bits` key bits.  keys_in is
+// only read; the passes ping-pong between (k0, v0) and (k1, v1), n uint32 each, and the result is
+// in the pair returned through out_keys/out_vals.  tmp holds sort_scratch_u32(n) uint32.
+size_t sort_scratch_u32(uint32_t n);
+void launch_sort_pairs(const uint32_t* keys_in, uint32_t* k0, uint32_t* v0, uint32_t* k1,
+                       uint32_t* v1, uint32_t n, uint32_t bits, uint32_t* tmp,
+                       uint32_t** out_keys, uint32_t** out_vals, hipStream_t st);
+
+// Exclusive prefix sum of n uint32 (in place allowed); total (may be null) gets the sum.
+size_t scan_scratch_u32(uint32_t n);
+void launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* tmp,
+                           uint32_t* total, hipStream_t st);
+
+// ---- adjust ------------------------------------------------------------------------------------
+// Chunk sizes of the segmented reductions (entries per lane group).
+uint32_t useg_pairs_per_chunk(uint32_t T);
+uint32_t wseg_entries_per_chunk();
+uint32_t tail_entries_per_chunk();
+
+// Input-vector side, level 1.  Sorted pairs ps = 0..n-1 (key skey[ps] = in_idx of pair perm[ps]).
+// A lane group sums coeffs[p][j] * W[keys[p][j]] over the pairs of its chunk; a run of equal keys
+// that lies inside the chunk is written to delta[first ps of run] with dkey[ps] = key (KEY_NONE
+// elsewhere); runs cut by a chunk border go to the partial slots (pkeys/prows), two per border.
+// With `fused` the group also loads u = U[key], forms the dots, writes coefficients (and block
+// losses) and uses those coefficients.
+struct USideArgs {
+    const float* U; const float* W; RowGeom g;
+    const uint32_t* skey; const uint32_t* perm; const uint32_t* keys; uint32_t n; uint32_t T;
+    const float* coeffs_in;      // unfused: coefficients to use
+    float* coeffs_out;           // fused: coefficients written here [n][T]
+    float* dots_out;             // fused, optional: the dots themselves
+    double* pair_loss;           // fused, optional: per-pair loss [n] (by pair number)
+    float* delta; uint32_t* dkey;
+    float* prows; uint32_t* pkeys;
+    bool fused;
+};
+void launch_useg(const USideArgs& a, hipStream_t st);
+void launch_sum_pair_loss(const double* pair_loss, uint32_t n, double* loss_out, hipStream_t st);
+
+// Output-vector side, level 1.  Sorted contributions i = 0..M-1 with destination skey[i] and
+// original slot sidx[i] = p*T + j: adds alpha * sum coeffs[sidx] * U[in_idx[p]] to W[skey] for runs
+// inside a chunk; cut runs go to the partial slots.
+struct WSideArgs {
+    const float* U; float* W; RowGeom g;
+    const uint32_t* skey; const uint32_t* sidx; uint32_t M; uint32_t T;
+    const uint32_t* in_idx; const float* coeffs; float alpha;
+    float* prows; uint32_t* pkeys;
+};
+void launch_wseg(const WSideArgs& a, hipStream_t st);
+
+// Higher levels (both sides): entries are partial rows src_rows[i] with destination src_keys[i]
+// (KEY_NONE = nothing, KEY_ZERO flag = belongs to the run but empty).
+struct TailArgs {
+    float* M; RowGeom g; float alpha;
+    const float* src_rows; const uint32_t* src_keys; uint32_t entries;
+    float* prows; uint32_t* pkeys;
+};
+void launch_tail(const TailArgs& a, hipStream_t st);
+
+// U[dkey[ps]] += alpha * delta[ps] wherever dkey[ps] != KEY_NONE.
+void launch_apply_delta(float* U, RowGeom g, const float* delta, const uint32_t* dkey, uint32_t n,
+                        float alpha, hipStream_t st);
+
+// ---- pair formation ------------------------------------------------------------------------------
+struct PairArgs {
+    const uint32_t* tokens; const uint64_t* sent_off; uint32_t n_sent; uint32_t n_tokens;
+    uint64_t token_base; uint32_t epoch; uint64_t seed; uint32_t B; const uint64_t* keep; uint32_t V;
+    uint32_t* in_idx; uint32_t* out_idx; uint64_t capacity;
+    uint32_t* scratch;      // pairs_scratch_u32(n_tokens) uint32
+    uint32_t* total_pairs;  // device, one uint32
+    uint32_t* err;
+};
+size_t pairs_scratch_u32(uint32_t n_tokens);
+void launch_make_pairs(const PairArgs& a, hipStream_t st);
+
+}  // namespace w2v

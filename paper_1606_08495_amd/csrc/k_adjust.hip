@@ -1,0 +1,364 @@
+// adjust: segmented, fixed-order reduction of row contributions and the single write-back.
+//
+// After the destination keys are sorted, the contributions to one row are a run of adjacent
+// entries.  The entry list is cut into chunks of a fixed number of entries; one lane group walks one
+// chunk in order with the running sum in registers.  A run that lies inside a chunk is finished by
+// that group (one read-modify-write of the destination row).  A run cut by a chunk border leaves
+// one partial row on each side of the border ("slots" 2b and 2b+1 of border b, tagged with the
+// row); the list of slots is then reduced by the same scheme, level after level, until a level
+// fits one chunk.  Which entries meet in which partial sum depends only on the entry positions, so
+// the result is bitwise reproducible, and a row that collects millions of contributions is spread
+// over as many groups as it has chunks.
+#include "rows.h"
+
+namespace w2v {
+
+static inline unsigned blocks_for(uint64_t items, unsigned per_block) {
+    return (unsigned)((items + per_block - 1) / per_block);
+}
+
+constexpr int ADJ_THREADS = 256;
+constexpr int WSEG_C = 8;      // entries per chunk, output side level 1
+constexpr int TAIL_C = 16;     // entries per chunk, higher levels (even, so a border's two slots
+                               // fall into one chunk)
+constexpr uint32_t NOKEY = 0xFFFFFFFFu;   // compares unequal to every masked key
+
+uint32_t wseg_entries_per_chunk() { return WSEG_C; }
+uint32_t tail_entries_per_chunk() { return TAIL_C; }
+uint32_t useg_pairs_per_chunk(uint32_t T) {
+    uint32_t c = (48 + T - 1) / T;
+    return c < 2 ? 2 : c;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic chunk walker for entries that each name ONE source row.
+//   SRC = 0: output-vector side, level 1: source U[in_idx[sidx / T]], weight coeffs[sidx]
+//   SRC = 1: higher level: source src_rows[entry], weight 1 (or none when flagged empty)
+// C entries per group (C <= G), loads issued D entries at a time (source rows and, for runs that
+// finish inside the chunk, the destination rows as well).
+// ---------------------------------------------------------------------------------------------
+struct SegArgs {
+    const float4* src;          // SRC 0: U; SRC 1: partial rows of the previous level
+    float4* dst;                // matrix updated in place
+    RowGeom g;
+    const uint32_t* skey;       // destination key per entry
+    const uint32_t* sidx;       // SRC 0 only
+    const uint32_t* in_idx;     // SRC 0 only
+    const float* coeffs;        // SRC 0 only
+    uint32_t entries, T;
+    float alpha;
+    float4* prows; uint32_t* pkeys;    // this level's partial slots
+};
+
+template <int G, int NV, int C, int D, int SRC>
+__global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
+    static_assert(C <= G && C % D == 0, "chunk must fit a lane group");
+    const int l = threadIdx.x % G;
+    const uint32_t c = (blockIdx.x * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
+    const uint32_t nchunks = (a.entries + C - 1) / C;
+    if (c >= nchunks) return;
+    const uint32_t e0 = c * C;
+    const uint32_t cnt = min((uint32_t)C, a.entries - e0);
+    const uint32_t d4 = a.g.d4;
+    const uint64_t s4 = a.g.stride4;
+
+    // ---- per-entry facts, entry e0+l in lane l ----
+    const bool valid = (uint32_t)l < cnt;
+    uint32_t key = NOKEY, srow = 0;
+    float coef = 1.0f;
+    int has = 0;
+    if (valid) {
+        uint32_t raw = a.skey[e0 + l];
+        if (SRC == 0) {
+            key = raw;
+            uint32_t q = a.sidx[e0 + l];
+            srow = a.in_idx[q / a.T];          // range-checked copy
+            coef = a.coeffs[q];
+            has = 1;
+        } else {
+            key = raw & KEY_MASK;
+            srow = e0 + l;
+            has = (raw != KEY_NONE) && !(raw & KEY_ZERO);
+        }
+    }
+    const uint32_t real_limit = (SRC == 0) ? NOKEY : KEY_MASK;   // keys >= this name no row
+    uint32_t key_prev = NOKEY, key_after = NOKEY;
+    if (e0 > 0) { uint32_t r = a.skey[e0 - 1]; key_prev = (SRC == 0) ? r : (r & KEY_MASK); }
+    if (e0 + cnt < a.entries) { uint32_t r = a.skey[e0 + cnt]; key_after = (SRC == 0) ? r : (r & KEY_MASK); }
+    uint32_t next = __shfl(key, l + 1, G);
+    if ((uint32_t)l + 1 >= cnt) next = key_after;
+    const uint32_t key0 = __shfl(key, 0, G);
+    const bool open_head = (key_prev == key0);
+    const int ends = valid && (next != key);
+    const int in_head = open_head && (key == key0);
+    const int real = key < real_limit;
+    const int complete = ends && !in_head && real;
+
+    float4 acc[NV];
+    clear<NV>(acc);
+    uint32_t head_key = KEY_NONE, tail_key = KEY_NONE;
+    const uint32_t head_slot = 2 * c - 1, tail_slot = 2 * c;   // used only when they exist
+
+#pragma unroll
+    for (int b = 0; b < C; b += D) {
+        float4 srcv[D][NV], dstv[D][NV];
+#pragma unroll
+        for (int t = 0; t < D; ++t) {
+            const int e = b + t;
+            uint32_t sr = __shfl(srow, e, G);
+            int h = __shfl(has, e, G);
+            int cm = __shfl(complete, e, G);
+            uint32_t dk = __shfl(key, e, G);
+            load_row_if<G, NV>(h != 0, a.src + (uint64_t)sr * s4, d4, l, srcv[t]);
+            load_row_if<G, NV>(cm != 0, a.dst + (uint64_t)(cm ? dk : 0u) * s4, d4, l, dstv[t]);
+        }
+#pragma unroll
+        for (int t = 0; t < D; ++t) {
+            const int e = b + t;
+            float cf = __shfl(coef, e, G);
+            int h = __shfl(has, e, G);
+            int en = __shfl(ends, e, G);
+            int cm = __shfl(complete, e, G);
+            int ih = __shfl(in_head, e, G);
+            int rl = __shfl(real, e, G);
+            uint32_t dk = __shfl(key, e, G);
+            if (h) axpy<NV>(cf, srcv[t], acc);
+            if (en) {
+                if (cm) {
+                    float4 out[NV];
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) {
+                        out[v].x = fmaf(a.alpha, acc[v].x, dstv[t][v].x);
+                        out[v].y = fmaf(a.alpha, acc[v].y, dstv[t][v].y);
+                        out[v].z = fmaf(a.alpha, acc[v].z, dstv[t][v].z);
+                        out[v].w = fmaf(a.alpha, acc[v].w, dstv[t][v].w);
+                    }
+                    store_row<G, NV>(a.dst + (uint64_t)dk * s4, d4, l, out);
+                } else if (ih && rl) {      // the run came in from the previous chunk and ends here
+                    store_row<G, NV>(a.prows + (uint64_t)head_slot * s4, d4, l, acc);
+                    head_key = dk;
+                }
+                clear<NV>(acc);
+            }
+        }
+    }
+    // ---- the last run may go on into the next chunk ----
+    {
+        const int last = (int)cnt - 1;
+        int en = __shfl(ends, last, G);
+        int ih = __shfl(in_head, last, G);
+        int rl = __shfl(real, last, G);
+        uint32_t dk = __shfl(key, last, G);
+        if (!en && rl) {
+            if (ih) {               // one run covers the whole chunk: one partial, in the head slot
+                store_row<G, NV>(a.prows + (uint64_t)head_slot * s4, d4, l, acc);
+                head_key = dk;
+                tail_key = dk | KEY_ZERO;
+            } else {
+                store_row<G, NV>(a.prows + (uint64_t)tail_slot * s4, d4, l, acc);
+                tail_key = dk;
+            }
+        }
+    }
+    if (l == 0) {
+        if (c > 0) a.pkeys[head_slot] = head_key;
+        if (c + 1 < nchunks) a.pkeys[tail_slot] = tail_key;
+    }
+}
+
+void launch_wseg(const WSideArgs& w, hipStream_t st) {
+    if (w.M == 0) return;
+    SegArgs a;
+    a.src = (const float4*)w.U; a.dst = (float4*)w.W; a.g = w.g; a.skey = w.skey; a.sidx = w.sidx;
+    a.in_idx = w.in_idx; a.coeffs = w.coeffs; a.entries = w.M; a.T = w.T;
+    a.alpha = w.alpha; a.prows = (float4*)w.prows; a.pkeys = w.pkeys;
+    uint32_t nchunks = (w.M + WSEG_C - 1) / WSEG_C;
+#define CALL(G, NV)                                                                              \
+    hipLaunchKernelGGL((seg_kernel<G, NV, WSEG_C, (NV <= 2 ? 4 : 2), 0>),                        \
+                       dim3(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)), dim3(ADJ_THREADS), 0, \
+                       st, a)
+    W2V_DISPATCH_GEOM(w.g.d4, CALL);
+#undef CALL
+}
+
+void launch_tail(const TailArgs& t, hipStream_t st) {
+    if (t.entries == 0) return;
+    SegArgs a;
+    a.src = (const float4*)t.src_rows; a.dst = (float4*)t.M; a.g = t.g; a.skey = t.src_keys;
+    a.sidx = nullptr; a.in_idx = nullptr; a.coeffs = nullptr; a.entries = t.entries; a.T = 1;
+    a.alpha = t.alpha; a.prows = (float4*)t.prows; a.pkeys = t.pkeys;
+    uint32_t nchunks = (t.entries + TAIL_C - 1) / TAIL_C;
+#define CALL(G, NV)                                                                              \
+    hipLaunchKernelGGL((seg_kernel<G, NV, TAIL_C, (NV <= 2 ? 4 : 2), 1>),                        \
+                       dim3(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)), dim3(ADJ_THREADS), 0, \
+                       st, a)
+    W2V_DISPATCH_GEOM(t.g.d4, CALL);
+#undef CALL
+}
+
+// ---------------------------------------------------------------------------------------------
+// Input-vector side, level 1: entries are whole pairs (T source rows each) in the order of the
+// sorted input words.  Runs finished inside a chunk go to the delta buffer (the input matrix must
+// stay untouched until the output side has read it); cut runs go to the partial slots.
+// FUSED: the group also holds u, forms the T dots of the pair, turns them into coefficients
+// (written out for the output side) and uses them at once -- the output rows are read only once.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float softplus_f(float x) {
+    return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
+}
+
+template <int G, int NV, int TB, bool FUSED>
+__global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t CP) {
+    const int l = threadIdx.x % G;
+    const uint32_t c = (blockIdx.x * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
+    const uint32_t nchunks = (a.n + CP - 1) / CP;
+    if (c >= nchunks) return;
+    const uint32_t ps0 = c * CP;
+    const uint32_t ps1 = min(a.n, ps0 + CP);
+    const uint32_t d4 = a.g.d4;
+    const uint64_t s4 = a.g.stride4;
+    const float4* U4p = (const float4*)a.U;
+    const float4* W4p = (const float4*)a.W;
+    float4* delta = (float4*)a.delta;
+    float4* prows = (float4*)a.prows;
+    const uint32_t T = a.T;
+
+    const uint32_t key_prev = ps0 > 0 ? a.skey[ps0 - 1] : NOKEY;
+    const uint32_t key_after = ps1 < a.n ? a.skey[ps1] : NOKEY;
+    uint32_t key = a.skey[ps0];
+    const bool open_head = (key_prev == key);
+    uint32_t run_start = ps0;
+    uint32_t head_key = KEY_NONE, tail_key = KEY_NONE;
+    const uint32_t head_slot = 2 * c - 1, tail_slot = 2 * c;
+
+    float4 acc[NV];
+    clear<NV>(acc);
+    for (uint32_t ps = ps0; ps < ps1; ++ps) {
+        const uint32_t p = a.perm[ps];
+        const uint32_t next = (ps + 1 < ps1) ? a.skey[ps + 1] : key_after;
+        if (l == 0) a.dkey[ps] = KEY_NONE;
+        float4 u[NV];
+        if (FUSED) load_row<G, NV>(U4p + (uint64_t)key * s4, d4, l, u);
+        double pair_loss = 0.0;
+        for (uint32_t jb = 0; jb < T; jb += TB) {
+            float4 w[TB][NV];
+            float gco[TB];
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                uint32_t j = jb + t;
+                bool on = j < T;
+                uint32_t r = on ? a.keys[p * T + j] : 0u;
+                load_row_if<G, NV>(on, W4p + (uint64_t)r * s4, d4, l, w[t]);
+                if (!FUSED) gco[t] = on ? a.coeffs_in[p * T + j] : 0.f;
+            }
+            if (FUSED) {
+                float s[TB];
+#pragma unroll
+                for (int t = 0; t < TB; ++t) s[t] = dot_part<NV>(u, w[t]);
+#pragma unroll
+                for (int t = 0; t < TB; ++t) s[t] = group_sum<G>(s[t]);
+#pragma unroll
+                for (int t = 0; t < TB; ++t) {
+                    uint32_t j = jb + t;
+                    float f = s[t];
+                    float gc;
+                    if (j == 0) gc = 1.0f / (1.0f + expf(f));
+                    else        gc = -1.0f / (1.0f + expf(-f));
+                    gco[t] = (j < T) ? gc : 0.f;
+                    if (a.pair_loss && j < T) pair_loss += (double)softplus_f(j == 0 ? -f : f);
+                    if (l == t && j < T) {
+                        a.coeffs_out[p * T + j] = gc;
+                        if (a.dots_out) a.dots_out[p * T + j] = f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+                if (jb + t < T) axpy<NV>(gco[t], w[t], acc);
+        }
+        if (FUSED && a.pair_loss && l == 0) a.pair_loss[p] = pair_loss;
+        if (next != key) {                       // the run of `key` ends with this pair
+            if (run_start == ps0 && open_head) {
+                store_row<G, NV>(prows + (uint64_t)head_slot * s4, d4, l, acc);
+                head_key = key;
+            } else {
+                store_row<G, NV>(delta + (uint64_t)run_start * s4, d4, l, acc);
+                if (l == 0) a.dkey[run_start] = key;
+            }
+            clear<NV>(acc);
+            run_start = ps + 1;
+        }
+        key = next;
+    }
+    if (run_start < ps1) {                       // the last run goes on into the next chunk
+        const uint32_t k_last = a.skey[ps1 - 1];
+        if (run_start == ps0 && open_head) {
+            store_row<G, NV>(prows + (uint64_t)head_slot * s4, d4, l, acc);
+            head_key = k_last;
+            tail_key = k_last | KEY_ZERO;
+        } else {
+            store_row<G, NV>(prows + (uint64_t)tail_slot * s4, d4, l, acc);
+            tail_key = k_last;
+        }
+    }
+    if (l == 0) {
+        if (c > 0) a.pkeys[head_slot] = head_key;
+        if (c + 1 < nchunks) a.pkeys[tail_slot] = tail_key;
+    }
+}
+
+void launch_useg(const USideArgs& a, hipStream_t st) {
+    if (a.n == 0) return;
+    uint32_t CP = useg_pairs_per_chunk(a.T);
+    uint32_t nchunks = (a.n + CP - 1) / CP;
+#define CALL(G, NV)                                                                               \
+    do {                                                                                          \
+        dim3 grid(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)), block(ADJ_THREADS);            \
+        if (a.fused)                                                                              \
+            hipLaunchKernelGGL((useg_kernel<G, NV, (NV <= 2 ? 6 : 4), true>), grid, block, 0, st, \
+                               a, CP);                                                            \
+        else                                                                                      \
+            hipLaunchKernelGGL((useg_kernel<G, NV, (NV <= 2 ? 6 : 4), false>), grid, block, 0,    \
+                               st, a, CP);                                                        \
+    } while (0)
+    W2V_DISPATCH_GEOM(a.g.d4, CALL);
+#undef CALL
+}
+
+// ---------------------------------------------------------------------------------------------
+// Write-back of the input-vector changes held in the delta buffer.
+// ---------------------------------------------------------------------------------------------
+template <int G, int NV>
+__global__ __launch_bounds__(ADJ_THREADS) void apply_delta_kernel(float4* __restrict__ U, RowGeom g,
+                                                                  const float4* __restrict__ delta,
+                                                                  const uint32_t* __restrict__ dkey,
+                                                                  uint32_t n, float alpha) {
+    const int l = threadIdx.x % G;
+    const uint32_t ps = (blockIdx.x * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
+    if (ps >= n) return;
+    const uint32_t key = dkey[ps];
+    if (key == KEY_NONE) return;
+    float4 dv[NV], uv[NV];
+    load_row<G, NV>(delta + (uint64_t)ps * g.stride4, g.d4, l, dv);
+    load_row<G, NV>(U + (uint64_t)key * g.stride4, g.d4, l, uv);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        uv[v].x = fmaf(alpha, dv[v].x, uv[v].x);
+        uv[v].y = fmaf(alpha, dv[v].y, uv[v].y);
+        uv[v].z = fmaf(alpha, dv[v].z, uv[v].z);
+        uv[v].w = fmaf(alpha, dv[v].w, uv[v].w);
+    }
+    store_row<G, NV>(U + (uint64_t)key * g.stride4, g.d4, l, uv);
+}
+
+void launch_apply_delta(float* U, RowGeom g, const float* delta, const uint32_t* dkey, uint32_t n,
+                        float alpha, hipStream_t st) {
+    if (n == 0) return;
+#define CALL(G, NV)                                                                              \
+    hipLaunchKernelGGL((apply_delta_kernel<G, NV>), dim3(blocks_for((uint64_t)n * G, ADJ_THREADS)), \
+                       dim3(ADJ_THREADS), 0, st, (float4*)U, g, (const float4*)delta, dkey, n, alpha)
+    W2V_DISPATCH_GEOM(g.d4, CALL);
+#undef CALL
+}
+
+}  // namespace w2v

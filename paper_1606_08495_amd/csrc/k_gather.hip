@@ -1,0 +1,288 @@
+// Initial values, row get/set, negative sampling (destination keys), gather dot products and the
+// client's coefficient step.  gfx950, wave64.
+#include "rows.h"
+
+namespace w2v {
+
+static inline unsigned blocks_for(uint64_t items, unsigned per_block) {
+    return (unsigned)((items + per_block - 1) / per_block);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Initial vectors: component (word w, global column c) of matrix m is
+//   ((R >> 8) * 2^-24 - 0.5) / d_total,  R = word (c mod 4) of Philox(counter = (w, c/4, m, INIT)).
+// One thread per float4 of a row; columns past d_slice inside the stride stay zero.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void init_kernel(float4* __restrict__ M, uint32_t V, RowGeom g,
+                                                   uint32_t d_slice, float d_total,
+                                                   uint32_t col_begin, uint32_t k0, uint32_t k1,
+                                                   uint32_t matrix, int zero) {
+    uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    uint64_t total = (uint64_t)V * g.stride4;
+    if (i >= total) return;
+    uint32_t w = (uint32_t)(i / g.stride4);
+    uint32_t q = (uint32_t)(i % g.stride4);
+    float vals[4] = {0.f, 0.f, 0.f, 0.f};
+    if (!zero) {
+        uint32_t have_block = 0xFFFFFFFFu;
+        U4 r{0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint32_t local = q * 4 + e;
+            if (local < d_slice) {
+                uint32_t c = col_begin + local;
+                if ((c >> 2) != have_block) {
+                    have_block = c >> 2;
+                    r = philox4x32_10(w, have_block, matrix, DOM_INIT, k0, k1);
+                }
+                uint32_t lane = c & 3u;
+                uint32_t bits = lane == 0 ? r.x : lane == 1 ? r.y : lane == 2 ? r.z : r.w;
+                float x = (float)(bits >> 8) * (1.0f / 16777216.0f) - 0.5f;
+                vals[e] = x / d_total;
+            }
+        }
+    }
+    M[i] = make_float4(vals[0], vals[1], vals[2], vals[3]);
+}
+
+void launch_init(float* M, uint32_t V, RowGeom g, uint32_t d_slice, uint32_t d_total,
+                 uint32_t col_begin, uint64_t seed, uint32_t matrix, bool zero, hipStream_t st) {
+    uint64_t total = (uint64_t)V * g.stride4;
+    hipLaunchKernelGGL(init_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, st, (float4*)M, V,
+                       g, d_slice, (float)d_total, col_begin, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), matrix, zero ? 1 : 0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// get / set of listed rows, dense [m][d_slice] on the caller's side.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ M,
+                                                          uint32_t stride, uint32_t d_slice,
+                                                          const uint32_t* __restrict__ rows,
+                                                          uint32_t m, uint32_t V,
+                                                          float* __restrict__ dst,
+                                                          uint32_t* err) {
+    uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (uint64_t)m * d_slice) return;
+    uint32_t r = (uint32_t)(i / d_slice), c = (uint32_t)(i % d_slice);
+    uint32_t w = rows[r];
+    if (w >= V) { if (c == 0) atomicOr(err, 1u); w = 0; }
+    dst[i] = M[(uint64_t)w * stride + c];
+}
+
+__global__ __launch_bounds__(256) void scatter_rows_kernel(float* __restrict__ M, uint32_t stride,
+                                                           uint32_t d_slice,
+                                                           const uint32_t* __restrict__ rows,
+                                                           uint32_t m, uint32_t V,
+                                                           const float* __restrict__ src,
+                                                           uint32_t* err) {
+    uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (uint64_t)m * d_slice) return;
+    uint32_t r = (uint32_t)(i / d_slice), c = (uint32_t)(i % d_slice);
+    uint32_t w = rows[r];
+    if (w >= V) { if (c == 0) atomicOr(err, 1u); return; }
+    M[(uint64_t)w * stride + c] = src[i];
+}
+
+void launch_gather_rows(const float* M, RowGeom g, uint32_t d_slice, const uint32_t* rows,
+                        uint32_t m, uint32_t V, float* dst, uint32_t* err, hipStream_t st) {
+    if (m == 0) return;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks_for((uint64_t)m * d_slice, 256)), dim3(256),
+                       0, st, M, g.stride4 * 4, d_slice, rows, m, V, dst, err);
+}
+
+void launch_scatter_rows(float* M, RowGeom g, uint32_t d_slice, const uint32_t* rows, uint32_t m,
+                         uint32_t V, const float* src, uint32_t* err, hipStream_t st) {
+    if (m == 0) return;
+    hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks_for((uint64_t)m * d_slice, 256)), dim3(256),
+                       0, st, M, g.stride4 * 4, d_slice, rows, m, V, src, err);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Destination keys: slot 0 of pair p is its positive output word, slot j >= 1 its j-th negative.
+// A negative is the first alias-table candidate (attempt t = 0..15, Philox counter (p, j, t, NEG))
+// that differs from the positive word; after 16 rejections it is the next word index, cyclically.
+// One thread per slot, so the generator runs with all 64 lanes busy.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dest_keys_kernel(const uint2* __restrict__ bins, uint32_t V,
+                                                        const uint32_t* __restrict__ in_idx,
+                                                        const uint32_t* __restrict__ out_idx,
+                                                        uint32_t n, uint32_t T, uint32_t k0,
+                                                        uint32_t k1, uint32_t* __restrict__ keys,
+                                                        uint32_t* __restrict__ in_safe,
+                                                        uint32_t* err) {
+    uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n * T) return;
+    uint32_t p = i / T, j = i - p * T;
+    uint32_t wo = out_idx[p];
+    if (wo >= V) { wo = 0; if (j == 0) atomicOr(err, 1u); }
+    uint32_t key;
+    if (j == 0) {
+        uint32_t wi = in_idx[p];
+        if (wi >= V) { atomicOr(err, 1u); wi = 0; }
+        in_safe[p] = wi;
+        key = wo;
+    } else {
+        key = wo + 1 == V ? 0u : wo + 1;           // the fallback
+        for (uint32_t t = 0; t < 16; ++t) {
+            U4 r = philox4x32_10(p, j, t, DOM_NEG, k0, k1);
+            uint64_t r64 = ((uint64_t)r.y << 32) | (uint64_t)r.x;
+            uint32_t bin = (uint32_t)__umul64hi(r64, (uint64_t)V);
+            uint2 b = bins[bin];
+            uint32_t cand = (r.z < b.x) ? bin : b.y;
+            if (cand != wo) { key = cand; break; }
+        }
+    }
+    keys[i] = key;
+}
+
+void launch_dest_keys(NoiseTable nt, const uint32_t* in_idx, const uint32_t* out_idx, uint32_t n,
+                      uint32_t k, uint64_t seed, uint32_t* keys, uint32_t* in_safe, uint32_t* err,
+                      hipStream_t st) {
+    if (n == 0) return;
+    uint32_t T = k + 1;
+    hipLaunchKernelGGL(dest_keys_kernel, dim3(blocks_for((uint64_t)n * T, 256)), dim3(256), 0, st,
+                       nt.bins, nt.V, in_idx, out_idx, n, T, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), keys, in_safe, err);
+}
+
+__global__ __launch_bounds__(256) void copy_negatives_kernel(const uint32_t* __restrict__ keys,
+                                                             uint32_t n, uint32_t k,
+                                                             uint32_t* __restrict__ neg) {
+    uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n * k) return;
+    uint32_t p = i / k, j = i - p * k;
+    neg[i] = keys[p * (k + 1) + 1 + j];
+}
+
+void launch_copy_negatives(const uint32_t* keys, uint32_t n, uint32_t k, uint32_t* neg,
+                           hipStream_t st) {
+    if (n == 0 || k == 0) return;
+    hipLaunchKernelGGL(copy_negatives_kernel, dim3(blocks_for((uint64_t)n * k, 256)), dim3(256), 0,
+                       st, keys, n, k, neg);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gather dot products: one lane group per pair.  The group loads u once, then the T output rows in
+// batches of TB with every load of a batch issued before the first multiply.
+// ---------------------------------------------------------------------------------------------
+template <int G, int NV, int TB>
+__global__ __launch_bounds__(256) void dots_kernel(const float4* __restrict__ U,
+                                                   const float4* __restrict__ W, RowGeom g,
+                                                   const uint32_t* __restrict__ in_idx,
+                                                   const uint32_t* __restrict__ keys, uint32_t n,
+                                                   uint32_t T, float* __restrict__ dots) {
+    const int l = threadIdx.x % G;
+    uint32_t grp = (blockIdx.x * 256u + threadIdx.x) / G;
+    const bool live = grp < n;
+    const uint32_t p = live ? grp : n - 1;
+    const uint32_t wi = in_idx[p];          // already range-checked (launch_dest_keys)
+    float4 u[NV];
+    load_row<G, NV>(U + (uint64_t)wi * g.stride4, g.d4, l, u);
+    for (uint32_t jb = 0; jb < T; jb += TB) {
+        float4 w[TB][NV];
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            uint32_t j = jb + t;
+            bool on = j < T;
+            uint32_t r = on ? keys[p * T + j] : 0u;
+            load_row_if<G, NV>(on, W + (uint64_t)r * g.stride4, g.d4, l, w[t]);
+        }
+        float s[TB];
+#pragma unroll
+        for (int t = 0; t < TB; ++t) s[t] = dot_part<NV>(u, w[t]);
+#pragma unroll
+        for (int t = 0; t < TB; ++t) s[t] = group_sum<G>(s[t]);
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+            if (l == t && live && jb + t < T) dots[p * T + jb + t] = s[t];
+    }
+}
+
+void launch_dots(const float* U, const float* W, RowGeom g, const uint32_t* in_idx,
+                 const uint32_t* keys, uint32_t n, uint32_t T, float* dots, hipStream_t st) {
+    if (n == 0) return;
+#define CALL(G, NV)                                                                               \
+    hipLaunchKernelGGL((dots_kernel<G, NV, (NV <= 2 ? 6 : 4)>),                                   \
+                       dim3(blocks_for((uint64_t)n * G, 256)), dim3(256), 0, st, (const float4*)U, \
+                       (const float4*)W, g, in_idx, keys, n, T, dots)
+    W2V_DISPATCH_GEOM(g.d4, CALL);
+#undef CALL
+}
+
+// ---------------------------------------------------------------------------------------------
+// Client step between the two calls: f = sum over shards of the partial dots (shard order), then
+// the coefficient label - sigma(f), written as sigma(-f) for the positive slot so that it keeps
+// its relative accuracy when f is large.  Loss terms are softplus(-f) / softplus(f), summed per
+// block in double by a fixed tree, then over blocks in index order by one thread.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float softplus(float x) {
+    return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
+}
+
+__global__ __launch_bounds__(256) void coeffs_kernel(PartialPtrs parts, uint32_t S, uint32_t total,
+                                                     uint32_t T, float* __restrict__ coeffs,
+                                                     double* __restrict__ block_loss) {
+    __shared__ double red[256];
+    uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    double term = 0.0;
+    if (i < total) {
+        float f = 0.f;
+        for (uint32_t s = 0; s < S; ++s) f += parts.p[s][i];
+        uint32_t j = i % T;
+        float gcoef;
+        if (j == 0) { gcoef = 1.0f / (1.0f + expf(f)); term = (double)softplus(-f); }
+        else        { gcoef = -1.0f / (1.0f + expf(-f)); term = (double)softplus(f); }
+        coeffs[i] = gcoef;
+    }
+    if (block_loss) {
+        red[threadIdx.x] = term;
+        __syncthreads();
+        for (int s = 128; s >= 1; s >>= 1) {
+            if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) block_loss[blockIdx.x] = red[0];
+    }
+}
+
+__global__ void sum_doubles_kernel(const double* __restrict__ x, uint32_t n,
+                                   double* __restrict__ out) {
+    // One block of 256 threads: thread t sums x[t], x[t+256], ... in order; then a fixed tree.
+    __shared__ double red[256];
+    double s = 0.0;
+    for (uint32_t i = threadIdx.x; i < n; i += 256) s += x[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int h = 128; h >= 1; h >>= 1) {
+        if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = red[0];
+}
+
+size_t coeffs_loss_scratch_doubles(uint32_t n, uint32_t T) {
+    return blocks_for((uint64_t)n * T, 256);
+}
+
+void launch_coeffs(PartialPtrs parts, uint32_t S, uint32_t n, uint32_t T, float* coeffs,
+                   double* block_loss, double* loss_out, hipStream_t st) {
+    uint32_t total = n * T;
+    if (total == 0) {
+        if (loss_out) hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st,
+                                         (const double*)nullptr, 0u, loss_out);
+        return;
+    }
+    unsigned nb = blocks_for(total, 256);
+    hipLaunchKernelGGL(coeffs_kernel, dim3(nb), dim3(256), 0, st, parts, S, total, T, coeffs,
+                       loss_out ? block_loss : (double*)nullptr);
+    if (loss_out)
+        hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st,
+                           (const double*)block_loss, nb, loss_out);
+}
+
+void launch_sum_pair_loss(const double* pair_loss, uint32_t n, double* loss_out, hipStream_t st) {
+    hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st, pair_loss, n, loss_out);
+}
+
+}  // namespace w2v

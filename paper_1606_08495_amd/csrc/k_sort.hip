@@ -1,0 +1,240 @@
+// Device-wide exclusive scan and a stable least-significant-digit radix sort of (key, value)
+// pairs, 8 bits per pass.  Used to group the contributions of adjust by destination row: equal
+// keys end up adjacent and, the sort being stable, in increasing order of their original slot, so
+// the order in which a row's contributions are summed is fixed by the input alone.
+#include "common.h"
+
+namespace w2v {
+
+static inline unsigned blocks_for(uint64_t items, unsigned per_block) {
+    return (unsigned)((items + per_block - 1) / per_block);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scan.  Blocks of 256 threads x 8 items: (1) per-block sums, (2) one block scans the sums with a
+// running carry, (3) per-block local scan plus the block's offset.
+// ---------------------------------------------------------------------------------------------
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_ITEMS = 8;
+constexpr int SCAN_TILE = SCAN_THREADS * SCAN_ITEMS;
+
+// Exclusive scan of one value per thread across a 256-thread block; returns the exclusive prefix
+// and leaves the block total in *total_out (shared).
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t* wave_sums,
+                                                         uint32_t* total_out) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = x;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t y = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += y;
+    }
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0;
+#pragma unroll
+    for (int w = 0; w < SCAN_THREADS / 64; ++w) {
+        uint32_t s = wave_sums[w];
+        if (w < wave) base += s;
+    }
+    if (threadIdx.x == SCAN_THREADS - 1) *total_out = base + incl;
+    __syncthreads();
+    return base + incl - x;
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void scan_block_sums_kernel(
+    const uint32_t* __restrict__ in, uint32_t n, uint32_t* __restrict__ sums) {
+    __shared__ uint32_t wave_sums[4];
+    __shared__ uint32_t total;
+    uint64_t base = (uint64_t)blockIdx.x * SCAN_TILE + (uint64_t)threadIdx.x * SCAN_ITEMS;
+    uint32_t s = 0;
+#pragma unroll
+    for (int e = 0; e < SCAN_ITEMS; ++e)
+        if (base + e < n) s += in[base + e];
+    block_exclusive_scan(s, wave_sums, &total);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void scan_sums_kernel(uint32_t* __restrict__ sums,
+                                                                 uint32_t nb,
+                                                                 uint32_t* __restrict__ total_out) {
+    __shared__ uint32_t wave_sums[4];
+    __shared__ uint32_t total;
+    uint32_t carry = 0;
+    for (uint32_t start = 0; start < nb; start += SCAN_THREADS) {
+        uint32_t i = start + threadIdx.x;
+        uint32_t x = i < nb ? sums[i] : 0u;
+        uint32_t ex = block_exclusive_scan(x, wave_sums, &total);
+        if (i < nb) sums[i] = carry + ex;
+        carry += total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && total_out) *total_out = carry;
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void scan_apply_kernel(const uint32_t* __restrict__ in,
+                                                                  uint32_t* __restrict__ out,
+                                                                  uint32_t n,
+                                                                  const uint32_t* __restrict__ sums) {
+    __shared__ uint32_t wave_sums[4];
+    __shared__ uint32_t total;
+    uint64_t base = (uint64_t)blockIdx.x * SCAN_TILE + (uint64_t)threadIdx.x * SCAN_ITEMS;
+    uint32_t v[SCAN_ITEMS];
+    uint32_t s = 0;
+#pragma unroll
+    for (int e = 0; e < SCAN_ITEMS; ++e) {
+        v[e] = (base + e < n) ? in[base + e] : 0u;
+        s += v[e];
+    }
+    uint32_t run = block_exclusive_scan(s, wave_sums, &total) + sums[blockIdx.x];
+#pragma unroll
+    for (int e = 0; e < SCAN_ITEMS; ++e) {
+        if (base + e < n) out[base + e] = run;
+        run += v[e];
+    }
+}
+
+size_t scan_scratch_u32(uint32_t n) { return blocks_for(n, SCAN_TILE) + 1; }
+
+void launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* tmp,
+                           uint32_t* total, hipStream_t st) {
+    unsigned nb = blocks_for(n, SCAN_TILE);
+    if (n == 0) {
+        hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(SCAN_THREADS), 0, st, tmp, 0u, total);
+        return;
+    }
+    hipLaunchKernelGGL(scan_block_sums_kernel, dim3(nb), dim3(SCAN_THREADS), 0, st, in, n, tmp);
+    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(SCAN_THREADS), 0, st, tmp, nb, total);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3(nb), dim3(SCAN_THREADS), 0, st, in, out, n, tmp);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Radix sort pass.  A block owns a tile of 256 x 8 consecutive elements; wave w of the block owns
+// the w-th quarter of the tile and walks it in order, 64 elements at a time.
+//   histogram : per-block digit counts, stored digit-major [256][blocks]
+//   (scan of that array gives, for every (digit, block), where the block's elements of that digit
+//    start in the output)
+//   scatter   : each element's position = that start + its rank among the block's elements with
+//               the same digit, counted in tile order -> stable.
+// ---------------------------------------------------------------------------------------------
+constexpr int SORT_THREADS = 256;
+constexpr int SORT_ITEMS = 8;
+constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
+constexpr int SORT_WAVES = SORT_THREADS / 64;
+constexpr int SORT_WAVE_SPAN = 64 * SORT_ITEMS;
+
+__global__ __launch_bounds__(SORT_THREADS) void sort_hist_kernel(const uint32_t* __restrict__ keys,
+                                                                 uint32_t n, uint32_t shift,
+                                                                 uint32_t nblocks,
+                                                                 uint32_t* __restrict__ hist) {
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    uint64_t base = (uint64_t)blockIdx.x * SORT_TILE;
+#pragma unroll
+    for (int e = 0; e < SORT_ITEMS; ++e) {
+        uint64_t i = base + (uint64_t)e * SORT_THREADS + threadIdx.x;
+        if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[(uint64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
+}
+
+__global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
+    const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
+    uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, uint32_t n, uint32_t shift,
+    uint32_t nblocks, const uint32_t* __restrict__ offsets) {
+    __shared__ uint32_t cnt[SORT_WAVES][256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int w = 0; w < SORT_WAVES; ++w) cnt[w][threadIdx.x] = 0;
+    __syncthreads();
+
+    uint64_t base = (uint64_t)blockIdx.x * SORT_TILE + (uint64_t)wave * SORT_WAVE_SPAN;
+    uint32_t key[SORT_ITEMS], val[SORT_ITEMS], rank[SORT_ITEMS];
+    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+    for (int e = 0; e < SORT_ITEMS; ++e) {
+        uint64_t i = base + (uint64_t)e * 64 + lane;
+        bool valid = i < n;
+        key[e] = valid ? keys_in[i] : 0u;
+        val[e] = valid ? (vals_in ? vals_in[i] : (uint32_t)i) : 0u;
+        uint32_t d = (key[e] >> shift) & 255u;
+        // lanes of this wave holding the same digit
+        uint64_t same = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            uint64_t bal = __ballot((d >> b) & 1u);
+            same &= ((d >> b) & 1u) ? bal : ~bal;
+        }
+        uint32_t before = 0;
+        if (valid) {
+            before = cnt[wave][d];
+            rank[e] = before + (uint32_t)__popcll(same & below);
+        } else {
+            rank[e] = 0;
+        }
+        // The reads above are issued before the write below by every lane of the wave (one
+        // instruction stream), so the leader's update cannot be seen by this step's readers.
+        if (valid && (same & below) == 0) cnt[wave][d] = before + (uint32_t)__popcll(same);
+    }
+    __syncthreads();
+    {   // thread t owns digit t: turn per-wave counts into per-wave starts in the output
+        uint32_t d = threadIdx.x;
+        uint32_t run = offsets[(uint64_t)d * nblocks + blockIdx.x];
+#pragma unroll
+        for (int w = 0; w < SORT_WAVES; ++w) {
+            uint32_t c = cnt[w][d];
+            cnt[w][d] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < SORT_ITEMS; ++e) {
+        uint64_t i = base + (uint64_t)e * 64 + lane;
+        if (i < n) {
+            uint32_t d = (key[e] >> shift) & 255u;
+            uint32_t pos = cnt[wave][d] + rank[e];
+            keys_out[pos] = key[e];
+            vals_out[pos] = val[e];
+        }
+    }
+}
+
+size_t sort_scratch_u32(uint32_t n) {
+    uint32_t nblocks = blocks_for(n, SORT_TILE);
+    uint32_t hist = 256u * (nblocks ? nblocks : 1u);
+    return (size_t)hist + scan_scratch_u32(hist) + 8;
+}
+
+void launch_sort_pairs(const uint32_t* keys_in, uint32_t* k0, uint32_t* v0, uint32_t* k1, uint32_t* v1,
+                       uint32_t n, uint32_t bits, uint32_t* tmp, uint32_t** out_keys,
+                       uint32_t** out_vals, hipStream_t st) {
+    if (bits == 0) bits = 1;
+    uint32_t passes = (bits + 7) / 8;
+    uint32_t nblocks = blocks_for(n, SORT_TILE);
+    uint32_t hist_len = 256u * nblocks;
+    uint32_t* hist = tmp;
+    uint32_t* scan_tmp = tmp + hist_len;
+    *out_keys = k0;
+    *out_vals = v0;
+    if (n == 0) return;
+    const uint32_t* kin = keys_in;
+    const uint32_t* vin = nullptr;           // first pass: value i = i
+    uint32_t *kout = k0, *vout = v0;
+    for (uint32_t ps = 0; ps < passes; ++ps) {
+        uint32_t shift = ps * 8;
+        hipLaunchKernelGGL(sort_hist_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, st, kin, n,
+                           shift, nblocks, hist);
+        launch_exclusive_scan(hist, hist, hist_len, scan_tmp, nullptr, st);
+        hipLaunchKernelGGL(sort_scatter_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, st, kin, vin,
+                           kout, vout, n, shift, nblocks, hist);
+        *out_keys = kout;
+        *out_vals = vout;
+        kin = kout; vin = vout;
+        if (kout == k0) { kout = k1; vout = v1; } else { kout = k0; vout = v0; }
+    }
+}
+
+}  // namespace w2v

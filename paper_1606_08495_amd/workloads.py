@@ -7,7 +7,7 @@ sessions of a few tens of tokens).  It holds none of the method's arithmetic: no
 sampling, no subsampling, no windows, no dot products.  The GPU library and the CPU oracle are
 both driven from the arrays made here.
 
-Word id == frequency rank (Section 4.1: the vocabulary is ordered by decreasing frequency).
+Word id == frequency rank (Section 5.1: the vocabulary is ordered by decreasing frequency).
 """
 from dataclasses import dataclass
 

@@ -1,0 +1,69 @@
+"""CPU-side checks of the boundary: the built library loads, exports every function the header
+declares, and its host-only entry points behave (no kernels are launched here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+
+import oracle
+from paper_1606_08495_amd import w2v, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "w2v_shard.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(w2v_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert len(names) >= 17
+    L = ctypes.CDLL(w2v.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    assert names == w2v.EXPORTS          # the binding wraps exactly the declared set
+
+
+def test_minibatch_seed_matches_the_oracle():
+    for master in (0, 1, 2 ** 63 + 5):
+        for h in (0, 1, 77, 2 ** 40 + 3):
+            assert w2v.minibatch_seed(master, h) == oracle.minibatch_seed(master, h)
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    L = w2v.lib()
+    h = ctypes.c_void_p(0)
+    assert L.w2v_shard_create_ex(0, 4, 0, 4, 1, 0, ctypes.byref(h)) == -2          # V = 0
+    assert L.w2v_shard_create_ex(10, 4, 2, 4, 1, 0, ctypes.byref(h)) == -2         # columns 2..6 of 4
+    assert L.w2v_shard_create_ex(10, 2048, 0, 2048, 1, 0, ctypes.byref(h)) == -2   # d_slice too large
+    assert L.w2v_shard_create_ex(10, 4, 0, 4, 1, 7, ctypes.byref(h)) == -2         # init mode
+    assert L.w2v_shard_create_ex(10, 4, 0, 4, 1, 0, None) == -1
+    assert b"NULL" in L.w2v_last_error()
+    assert L.w2v_shard_destroy(None) == 0
+    assert L.w2v_shard_status(None, None) == -1
+
+
+def test_workload_generators_are_seeded_and_shaped():
+    wl = workloads.WORKLOADS["tiny"]
+    t1, o1 = workloads.corpus(wl, 5000)
+    t2, o2 = workloads.corpus(wl, 5000)
+    assert np.array_equal(t1, t2) and np.array_equal(o1, o2)
+    assert t1.dtype == np.uint32 and t1.max() < wl.V
+    assert o1[0] == 0 and o1[-1] == 5000 and np.all(np.diff(o1.astype(np.int64)) == 20)
+    wl4 = workloads.WORKLOADS["search200m"]
+    rng = np.random.default_rng(0)
+    off = workloads.sentence_offsets(10_000, wl4.sent_min, wl4.sent_max, rng)
+    lens = np.diff(off.astype(np.int64))
+    assert off[-1] == 10_000 and lens[:-1].min() >= 10 and lens.max() <= 40
+    # Zipf(1): the most frequent word is about twice as frequent as the second
+    cdf = workloads.zipf_cdf(1000, 1.0)
+    x = workloads.zipf_draw(cdf, 200_000, rng)
+    c = np.bincount(x, minlength=1000)
+    assert 1.8 < c[0] / c[1] < 2.2
+    counts = workloads.analytic_counts(1000, 1.0, 10 ** 6)
+    assert counts.min() >= 1 and counts[0] > counts[1] > counts[10]
+    assert workloads.alpha_schedule(workloads.WORKLOADS["full300"], 0, 100) == np.float32(0.025)
+    assert abs(workloads.alpha_schedule(workloads.WORKLOADS["full300"], 100, 100) - 1e-4) < 1e-9

@@ -1,0 +1,428 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded
+inputs.  Integer results (tables, negatives, pairs) must match bit for bit; fp32 results within
+1e-5 after one minibatch and 1e-3 after a hundred (error measures in tests/util.py).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1606_08495_amd import w2v, workloads
+from util import all_rows, dev, dot_error, set_all_rows, vec_error, zipf_counts
+
+pytestmark = pytest.mark.gpu
+
+TOL1 = 1e-5
+TOL100 = 1e-3
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def make_shard(V, d, seed, counts=None, t=0.0, d_total=None, col_begin=0, init_mode=1):
+    sh = w2v.Shard(V, d, seed, d_total=d_total, col_begin=col_begin, init_mode=init_mode)
+    if counts is not None:
+        sh.set_counts(counts, t)
+    return sh
+
+
+def oracle_state(V, d, seed, d_total=None, col_begin=0, init_mode=1):
+    rows = np.arange(V, dtype=np.uint32)
+    dt = d if d_total is None else d_total
+    U = oracle.init_rows(seed, dt, col_begin, d, 0, rows)
+    W = oracle.init_rows(seed, dt, col_begin, d, 1, rows) if init_mode else np.zeros((V, d), np.float32)
+    return U, W
+
+
+# --- initial vectors and tables: bit exact ---------------------------------------------------
+
+@pytest.mark.parametrize("V,d,d_total,col_begin,mode", [
+    (1000, 60, 300, 60, 1), (300, 300, 300, 0, 0), (257, 7, 23, 5, 1), (64, 100, 100, 0, 1),
+    (50, 1000, 1000, 0, 1), (33, 1, 1, 0, 1)])
+def test_initial_vectors_bit_exact(V, d, d_total, col_begin, mode):
+    say("init", V, d, d_total, col_begin, mode)
+    sh = make_shard(V, d, 12345, d_total=d_total, col_begin=col_begin, init_mode=mode)
+    U, W = oracle_state(V, d, 12345, d_total, col_begin, mode)
+    assert np.array_equal(all_rows(sh, 0), U)
+    assert np.array_equal(all_rows(sh, 1), W)
+    sh.destroy()
+
+
+def test_tables_bit_exact():
+    V = 50_000
+    counts = zipf_counts(V, 1.07, 3e8)
+    counts[100:120] = 0
+    sh = make_shard(V, 8, 1, counts, 1e-4)
+    th, al, kp = sh.get_tables()
+    oth, oal = oracle.build_alias(counts)
+    assert np.array_equal(th, oth) and np.array_equal(al, oal)
+    assert np.array_equal(kp, oracle.build_keep(counts, 1e-4))
+    sh.set_counts(counts, 0.0)
+    assert np.all(sh.get_tables()[2] == 2 ** 32)
+    sh.destroy()
+
+
+# --- negatives: bit exact ------------------------------------------------------------------------
+
+@pytest.mark.parametrize("V,n,k,skew", [(2, 3000, 3, 12.0), (5, 5000, 4, 3.0), (1000, 4099, 5, 1.0),
+                                        (100_000, 70_001, 25, 1.05), (3, 257, 64, 6.0)])
+def test_negatives_bit_exact(V, n, k, skew):
+    say("negatives", V, n, k, skew)
+    rng = np.random.default_rng(V + k)
+    counts = np.maximum(1, 1e12 / np.arange(1, V + 1) ** skew).astype(np.uint64)
+    sh = make_shard(V, 4, 7, counts)
+    th, al = oracle.build_alias(counts)
+    out = (rng.random(n) ** 3 * V).astype(np.uint32)        # mostly the frequent words
+    seed = 0x9E3779B97F4A7C15
+    neg = w2v.index_to_numpy(sh.negatives(dev(out), k, seed))
+    ref = oracle.negatives(out, k, seed, th, al)
+    assert np.array_equal(neg, ref)
+    assert not np.any(neg == out[:, None])
+    sh.status()
+    sh.destroy()
+
+
+# --- dotprod ----------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("V,d,n,k", [(5000, 60, 4099, 5), (3000, 300, 2050, 5), (2000, 100, 1000, 10),
+                                     (1500, 200, 777, 25), (400, 7, 513, 0), (300, 1000, 300, 3),
+                                     (900, 129, 1, 6), (64, 256, 65, 64)])
+def test_dotprod_parity(V, d, n, k):
+    say("dotprod", V, d, n, k)
+    rng = np.random.default_rng(d + n)
+    counts = zipf_counts(V)
+    sh = make_shard(V, d, 99, counts)
+    U, W = oracle_state(V, d, 99)
+    th, al = oracle.build_alias(counts)
+    in_idx = rng.integers(0, V, n).astype(np.uint32)
+    out_idx = rng.integers(0, V, n).astype(np.uint32)
+    seed = 4242
+    got = sh.dotprod(dev(in_idx), dev(out_idx), k, seed).cpu().numpy()
+    ref = oracle.dotprod(U, W, in_idx, out_idx, k, seed, th, al)
+    rows = np.concatenate([out_idx[:, None], oracle.negatives(out_idx, k, seed, th, al)], axis=1)
+    err = dot_error(got, ref, U, W, in_idx, rows)
+    say("  dot error", err)
+    assert err <= TOL1
+    # dotprod does not modify the shard
+    assert np.array_equal(all_rows(sh, 0), U) and np.array_equal(all_rows(sh, 1), W)
+    sh.status()
+    sh.destroy()
+
+
+def test_dotprod_empty_batch_and_zero_output_vectors():
+    V, d = 100, 60
+    counts = zipf_counts(V)
+    sh = make_shard(V, d, 5, counts, init_mode=0)
+    e = torch.empty(0, dtype=torch.int32, device="cuda")
+    assert sh.dotprod(e, e, 5, 1).shape == (0, 6)
+    idx = dev(np.arange(50, dtype=np.uint32))
+    assert torch.all(sh.dotprod(idx, idx, 5, 1) == 0)
+    sh.destroy()
+
+
+# --- coefficients ------------------------------------------------------------------------------------
+
+def test_coeffs_parity():
+    rng = np.random.default_rng(3)
+    n, k, S = 3001, 5, 3
+    sh = make_shard(10, 4, 1)
+    parts = [(rng.standard_normal((n, k + 1)) * 4).astype(np.float32) for _ in range(S)]
+    parts[0][0, :] = 60.0
+    parts[0][1, :] = -60.0
+    got, loss = sh.coeffs([torch.from_numpy(p).cuda() for p in parts], k, want_loss=True)
+    ref, ref_loss = oracle.coeffs(parts, want_loss=True)
+    got = got.cpu().numpy()
+    # the three float partials are added in float on the GPU and in double by the oracle: the sum
+    # differs by a few ulp of its magnitude, and d(coefficient)/df <= 1/4
+    ftot = np.sum([np.abs(p.astype(np.float64)) for p in parts], axis=0)
+    assert np.all(np.abs(got - ref) <= 1e-6 * np.maximum(np.abs(ref), 1e-30) + 0.25 * 3e-7 * ftot)
+    assert abs(float(loss.item()) - ref_loss) <= 1e-5 * abs(ref_loss)
+    sh.destroy()
+
+
+# --- adjust ------------------------------------------------------------------------------------------
+
+def run_adjust_case(V, d, n, k, in_idx, out_idx, seed=77, alpha=0.025, label=""):
+    counts = zipf_counts(V)
+    sh = make_shard(V, d, 31, counts)
+    U, W = oracle_state(V, d, 31)
+    th, al = oracle.build_alias(counts)
+    g = workloads.uniform_coeffs(n, k + 1, seed)
+    sh.adjust(dev(in_idx), dev(out_idx), k, seed, torch.from_numpy(g).cuda(), alpha)
+    oracle.adjust(U, W, in_idx, out_idx, k, seed, th, al, g, alpha)
+    eu, ew = vec_error(all_rows(sh, 0), U), vec_error(all_rows(sh, 1), W)
+    say("  adjust", label, "U error", eu, "W error", ew)
+    sh.status()
+    sh.destroy()
+    return eu, ew
+
+
+@pytest.mark.parametrize("V,d,n,k", [(3000, 60, 4099, 5), (2000, 300, 2050, 5), (50, 100, 3000, 5),
+                                     (4000, 200, 999, 25), (30, 7, 1025, 2), (500, 1000, 200, 3),
+                                     (7, 16, 1, 0), (100, 128, 257, 10)])
+def test_adjust_parity(V, d, n, k):
+    say("adjust", V, d, n, k)
+    rng = np.random.default_rng(V + d)
+    in_idx = rng.integers(0, V, n).astype(np.uint32)
+    out_idx = rng.integers(0, V, n).astype(np.uint32)
+    eu, ew = run_adjust_case(V, d, n, k, in_idx, out_idx)
+    assert eu <= TOL1 and ew <= TOL1
+
+
+def test_adjust_heavy_rows_many_levels():
+    # every pair shares one input word and one output word: both runs span every chunk, so the
+    # partial sums go through several levels of the reduction (T13)
+    V, d, n, k = 10, 60, 20_000, 1
+    in_idx = np.full(n, 3, np.uint32)
+    out_idx = np.full(n, 7, np.uint32)
+    eu, ew = run_adjust_case(V, d, n, k, in_idx, out_idx, label="heavy")
+    assert eu <= TOL1 and ew <= TOL1
+    # a Zipf(1.2)-like head: word 0 takes a fifth of the pairs
+    rng = np.random.default_rng(8)
+    V, d, n, k = 2000, 200, 30_000, 5
+    cdf = workloads.zipf_cdf(V, 1.2)
+    in_idx = workloads.zipf_draw(cdf, n, rng)
+    out_idx = workloads.zipf_draw(cdf, n, rng)
+    eu, ew = run_adjust_case(V, d, n, k, in_idx, out_idx, label="zipf1.2")
+    assert eu <= TOL1 and ew <= TOL1
+
+
+def test_adjust_reads_start_of_call_vectors():
+    # the same pair twice in one call gives exactly twice the change of one call (T8)
+    V, d = 6, 60
+    sh = make_shard(V, d, 3, np.ones(V, np.uint64))
+    U0, W0 = all_rows(sh, 0), all_rows(sh, 1)
+    a, b = np.array([2, 2], np.uint32), np.array([4, 4], np.uint32)
+    g = torch.tensor([[0.3], [0.3]], dtype=torch.float32, device="cuda")
+    sh.adjust(dev(a), dev(b), 0, 1, g, 1.0)
+    U1, W1 = all_rows(sh, 0), all_rows(sh, 1)
+    np.testing.assert_allclose(U1[2] - U0[2], 2 * np.float32(0.3) * W0[4], rtol=1e-6, atol=1e-9)
+    np.testing.assert_allclose(W1[4] - W0[4], 2 * np.float32(0.3) * U0[2], rtol=1e-6, atol=1e-9)
+    untouched = [r for r in range(V) if r != 2]
+    assert np.array_equal(U1[untouched], U0[untouched])
+    sh.destroy()
+
+
+def test_adjust_null_updates_are_bitwise_noops():
+    rng = np.random.default_rng(9)
+    V, d, n, k = 200, 100, 1500, 5
+    counts = zipf_counts(V)
+    sh = make_shard(V, d, 4, counts)
+    U0, W0 = all_rows(sh, 0), all_rows(sh, 1)
+    in_idx, out_idx = dev(rng.integers(0, V, n)), dev(rng.integers(0, V, n))
+    g = torch.from_numpy(workloads.uniform_coeffs(n, k + 1, 1)).cuda()
+    sh.adjust(in_idx, out_idx, k, 5, g, 0.0)
+    assert np.array_equal(all_rows(sh, 0), U0) and np.array_equal(all_rows(sh, 1), W0)
+    sh.adjust(in_idx, out_idx, k, 5, torch.zeros_like(g), 0.5)
+    assert np.array_equal(all_rows(sh, 0), U0) and np.array_equal(all_rows(sh, 1), W0)
+    sh.adjust(in_idx[:0], out_idx[:0], k, 5, g[:0], 0.5)
+    assert np.array_equal(all_rows(sh, 0), U0)
+    sh.destroy()
+
+
+def test_runs_are_bitwise_reproducible():
+    rng = np.random.default_rng(10)
+    V, d, n, k = 500, 300, 6000, 5
+    counts = zipf_counts(V)
+    in_idx, out_idx = dev(rng.integers(0, V, n)), dev(rng.integers(0, V, n))
+    results = []
+    for rep in range(2):
+        sh = make_shard(V, d, 8, counts)
+        dots = sh.dotprod(in_idx, out_idx, k, 123).cpu().numpy()
+        loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+        for h in range(3):
+            w2v.train_minibatch([sh], in_idx, out_idx, k, 1000 + h, 0.025, loss=loss)
+        results.append((dots, all_rows(sh, 0), all_rows(sh, 1), loss.item()))
+        sh.destroy()
+    for a, b in zip(results[0], results[1]):
+        assert np.array_equal(a, b)
+
+
+# --- the whole step --------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("V,d,n,k,mode", [(3000, 300, 4099, 5, 1), (2000, 60, 2500, 5, 1),
+                                          (800, 100, 4096, 5, 0), (500, 200, 1111, 25, 1)])
+def test_train_minibatch_parity_one_shard(V, d, n, k, mode):
+    say("train S=1", V, d, n, k, mode)
+    rng = np.random.default_rng(n)
+    counts = zipf_counts(V)
+    sh = make_shard(V, d, 21, counts, init_mode=mode)
+    U, W = oracle_state(V, d, 21, init_mode=mode)
+    th, al = oracle.build_alias(counts)
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for h in range(2):
+        in_idx = rng.integers(0, V, n).astype(np.uint32)
+        out_idx = rng.integers(0, V, n).astype(np.uint32)
+        seed = w2v.minibatch_seed(5, h)
+        assert seed == oracle.minibatch_seed(5, h)
+        w2v.train_minibatch([sh], dev(in_idx), dev(out_idx), k, seed, 0.05, loss=loss)
+        ref_loss = oracle.train_minibatch([U], [W], in_idx, out_idx, k, seed, th, al, 0.05)
+        assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss)
+    eu, ew = vec_error(all_rows(sh, 0), U), vec_error(all_rows(sh, 1), W)
+    say("  errors", eu, ew)
+    assert eu <= 2 * TOL1 and ew <= 2 * TOL1      # two minibatches
+    sh.status()
+    sh.destroy()
+
+
+def test_train_minibatch_five_column_shards_match_one_wide_shard():
+    # T4: S = 5 slices of 60 columns against the oracle's single 300-wide vectors
+    rng = np.random.default_rng(55)
+    V, n, k = 1500, 3000, 5
+    counts = zipf_counts(V)
+    shards = [make_shard(V, 60, 77, counts, d_total=300, col_begin=60 * s) for s in range(5)]
+    U, W = oracle_state(V, 300, 77)
+    assert np.array_equal(np.concatenate([all_rows(s, 0) for s in shards], axis=1), U)
+    th, al = oracle.build_alias(counts)
+    in_idx = rng.integers(0, V, n).astype(np.uint32)
+    out_idx = rng.integers(0, V, n).astype(np.uint32)
+    # partial dots sum to the full dot
+    parts = [s.dotprod(dev(in_idx), dev(out_idx), k, 9).cpu().numpy().astype(np.float64) for s in shards]
+    full = oracle.dotprod(U, W, in_idx, out_idx, k, 9, th, al)
+    rows = np.concatenate([out_idx[:, None], oracle.negatives(out_idx, k, 9, th, al)], axis=1)
+    assert dot_error(np.sum(parts, axis=0), full, U, W, in_idx, rows) <= TOL1
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    w2v.train_minibatch(shards, dev(in_idx), dev(out_idx), k, 9, 0.05, loss=loss)
+    ref_loss = oracle.train_minibatch([U], [W], in_idx, out_idx, k, 9, th, al, 0.05)
+    assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss)
+    Ug = np.concatenate([all_rows(s, 0) for s in shards], axis=1)
+    Wg = np.concatenate([all_rows(s, 1) for s in shards], axis=1)
+    assert vec_error(Ug, U) <= TOL1 and vec_error(Wg, W) <= TOL1
+    for s in shards:
+        s.destroy()
+
+
+def test_unequal_slices_and_two_call_form_match_the_fused_step():
+    rng = np.random.default_rng(56)
+    V, n, k = 400, 1200, 5
+    counts = zipf_counts(V)
+    cuts = [(0, 7), (7, 143), (150, 150)]
+    shards = [make_shard(V, w, 3, counts, d_total=300, col_begin=b) for b, w in cuts]
+    one = make_shard(V, 300, 3, counts)
+    in_idx, out_idx = dev(rng.integers(0, V, n)), dev(rng.integers(0, V, n))
+    w2v.train_minibatch(shards, in_idx, out_idx, k, 1, 0.05)
+    w2v.train_minibatch([one], in_idx, out_idx, k, 1, 0.05)
+    Ug = np.concatenate([all_rows(s, 0) for s in shards], axis=1)
+    Wg = np.concatenate([all_rows(s, 1) for s in shards], axis=1)
+    assert vec_error(Ug, all_rows(one, 0)) <= TOL1 and vec_error(Wg, all_rows(one, 1)) <= TOL1
+    for s in shards + [one]:
+        s.destroy()
+
+
+def test_tiny_config_hundred_minibatches():
+    # BASELINE config 1: V = 10,000, d = 100, window 5, k = 5, t = 1e-4, minibatches of 4096 pairs
+    wl = workloads.WORKLOADS["tiny"]
+    tokens, off = workloads.corpus(wl)
+    counts = workloads.counted(tokens, wl.V)
+    sh = make_shard(wl.V, wl.d_slice, wl.seed, counts, wl.subsample_t, init_mode=0)
+    U, W = oracle_state(wl.V, wl.d_slice, wl.seed, init_mode=0)
+    th, al = oracle.build_alias(counts)
+    kt = oracle.build_keep(counts, wl.subsample_t)
+    cap = tokens.size * 2 * wl.window
+    gi = torch.empty(cap, dtype=torch.int32, device="cuda")
+    go = torch.empty(cap, dtype=torch.int32, device="cuda")
+    off_dev = torch.from_numpy(off.astype(np.int64)).cuda()
+    cnt = sh.make_pairs(dev(tokens), off_dev, 0, 0, wl.seed, wl.window, gi, go)
+    oi, oo, ocnt = oracle.make_pairs(tokens, off, 0, 0, wl.seed, wl.window, kt)
+    assert cnt == ocnt
+    assert np.array_equal(w2v.index_to_numpy(gi[:cnt]), oi) and np.array_equal(w2v.index_to_numpy(go[:cnt]), oo)
+    nb = min(100, cnt // wl.n_pairs)
+    say("  tiny config:", cnt, "pairs,", nb, "minibatches")
+    assert nb >= 100
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    losses, ref_losses = [], []
+    for h in range(nb):
+        a, b = h * wl.n_pairs, (h + 1) * wl.n_pairs
+        seed = w2v.minibatch_seed(wl.seed, h)
+        w2v.train_minibatch([sh], gi[a:b], go[a:b], wl.k, seed, wl.alpha, loss=loss)
+        losses.append(loss.item())
+        ref_losses.append(oracle.train_minibatch([U], [W], oi[a:b], oo[a:b], wl.k, seed, th, al, wl.alpha))
+        if h == 0:
+            e1 = max(vec_error(all_rows(sh, 0), U), vec_error(all_rows(sh, 1), W))
+            say("  after 1 minibatch:", e1)
+            assert e1 <= TOL1
+    eu, ew = vec_error(all_rows(sh, 0), U), vec_error(all_rows(sh, 1), W)
+    say("  after", nb, "minibatches:", eu, ew, "loss", losses[0], "->", losses[-1])
+    assert eu <= TOL100 and ew <= TOL100
+    assert np.allclose(losses, ref_losses, rtol=1e-4)
+    assert np.mean(losses[-10:]) < np.mean(losses[:10])
+    sh.status()
+    sh.destroy()
+
+
+# --- pair formation: bit exact -------------------------------------------------------------------------
+
+@pytest.mark.parametrize("B,t", [(1, 0.0), (5, 1e-3), (10, 1e-2), (3, 1e9)])
+def test_make_pairs_bit_exact(B, t):
+    rng = np.random.default_rng(B)
+    V, n_tok = 300, 20_011
+    tokens = workloads.zipf_draw(workloads.zipf_cdf(V, 1.0), n_tok, rng)
+    counts = workloads.counted(tokens, V)
+    lens = rng.integers(0, 45, 2000)                 # includes empty and one-word sentences
+    off = np.concatenate([[0], np.cumsum(lens)])
+    off = np.append(off[off < n_tok], n_tok).astype(np.uint64)
+    sh = make_shard(V, 4, 1, counts, t)
+    kt = oracle.build_keep(counts, t) if t > 0 else None
+    base = (1 << 33) + 12345
+    cap = n_tok * 2 * B
+    gi = torch.empty(cap, dtype=torch.int32, device="cuda")
+    go = torch.empty(cap, dtype=torch.int32, device="cuda")
+    cnt = sh.make_pairs(dev(tokens), torch.from_numpy(off.astype(np.int64)).cuda(), base, 3, 99, B, gi, go)
+    oi, oo, ocnt = oracle.make_pairs(tokens, off, base, 3, 99, B, kt)
+    assert cnt == ocnt
+    assert np.array_equal(w2v.index_to_numpy(gi[:cnt]), oi)
+    assert np.array_equal(w2v.index_to_numpy(go[:cnt]), oo)
+    # a too-small output still reports the full count and fills what fits
+    gi2 = torch.empty(1000, dtype=torch.int32, device="cuda")
+    go2 = torch.empty(1000, dtype=torch.int32, device="cuda")
+    cnt2 = sh.make_pairs(dev(tokens), torch.from_numpy(off.astype(np.int64)).cuda(), base, 3, 99, B, gi2, go2)
+    assert cnt2 == cnt and np.array_equal(w2v.index_to_numpy(gi2), oi[:1000])
+    sh.status()
+    sh.destroy()
+
+
+# --- errors are reported, never faults -------------------------------------------------------------------
+
+def test_argument_errors():
+    sh = make_shard(100, 60, 1)
+    idx = dev(np.arange(10, dtype=np.uint32))
+    with pytest.raises(w2v.W2VError) as e:
+        sh.dotprod(idx, idx, 5, 1)                        # no noise table yet
+    assert e.value.code == -5
+    sh.set_counts(np.ones(100, np.uint64))
+    with pytest.raises(w2v.W2VError) as e:
+        sh.dotprod(idx, idx, 65, 1)
+    assert e.value.code == -2
+    with pytest.raises(w2v.W2VError):
+        w2v.Shard(0, 60, 1)
+    with pytest.raises(w2v.W2VError):
+        w2v.Shard(10, 2000, 1)
+    other = make_shard(101, 60, 1, np.ones(101, np.uint64))
+    with pytest.raises(w2v.W2VError) as e:
+        w2v.train_minibatch([sh, other], idx, idx, 5, 1, 0.1)
+    assert e.value.code == -7
+    other.destroy()
+    sh.destroy()
+
+
+def test_out_of_range_index_raises_the_sticky_flag_without_a_fault():
+    sh = make_shard(100, 60, 1, np.ones(100, np.uint64))
+    bad = dev(np.array([1, 2, 100, 4_000_000_000], np.uint32))
+    good = dev(np.array([1, 2, 3, 4], np.uint32))
+    sh.dotprod(bad, good, 5, 1)
+    with pytest.raises(w2v.W2VError) as e:
+        sh.status()
+    assert e.value.code == -6
+    sh.status()                                           # cleared
+    g = torch.zeros((4, 6), dtype=torch.float32, device="cuda")
+    sh.adjust(good, bad, 5, 1, g, 0.1)
+    with pytest.raises(w2v.W2VError):
+        sh.status()
+    w2v.train_minibatch([sh], bad, bad, 5, 1, 0.1)
+    with pytest.raises(w2v.W2VError):
+        sh.status()
+    sh.get_rows(0, bad)
+    with pytest.raises(w2v.W2VError):
+        sh.status()
+    sh.destroy()

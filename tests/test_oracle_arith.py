@@ -1,6 +1,6 @@
 """Pins of the oracle's arithmetic (dots, coefficients, adjust) against things the oracle does not
 compute itself: brute-force loops written here, closed forms, finite differences of the objective
-(Eq.1/Eq.3), the column-slice invariant (Section 4.1) and the start-of-call rule of adjust.
+(Eq.1/Eq.3), the column-slice invariant (Section 5.1) and the start-of-call rule of adjust.
 """
 import math
 import os
