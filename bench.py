@@ -1,0 +1,313 @@
+#!/usr/bin/env python3
+"""Benchmark of the word2vec shard path on one MI355X.
+
+One step = one pass of the whole hot path over one minibatch: pair formation from the token stream
+(amortised over the minibatches a token block yields), negatives, dot products, coefficients and
+the deterministic adjust -- i.e. w2v_make_pairs + w2v_train_minibatch (workload "full300", the
+10M-word d=300 configuration the bandwidth target is stated on), or w2v_dotprod + w2v_adjust with
+harness coefficients (workload "slice60", one of five column shards).
+
+Prints one JSON line: pairs/s (k negatives included), ms per step, the roofline entry of the
+dominant kernel (algorithmic bytes / its measured HIP-event time, against 8 TB/s) and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class PairStream:
+    """Feeds minibatches of n pairs cut from the pair stream of a token corpus (device side)."""
+
+    def __init__(self, shard, wl, tokens, sent_off, block_tokens, torch):
+        self.torch = torch
+        self.sh, self.wl = shard, wl
+        self.tok = torch.from_numpy(tokens.view(np.int32)).cuda()
+        self.off_host = sent_off.astype(np.int64)
+        self.block_tokens = block_tokens
+        cap = wl.n_pairs + block_tokens * 2 * wl.window
+        self.a = torch.empty(cap, dtype=torch.int32, device="cuda")
+        self.b = torch.empty(cap, dtype=torch.int32, device="cuda")
+        self.have = 0           # valid pairs at the front of the buffers
+        self.pos = 0            # consumed pairs
+        self.sent = 0           # next sentence
+        self.epoch = 0
+        self.tokens_used = 0
+
+    def _refill(self):
+        torch = self.torch
+        rest = self.have - self.pos
+        if rest > 0 and self.pos > 0:
+            self.a[:rest] = self.a[self.pos:self.have].clone()
+            self.b[:rest] = self.b[self.pos:self.have].clone()
+        self.have, self.pos = rest, 0
+        off = self.off_host
+        if self.sent >= off.size - 1:
+            self.sent, self.epoch = 0, self.epoch + 1
+        s0 = self.sent
+        t0 = int(off[s0])
+        s1 = int(np.searchsorted(off, t0 + self.block_tokens, side="right")) - 1
+        s1 = max(s1, s0 + 1)
+        s1 = min(s1, off.size - 1)
+        t1 = int(off[s1])
+        rel = torch.from_numpy(off[s0:s1 + 1] - t0).cuda()
+        cnt = self.sh.make_pairs(self.tok[t0:t1], rel, t0, self.epoch, self.wl.seed, self.wl.window,
+                                 self.a[self.have:], self.b[self.have:])
+        assert cnt <= self.a.numel() - self.have
+        self.have += cnt
+        self.sent = s1
+        self.tokens_used += t1 - t0
+
+    def next(self):
+        n = self.wl.n_pairs
+        while self.have - self.pos < n:
+            self._refill()
+        a = self.a[self.pos:self.pos + n]
+        b = self.b[self.pos:self.pos + n]
+        self.pos += n
+        return a, b
+
+
+def cpu_baseline_full(wl, counts, in_idx, out_idx, seed, sample_pairs):
+    import oracle
+    th, al = oracle.build_alias(counts)
+    lazy = oracle.LazyShard(wl.V, wl.d_total, wl.col_begin, wl.d_slice, wl.seed, wl.w_uniform)
+    m = min(sample_pairs, in_idx.size)
+    t0 = time.perf_counter()
+    lazy.train_minibatch(in_idx[:m], out_idx[:m], wl.k, seed, th, al, wl.alpha)
+    dt = time.perf_counter() - t0
+    lazy.close()
+    return {"value": m / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d pairs of minibatch 0 of workload %s, oracle train_minibatch on "
+                      "lazily initialised rows, %.1f s" % (m, wl.name, dt)}
+
+
+def cpu_baseline_slice(wl, counts, in_idx, out_idx, coeffs, seed, sample_pairs):
+    import oracle
+    th, al = oracle.build_alias(counts)
+    m = min(sample_pairs, in_idx.size)
+    ii, oo = in_idx[:m], out_idx[:m]
+    neg = oracle.negatives(oo, wl.k, seed, th, al)
+    rows = np.concatenate([oo[:, None], neg], axis=1)
+    words, inv = np.unique(np.concatenate([ii, rows.ravel()]), return_inverse=True)
+    U = oracle.init_rows(wl.seed, wl.d_total, wl.col_begin, wl.d_slice, 0, words.astype(np.uint32))
+    W = oracle.init_rows(wl.seed, wl.d_total, wl.col_begin, wl.d_slice, 1, words.astype(np.uint32))
+    ci = inv[:m].astype(np.uint32)
+    cr = inv[m:].reshape(rows.shape).astype(np.uint32)
+    t0 = time.perf_counter()
+    oracle.negatives(oo, wl.k, seed, th, al)
+    oracle.dots(U, W, ci, cr)
+    oracle.negatives(oo, wl.k, seed, th, al)
+    oracle.adjust_rows(U, W, ci, cr, coeffs[:m], wl.alpha)
+    dt = time.perf_counter() - t0
+    return {"value": m / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d pairs of the minibatch of workload %s, oracle dotprod + adjust on "
+                      "the touched rows, %.1f s" % (m, wl.name, dt)}
+
+
+def distinct_rows(torch, shard, in_idx, out_idx, k, seed):
+    """Distinct input rows and distinct output/negative rows of one minibatch (for byte counts)."""
+    neg = shard.negatives(out_idx, k, seed)
+    du = int(torch.unique(in_idx).numel())
+    dw = int(torch.unique(torch.cat([out_idx, neg.reshape(-1)])).numel())
+    return du, dw
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="full300", choices=["full300", "slice60", "tiny"])
+    ap.add_argument("--corpus-tokens", type=int, default=0, help="tokens of the corpus slice to generate")
+    ap.add_argument("--cpu-sample-pairs", type=int, default=1 << 17)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (a shard is one GPU's column slice); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1606_08495_amd import w2v, workloads
+
+    if not os.path.exists(w2v.LIB_PATH):
+        from paper_1606_08495_amd import build as hip_build
+        hip_build.build()
+    torch.cuda.set_device(0)
+    wl = workloads.WORKLOADS[args.workload]
+    K, Wm = args.steps, args.warmup
+    R = 4 * wl.d_slice
+    T = wl.k + 1
+
+    t_setup = time.perf_counter()
+    cdf = workloads.zipf_cdf(wl.V, wl.zipf_s)
+    if wl.name == "tiny":
+        tokens, off = workloads.corpus(wl, cdf=cdf)
+        counts = workloads.counted(tokens, wl.V)
+    else:
+        counts = workloads.analytic_counts(wl.V, wl.zipf_s, wl.corpus_tokens)
+    sh = w2v.Shard(wl.V, wl.d_slice, wl.seed, d_total=wl.d_total, col_begin=wl.col_begin,
+                   init_mode=1 if wl.w_uniform else 0)
+    sh.set_counts(counts, wl.subsample_t)
+    log("setup: shard V=%d d_slice=%d (%.1f GB of vectors) ready in %.1f s"
+        % (wl.V, wl.d_slice, 2.0 * wl.V * R / 1e9, time.perf_counter() - t_setup))
+
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    total_steps = K + Wm
+    result_extra = {}
+
+    if wl.pairs_from_corpus:
+        # ---- end-to-end: make_pairs + train_minibatch ------------------------------------------
+        if wl.name != "tiny":
+            n_tok = args.corpus_tokens or 12_000_000
+            tokens, off = workloads.corpus(wl, n_tok, cdf=cdf)
+        del cdf
+        stream = PairStream(sh, wl, tokens, off, block_tokens=min(tokens.size, 1 << 21), torch=torch)
+        H = max(1, wl.corpus_tokens * 4 // wl.n_pairs)     # minibatches in the nominal corpus
+
+        def step(h):
+            a, b = stream.next()
+            w2v.train_minibatch([sh], a, b, wl.k, w2v.minibatch_seed(wl.seed, h),
+                                workloads.alpha_schedule(wl, h, H), loss=loss)
+            return a, b
+
+        first = None
+        for h in range(Wm):
+            ab = step(h)
+            if first is None:
+                first = (w2v.index_to_numpy(ab[0]).copy(), w2v.index_to_numpy(ab[1]).copy())
+        if first is None:
+            a0, b0 = stream.next()
+            first = (w2v.index_to_numpy(a0).copy(), w2v.index_to_numpy(b0).copy())
+            stream.pos -= wl.n_pairs
+        sh.status()
+        sh.timing_enable(True)
+        sh.timing_read()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        last = None
+        for h in range(Wm, total_steps):
+            last = step(h)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        phases = sh.timing_read()
+        sh.timing_enable(False)
+        sh.status()
+        du, dw = distinct_rows(torch, sh, last[0], last[1], wl.k, w2v.minibatch_seed(wl.seed, total_steps - 1))
+        result_extra["tokens_per_minibatch"] = stream.tokens_used / max(1, total_steps)
+        if not args.no_cpu_baseline:
+            cpu = cpu_baseline_full(wl, counts, first[0], first[1], w2v.minibatch_seed(wl.seed, 0),
+                                    args.cpu_sample_pairs)
+    else:
+        # ---- two-call form on one column slice: dotprod + adjust with harness coefficients --------
+        ii, oo = workloads.iid_pairs(wl, cdf=cdf)
+        del cdf
+        g = workloads.uniform_coeffs(wl.n_pairs, T, wl.seed)
+        a, b = w2v.as_index_tensor(ii), w2v.as_index_tensor(oo)
+        gd = torch.from_numpy(g).cuda()
+        dots = torch.empty((wl.n_pairs, T), dtype=torch.float32, device="cuda")
+
+        def step(h):
+            seed = w2v.minibatch_seed(wl.seed, h)
+            sh.dotprod(a, b, wl.k, seed, out=dots)
+            sh.adjust(a, b, wl.k, seed, gd, wl.alpha)
+
+        for h in range(Wm):
+            step(h)
+        sh.status()
+        sh.timing_enable(True)
+        sh.timing_read()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for h in range(Wm, total_steps):
+            step(h)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        phases = sh.timing_read()
+        sh.timing_enable(False)
+        sh.status()
+        du, dw = distinct_rows(torch, sh, a, b, wl.k, w2v.minibatch_seed(wl.seed, total_steps - 1))
+        if not args.no_cpu_baseline:
+            cpu = cpu_baseline_slice(wl, counts, ii, oo, g, w2v.minibatch_seed(wl.seed, 0),
+                                     args.cpu_sample_pairs)
+
+    n = wl.n_pairs
+    M = n * T
+    ms_per_step = dt * 1e3 / K
+    pairs_per_s = n * K / dt
+
+    # ---- algorithmic bytes of each gather/scatter phase, per launch (= per minibatch) -------------
+    #   dot      : (k+2) rows per pair + keys + dots written
+    #   uside    : T output rows per pair (+ the input row when fused) + keys/coefficients/sort data
+    #              + one delta row written per distinct input row
+    #   wside    : one input row per contribution + 12 B of key/slot/coefficient
+    #              + one read and one write of every distinct destination row
+    fused = wl.pairs_from_corpus
+    algo = {
+        "dot": n * (wl.k + 2) * R + 8 * M,
+        "uside": n * (T + (1 if fused else 0)) * R + 8 * M + 8 * n + du * R,
+        "wside": M * R + 12 * M + 2 * dw * R,
+    }
+    per_phase = {}
+    for name, (ms, cnt) in phases.items():
+        if cnt:
+            per_phase[name] = {"ms_per_launch": ms / cnt, "launches": cnt}
+    dom = max((p for p in per_phase if p in algo), key=lambda p: per_phase[p]["ms_per_launch"] *
+              per_phase[p]["launches"])
+    dom_ms = per_phase[dom]["ms_per_launch"]
+    achieved = algo[dom] / (dom_ms * 1e-3) / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % wl.name)
+    if os.path.exists(tfile):
+        try:
+            traffic = json.load(open(tfile)).get(dom)
+        except Exception:
+            traffic = None
+    step_algo = 3 * (wl.k + 2) * R * n
+    out = {
+        "metric": "SGNS training pairs/s (k negatives incl.) on 1 MI355X",
+        "value": pairs_per_s,
+        "unit": "pairs/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": Wm,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "V": wl.V, "d_slice": wl.d_slice, "d_total": wl.d_total,
+                   "pairs_per_minibatch": n, "k": wl.k, "zipf_s": wl.zipf_s, "window": wl.window,
+                   "subsample_t": wl.subsample_t,
+                   "path": "make_pairs+train_minibatch" if fused else "dotprod+adjust",
+                   "distinct_input_rows": du, "distinct_output_rows": dw},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": algo[dom], "ms_per_launch": dom_ms},
+        "step_logical_GBps": step_algo / (ms_per_step * 1e-3) / 1e9,
+        "phases": per_phase,
+    }
+    out.update(result_extra)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu
+    sh.destroy()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
