@@ -135,6 +135,8 @@ def main():
     ap.add_argument("--corpus-tokens", type=int, default=0, help="tokens of the corpus slice to generate")
     ap.add_argument("--cpu-sample-pairs", type=int, default=1 << 17)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (calibrates HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (a shard is one GPU's column slice); "
@@ -165,6 +167,14 @@ def main():
     sh.set_counts(counts, wl.subsample_t)
     log("setup: shard V=%d d_slice=%d (%.1f GB of vectors) ready in %.1f s"
         % (wl.V, wl.d_slice, 2.0 * wl.V * R / 1e9, time.perf_counter() - t_setup))
+
+    if args.copy_probe_mb:
+        src = torch.ones(args.copy_probe_mb << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)              # one copy kernel: reads and writes copy_probe_mb MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     loss = torch.zeros(1, dtype=torch.float64, device="cuda")
     total_steps = K + Wm

@@ -183,7 +183,7 @@ Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_
     p.in_safe = c.take<uint32_t>(n);
     if (want_coeffs) p.coeffs = c.take<float>(p.M);
     if (S_dots) p.dots = c.take<float>((size_t)S_dots * p.M);
-    p.loss_tmp = c.take<double>(std::max<size_t>(coeffs_loss_scratch_doubles(n, p.T), n) + 8);
+    p.loss_tmp = c.take<double>(coeffs_loss_scratch_doubles(n, p.T));
     if (want_adjust) {
         p.uk0 = c.take<uint32_t>(n); p.uv0 = c.take<uint32_t>(n);
         p.uk1 = c.take<uint32_t>(n); p.uv1 = c.take<uint32_t>(n);
@@ -282,7 +282,15 @@ extern "C" int w2v_shard_create_ex(uint32_t V, uint32_t d_total, uint32_t col_be
     sh->V = V; sh->d_total = d_total; sh->col_begin = col_begin; sh->d_slice = d_slice;
     sh->seed = seed; sh->init_mode = init_mode;
     sh->g.d4 = (d_slice + 3) / 4;
+    // Row stride.  A short row that straddles 128-byte lines costs a whole extra line per gather
+    // (a 240-byte row touches 2.75 lines on average, 2 when aligned), so rows under 512 bytes are
+    // padded to a multiple of 128 bytes when that adds at most an eighth; longer rows gain nothing
+    // measurable and stay dense.  W2V_ROW_ALIGN_FLOATS overrides the granularity (for experiments).
     uint32_t align4 = 1;                     // row stride granularity in float4
+    if (sh->g.d4 < 32) {
+        uint32_t padded = ((sh->g.d4 + 7) / 8) * 8;
+        if ((padded - sh->g.d4) * 8 <= sh->g.d4) align4 = 8;
+    }
     if (const char* env = getenv("W2V_ROW_ALIGN_FLOATS")) {
         long v = atol(env);
         if (v >= 4 && v <= 256 && (v % 4) == 0) align4 = (uint32_t)v / 4;
@@ -499,7 +507,7 @@ extern "C" int w2v_coeffs(w2v_shard* sh, const float* const* partials, uint32_t 
         pp.p[s] = partials[s];
     }
     hipStream_t st = (hipStream_t)stream;
-    size_t need = sizeof(double) * (coeffs_loss_scratch_doubles(n, k + 1) + 8) + 512;
+    size_t need = sizeof(double) * coeffs_loss_scratch_doubles(n, k + 1) + 512;
     rc = ensure_ws(sh, need);
     if (rc) return rc;
     {

@@ -18,16 +18,18 @@ static inline unsigned blocks_for(uint64_t items, unsigned per_block) {
 }
 
 constexpr int ADJ_THREADS = 256;
-constexpr int WSEG_C = 8;      // entries per chunk, output side level 1
+constexpr int WSEG_C = 16;     // entries per chunk, output side level 1
 constexpr int TAIL_C = 16;     // entries per chunk, higher levels (even, so a border's two slots
                                // fall into one chunk)
 constexpr uint32_t NOKEY = 0xFFFFFFFFu;   // compares unequal to every masked key
 
 uint32_t wseg_entries_per_chunk() { return WSEG_C; }
 uint32_t tail_entries_per_chunk() { return TAIL_C; }
-uint32_t useg_pairs_per_chunk(uint32_t T) {
+uint32_t useg_pairs_per_chunk(uint32_t T) {     // about 48 entries, 2..16 pairs, <= 136 entries
     uint32_t c = (48 + T - 1) / T;
-    return c < 2 ? 2 : c;
+    if (c < 2) c = 2;
+    if (c > 16) c = 16;
+    return c;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -99,19 +101,22 @@ __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
     uint32_t head_key = KEY_NONE, tail_key = KEY_NONE;
     const uint32_t head_slot = 2 * c - 1, tail_slot = 2 * c;   // used only when they exist
 
+    // Register sets srcv[t] / dstv[t] hold the source row of an entry and, when its run finishes
+    // inside the chunk, the destination row.  Entry e uses set e % D; as soon as an entry has been
+    // consumed its set is refilled with entry e + D, so D entries' rows stay in flight.
+    float4 srcv[D][NV], dstv[D][NV];
+    auto fetch = [&](int e, float4 (&sv)[NV], float4 (&dv)[NV]) {
+        uint32_t sr = __shfl(srow, e, G);
+        int h = __shfl(has, e, G);
+        int cm = __shfl(complete, e, G);
+        uint32_t dk = __shfl(key, e, G);
+        load_row_if<G, NV>(h != 0, a.src + (uint64_t)sr * s4, d4, l, sv);
+        load_row_if<G, NV>(cm != 0, a.dst + (uint64_t)(cm ? dk : 0u) * s4, d4, l, dv);
+    };
+#pragma unroll
+    for (int t = 0; t < D; ++t) fetch(t, srcv[t], dstv[t]);
 #pragma unroll
     for (int b = 0; b < C; b += D) {
-        float4 srcv[D][NV], dstv[D][NV];
-#pragma unroll
-        for (int t = 0; t < D; ++t) {
-            const int e = b + t;
-            uint32_t sr = __shfl(srow, e, G);
-            int h = __shfl(has, e, G);
-            int cm = __shfl(complete, e, G);
-            uint32_t dk = __shfl(key, e, G);
-            load_row_if<G, NV>(h != 0, a.src + (uint64_t)sr * s4, d4, l, srcv[t]);
-            load_row_if<G, NV>(cm != 0, a.dst + (uint64_t)(cm ? dk : 0u) * s4, d4, l, dstv[t]);
-        }
 #pragma unroll
         for (int t = 0; t < D; ++t) {
             const int e = b + t;
@@ -140,6 +145,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
                 }
                 clear<NV>(acc);
             }
+            if (b + D < C) fetch(e + D, srcv[t], dstv[t]);
         }
     }
     // ---- the last run may go on into the next chunk ----
@@ -207,60 +213,92 @@ __device__ __forceinline__ float softplus_f(float x) {
     return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
 }
 
+constexpr int USEG_MAXP = 16;     // pairs per chunk, at most
+constexpr int USEG_MAXE = 136;    // entries (pairs x slots) per chunk, at most
+
 template <int G, int NV, int TB, bool FUSED>
 __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t CP) {
-    const int l = threadIdx.x % G;
-    const uint32_t c = (blockIdx.x * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
+    constexpr int GROUPS = ADJ_THREADS / G;
+    // The chunk's indices are staged in LDS first (two dependent gathers for the whole chunk), so
+    // that the row loads of the main loop depend on nothing but LDS reads.
+    __shared__ uint32_t s_key[GROUPS][USEG_MAXE];                 // output row of every entry
+    __shared__ float s_cf[FUSED ? 1 : GROUPS][FUSED ? 1 : USEG_MAXE];   // given coefficients
+    __shared__ uint32_t s_pair[GROUPS][USEG_MAXP];                // pair number of every sorted pair
+    __shared__ uint32_t s_skey[GROUPS][USEG_MAXP + 2];            // input word: [0] before, [cnt+1] after
+    const int l = threadIdx.x % G, grp = threadIdx.x / G;
+    const uint32_t c = blockIdx.x * (uint32_t)GROUPS + grp;
     const uint32_t nchunks = (a.n + CP - 1) / CP;
-    if (c >= nchunks) return;
-    const uint32_t ps0 = c * CP;
-    const uint32_t ps1 = min(a.n, ps0 + CP);
+    const bool active = c < nchunks;
+    const uint32_t ps0 = active ? c * CP : 0u;
+    const uint32_t cnt = active ? min(CP, a.n - ps0) : 0u;
+    const uint32_t T = a.T;
+    for (uint32_t i = l; i < cnt; i += G) {
+        s_pair[grp][i] = a.perm[ps0 + i];
+        s_skey[grp][i + 1] = a.skey[ps0 + i];
+    }
+    if (active && l == 0) {
+        s_skey[grp][0] = ps0 > 0 ? a.skey[ps0 - 1] : NOKEY;
+        s_skey[grp][cnt + 1] = ps0 + cnt < a.n ? a.skey[ps0 + cnt] : NOKEY;
+    }
+    __syncthreads();
+    for (uint32_t i = l; i < cnt * T; i += G) {
+        uint32_t pi = i / T, j = i - pi * T;
+        uint32_t q = s_pair[grp][pi] * T + j;
+        s_key[grp][i] = a.keys[q];
+        if (!FUSED) s_cf[grp][i] = a.coeffs_in[q];
+    }
+    __syncthreads();
+    if (!active) return;
+
     const uint32_t d4 = a.g.d4;
     const uint64_t s4 = a.g.stride4;
     const float4* U4p = (const float4*)a.U;
     const float4* W4p = (const float4*)a.W;
     float4* delta = (float4*)a.delta;
     float4* prows = (float4*)a.prows;
-    const uint32_t T = a.T;
 
-    const uint32_t key_prev = ps0 > 0 ? a.skey[ps0 - 1] : NOKEY;
-    const uint32_t key_after = ps1 < a.n ? a.skey[ps1] : NOKEY;
-    uint32_t key = a.skey[ps0];
-    const bool open_head = (key_prev == key);
+    uint32_t key = s_skey[grp][1];
+    const bool open_head = (s_skey[grp][0] == key);
     uint32_t run_start = ps0;
     uint32_t head_key = KEY_NONE, tail_key = KEY_NONE;
     const uint32_t head_slot = 2 * c - 1, tail_slot = 2 * c;
 
-    float4 acc[NV];
+    float4 acc[NV], w[TB][NV], u[NV], un[NV];
     clear<NV>(acc);
-    for (uint32_t ps = ps0; ps < ps1; ++ps) {
-        const uint32_t p = a.perm[ps];
-        const uint32_t next = (ps + 1 < ps1) ? a.skey[ps + 1] : key_after;
+    // prologue: the first batch of rows (and u) of the chunk's first pair
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        bool on = (uint32_t)t < T;
+        uint32_t r = on ? s_key[grp][t] : 0u;
+        load_row_if<G, NV>(on, W4p + (uint64_t)r * s4, d4, l, w[t]);
+    }
+    if (FUSED) load_row<G, NV>(U4p + (uint64_t)key * s4, d4, l, u);
+
+    for (uint32_t pi = 0; pi < cnt; ++pi) {
+        const uint32_t ps = ps0 + pi;
+        const uint32_t p = s_pair[grp][pi];
+        const uint32_t next = s_skey[grp][pi + 2];
         if (l == 0) a.dkey[ps] = KEY_NONE;
-        float4 u[NV];
-        if (FUSED) load_row<G, NV>(U4p + (uint64_t)key * s4, d4, l, u);
+        if (FUSED) {                                   // the next pair's input row, ahead of need
+            bool more = pi + 1 < cnt;
+            load_row_if<G, NV>(more, U4p + (uint64_t)(more ? next : 0u) * s4, d4, l, un);
+        }
         double pair_loss = 0.0;
         for (uint32_t jb = 0; jb < T; jb += TB) {
-            float4 w[TB][NV];
+            const bool last_batch = jb + TB >= T;
+            const uint32_t npi = last_batch ? pi + 1 : pi;     // where the following batch starts
+            const uint32_t njb = last_batch ? 0u : jb + TB;
             float gco[TB];
-#pragma unroll
-            for (int t = 0; t < TB; ++t) {
-                uint32_t j = jb + t;
-                bool on = j < T;
-                uint32_t r = on ? a.keys[p * T + j] : 0u;
-                load_row_if<G, NV>(on, W4p + (uint64_t)r * s4, d4, l, w[t]);
-                if (!FUSED) gco[t] = on ? a.coeffs_in[p * T + j] : 0.f;
-            }
             if (FUSED) {
-                float s[TB];
+                float sdot[TB];
 #pragma unroll
-                for (int t = 0; t < TB; ++t) s[t] = dot_part<NV>(u, w[t]);
+                for (int t = 0; t < TB; ++t) sdot[t] = dot_part<NV>(u, w[t]);
 #pragma unroll
-                for (int t = 0; t < TB; ++t) s[t] = group_sum<G>(s[t]);
+                for (int t = 0; t < TB; ++t) sdot[t] = group_sum<G>(sdot[t]);
 #pragma unroll
                 for (int t = 0; t < TB; ++t) {
                     uint32_t j = jb + t;
-                    float f = s[t];
+                    float f = sdot[t];
                     float gc;
                     if (j == 0) gc = 1.0f / (1.0f + expf(f));
                     else        gc = -1.0f / (1.0f + expf(-f));
@@ -271,10 +309,20 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
                         if (a.dots_out) a.dots_out[p * T + j] = f;
                     }
                 }
+            } else {
+#pragma unroll
+                for (int t = 0; t < TB; ++t)
+                    gco[t] = (jb + t < T) ? s_cf[grp][pi * T + jb + t] : 0.f;
             }
 #pragma unroll
-            for (int t = 0; t < TB; ++t)
+            for (int t = 0; t < TB; ++t) {
                 if (jb + t < T) axpy<NV>(gco[t], w[t], acc);
+                // this register set is free again: fetch the matching row of the following batch
+                uint32_t nj = njb + t;
+                bool on = npi < cnt && nj < T;
+                uint32_t r = on ? s_key[grp][npi * T + nj] : 0u;
+                load_row_if<G, NV>(on, W4p + (uint64_t)r * s4, d4, l, w[t]);
+            }
         }
         if (FUSED && a.pair_loss && l == 0) a.pair_loss[p] = pair_loss;
         if (next != key) {                       // the run of `key` ends with this pair
@@ -288,10 +336,14 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
             clear<NV>(acc);
             run_start = ps + 1;
         }
+        if (FUSED) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) u[v] = un[v];
+        }
         key = next;
     }
-    if (run_start < ps1) {                       // the last run goes on into the next chunk
-        const uint32_t k_last = a.skey[ps1 - 1];
+    if (run_start < ps0 + cnt) {                 // the last run goes on into the next chunk
+        const uint32_t k_last = s_skey[grp][cnt];
         if (run_start == ps0 && open_head) {
             store_row<G, NV>(prows + (uint64_t)head_slot * s4, d4, l, acc);
             head_key = k_last;

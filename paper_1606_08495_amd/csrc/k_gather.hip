@@ -1,5 +1,7 @@
 // Initial values, row get/set, negative sampling (destination keys), gather dot products and the
 // client's coefficient step.  gfx950, wave64.
+#include <algorithm>
+
 #include "rows.h"
 
 namespace w2v {
@@ -246,43 +248,63 @@ __global__ __launch_bounds__(256) void coeffs_kernel(PartialPtrs parts, uint32_t
     }
 }
 
-__global__ void sum_doubles_kernel(const double* __restrict__ x, uint32_t n,
-                                   double* __restrict__ out) {
-    // One block of 256 threads: thread t sums x[t], x[t+256], ... in order; then a fixed tree.
+// Sum of n doubles in a fixed order: block b of a grid takes the slice [b*span, (b+1)*span), its
+// thread t adds elements t, t+256, ... of the slice in order, then the block reduces by a fixed
+// tree.  Called once over the data (-> one partial per block) and once, with a single block, over
+// the partials.
+__global__ __launch_bounds__(256) void sum_doubles_kernel(const double* __restrict__ x, uint32_t n,
+                                                          uint32_t span,
+                                                          double* __restrict__ out) {
     __shared__ double red[256];
+    uint64_t lo = (uint64_t)blockIdx.x * span;
+    uint64_t hi = lo + span < n ? lo + span : n;
     double s = 0.0;
-    for (uint32_t i = threadIdx.x; i < n; i += 256) s += x[i];
+    for (uint64_t i = lo + threadIdx.x; i < hi; i += 256) s += x[i];
     red[threadIdx.x] = s;
     __syncthreads();
     for (int h = 128; h >= 1; h >>= 1) {
         if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
         __syncthreads();
     }
-    if (threadIdx.x == 0) *out = red[0];
+    if (threadIdx.x == 0) out[blockIdx.x] = red[0];
 }
 
+constexpr uint32_t SUM_SPAN = 4096;
+
+// x[n] -> *out, using tmp[ceil(n / SUM_SPAN)] doubles.
+static void launch_sum_doubles(const double* x, uint32_t n, double* tmp, double* out,
+                               hipStream_t st) {
+    uint32_t nb = (n + SUM_SPAN - 1) / SUM_SPAN;
+    if (nb <= 1) {
+        hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st, x, n, n ? n : 1u, out);
+        return;
+    }
+    hipLaunchKernelGGL(sum_doubles_kernel, dim3(nb), dim3(256), 0, st, x, n, SUM_SPAN, tmp);
+    hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st, (const double*)tmp, nb, nb,
+                       out);
+}
+
+// doubles of scratch for the loss: the per-block (or per-pair) terms plus the second-stage partials
 size_t coeffs_loss_scratch_doubles(uint32_t n, uint32_t T) {
-    return blocks_for((uint64_t)n * T, 256);
+    size_t terms = std::max<size_t>(blocks_for((uint64_t)n * T, 256), n);
+    return terms + (terms + SUM_SPAN - 1) / SUM_SPAN + 8;
 }
 
 void launch_coeffs(PartialPtrs parts, uint32_t S, uint32_t n, uint32_t T, float* coeffs,
                    double* block_loss, double* loss_out, hipStream_t st) {
     uint32_t total = n * T;
     if (total == 0) {
-        if (loss_out) hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st,
-                                         (const double*)nullptr, 0u, loss_out);
+        if (loss_out) launch_sum_doubles(nullptr, 0, nullptr, loss_out, st);
         return;
     }
     unsigned nb = blocks_for(total, 256);
     hipLaunchKernelGGL(coeffs_kernel, dim3(nb), dim3(256), 0, st, parts, S, total, T, coeffs,
                        loss_out ? block_loss : (double*)nullptr);
-    if (loss_out)
-        hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st,
-                           (const double*)block_loss, nb, loss_out);
+    if (loss_out) launch_sum_doubles(block_loss, nb, block_loss + nb, loss_out, st);
 }
 
 void launch_sum_pair_loss(const double* pair_loss, uint32_t n, double* loss_out, hipStream_t st) {
-    hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st, pair_loss, n, loss_out);
+    launch_sum_doubles(pair_loss, n, const_cast<double*>(pair_loss) + n, loss_out, st);
 }
 
 }  // namespace w2v
