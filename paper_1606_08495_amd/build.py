@@ -30,13 +30,27 @@ def _run(cmd):
     return r.stdout
 
 
-def build(verbose=False, jobs=None):
+def build(verbose=False, jobs=None, extra_flags=(), lib=None, obj_dir=None):
+    """extra_flags / lib / obj_dir: for building experimental variants beside the default one."""
+    global OBJ, LIB
+    OBJ_SAVE, LIB_SAVE = OBJ, LIB
+    if obj_dir:
+        OBJ = obj_dir
+    if lib:
+        LIB = lib
+    try:
+        return _build(verbose, jobs, list(extra_flags))
+    finally:
+        OBJ, LIB = OBJ_SAVE, LIB_SAVE
+
+
+def _build(verbose, jobs, extra_flags):
     os.makedirs(OBJ, exist_ok=True)
     jobs = jobs or min(8, len(HIP_SOURCES) + len(CPP_SOURCES))
     tasks = []
     for s in HIP_SOURCES:
         o = os.path.join(OBJ, s + ".o")
-        tasks.append(([HIPCC] + HIP_FLAGS + ["-c", os.path.join(CSRC, s), "-o", o], o))
+        tasks.append(([HIPCC] + HIP_FLAGS + extra_flags + ["-c", os.path.join(CSRC, s), "-o", o], o))
     for s in CPP_SOURCES:
         o = os.path.join(OBJ, s + ".o")
         tasks.append((["g++"] + CPP_FLAGS + ["-c", os.path.join(CSRC, s), "-o", o], o))

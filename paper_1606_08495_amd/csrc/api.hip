@@ -66,6 +66,11 @@ struct w2v_shard {
     // scratch: one region, carved per call
     char* ws = nullptr;
     size_t ws_cap = 0;
+    // second stream for work that only depends on the keys (the output-side sort), joined back
+    // into the caller's stream by an event before its result is used
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    bool overlap = true;
     // timing
     bool timing = false;
     std::vector<TimedSpan> spans;
@@ -164,7 +169,7 @@ struct Plan {
     uint32_t* keys; uint32_t* in_safe;
     uint32_t *uk0, *uv0, *uk1, *uv1;       // sort buffers, input side (n)
     uint32_t *wk0, *wv0, *wk1, *wv1;       // sort buffers, output side (M)
-    uint32_t* sort_tmp;
+    uint32_t* sort_tmp; uint32_t* sort_tmp_u;
     float* coeffs; float* dots; double* loss_tmp;
     float* delta; uint32_t* dkey;
     float* pa_rows; uint32_t* pa_keys;     // input side, level 1 slots
@@ -190,6 +195,7 @@ Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_
         p.wk0 = c.take<uint32_t>(p.M); p.wv0 = c.take<uint32_t>(p.M);
         p.wk1 = c.take<uint32_t>(p.M); p.wv1 = c.take<uint32_t>(p.M);
         p.sort_tmp = c.take<uint32_t>(sort_scratch_u32(p.M ? p.M : 1));
+        p.sort_tmp_u = c.take<uint32_t>(sort_scratch_u32(n ? n : 1));
         const size_t row = (size_t)stride4_max * 4;
         p.delta = c.take<float>((size_t)n * row);
         p.dkey = c.take<uint32_t>(n);
@@ -220,12 +226,43 @@ void run_tails(w2v_shard* sh, float* M, float alpha, float* rows_a, uint32_t* ke
     }
 }
 
-void sort_both_sides(w2v_shard* sh, Plan& p, uint32_t** sku, uint32_t** perm, uint32_t** skw,
-                     uint32_t** sidx, hipStream_t st) {
-    Phase ph(sh, W2V_PH_SORT, st);
+int ensure_side_stream(w2v_shard* sh) {
+    if (sh->side) return W2V_OK;
+    HIP_TRY(hipStreamCreateWithFlags(&sh->side, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&sh->ev_fork, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&sh->ev_join, hipEventDisableTiming));
+    return W2V_OK;
+}
+
+// Sorts the destination keys of both sides.  The output-side sort (the large one) needs nothing
+// but the keys, so it is queued on the shard's second stream, forked from the caller's stream by
+// an event, and runs beside whatever the caller's stream does next (the input-side kernel); the
+// caller's stream waits for it (join_output_sort) just before the first kernel that reads it.
+int sort_both_sides(w2v_shard* sh, Plan& p, uint32_t** sku, uint32_t** perm, uint32_t** skw,
+                    uint32_t** sidx, hipStream_t st) {
     uint32_t bits = key_bits(sh->V);
-    launch_sort_pairs(p.in_safe, p.uk0, p.uv0, p.uk1, p.uv1, p.n, bits, p.sort_tmp, sku, perm, st);
-    launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp, skw, sidx, st);
+    hipStream_t wst = st;
+    if (sh->overlap) {
+        int rc = ensure_side_stream(sh);
+        if (rc) return rc;
+        HIP_TRY(hipEventRecord(sh->ev_fork, st));
+        HIP_TRY(hipStreamWaitEvent(sh->side, sh->ev_fork, 0));
+        wst = sh->side;
+    }
+    {
+        Phase ph(sh, W2V_PH_SORT, wst);
+        launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp, skw, sidx, wst);
+    }
+    if (sh->overlap) HIP_TRY(hipEventRecord(sh->ev_join, sh->side));
+    {
+        Phase ph(sh, W2V_PH_SORT, st);
+        launch_sort_pairs(p.in_safe, p.uk0, p.uv0, p.uk1, p.uv1, p.n, bits, p.sort_tmp_u, sku, perm, st);
+    }
+    return W2V_OK;
+}
+
+void join_output_sort(w2v_shard* sh, hipStream_t st) {
+    if (sh->overlap && sh->side) (void)hipStreamWaitEvent(st, sh->ev_join, 0);
 }
 
 // The update of one shard from given coefficients (or, fused, from its own dots).
@@ -242,6 +279,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
         launch_useg(a, st);
     }
+    join_output_sort(ws_owner, st);
     {
         Phase ph(ws_owner, W2V_PH_WSIDE, st);
         WSideArgs w{};
@@ -296,6 +334,7 @@ extern "C" int w2v_shard_create_ex(uint32_t V, uint32_t d_total, uint32_t col_be
         if (v >= 4 && v <= 256 && (v % 4) == 0) align4 = (uint32_t)v / 4;
     }
     sh->g.stride4 = ((sh->g.d4 + align4 - 1) / align4) * align4;
+    if (const char* env = getenv("W2V_NO_OVERLAP")) sh->overlap = (atoi(env) == 0);
 
     size_t bytes = (size_t)V * sh->g.stride4 * 16;
     hipError_t e = hipMalloc((void**)&sh->U, bytes);
@@ -342,6 +381,9 @@ extern "C" int w2v_shard_destroy(w2v_shard* sh) {
     if (sh->keep) (void)hipFree(sh->keep);
     if (sh->err) (void)hipFree(sh->err);
     if (sh->ws) (void)hipFree(sh->ws);
+    if (sh->ev_fork) (void)hipEventDestroy(sh->ev_fork);
+    if (sh->ev_join) (void)hipEventDestroy(sh->ev_join);
+    if (sh->side) (void)hipStreamDestroy(sh->side);
     delete sh;
     return W2V_OK;
 }
@@ -540,7 +582,8 @@ extern "C" int w2v_adjust(w2v_shard* sh, const uint32_t* in_idx, const uint32_t*
                          p.in_safe, sh->err, st);
     }
     uint32_t *sku, *perm, *skw, *sidx;
-    sort_both_sides(sh, p, &sku, &perm, &skw, &sidx, st);
+    rc = sort_both_sides(sh, p, &sku, &perm, &skw, &sidx, st);
+    if (rc) return rc;
     queue_adjust(sh, sh, p, sku, perm, skw, sidx, coeffs, nullptr, nullptr, false, alpha, st);
     HIP_TRY(hipGetLastError());
     return W2V_OK;
@@ -585,7 +628,8 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
     }
     uint32_t *sku, *perm, *skw, *sidx;
     if (fused) {
-        sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
+        rc = sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
+        if (rc) return rc;
         queue_adjust(s0, s0, p, sku, perm, skw, sidx, nullptr, p.coeffs, loss ? p.loss_tmp : nullptr,
                      true, alpha, st);
         if (loss) launch_sum_pair_loss(p.loss_tmp, n, loss, st);
@@ -603,7 +647,8 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
             Phase ph(s0, W2V_PH_COEFF, st);
             launch_coeffs(pp, S, n, p.T, p.coeffs, p.loss_tmp, loss, st);
         }
-        sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
+        rc = sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
+        if (rc) return rc;
         for (uint32_t s = 0; s < S; ++s)
             queue_adjust(s0, shards[s], p, sku, perm, skw, sidx, p.coeffs, nullptr, nullptr, false,
                          alpha, st);

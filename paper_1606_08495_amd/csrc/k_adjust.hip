@@ -380,34 +380,41 @@ void launch_useg(const USideArgs& a, hipStream_t st) {
 // ---------------------------------------------------------------------------------------------
 // Write-back of the input-vector changes held in the delta buffer.
 // ---------------------------------------------------------------------------------------------
+// A lane group looks at G consecutive sorted positions at once (one dkey per lane) and then walks
+// the few that carry a finished run.
 template <int G, int NV>
 __global__ __launch_bounds__(ADJ_THREADS) void apply_delta_kernel(float4* __restrict__ U, RowGeom g,
                                                                   const float4* __restrict__ delta,
                                                                   const uint32_t* __restrict__ dkey,
                                                                   uint32_t n, float alpha) {
     const int l = threadIdx.x % G;
-    const uint32_t ps = (blockIdx.x * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
-    if (ps >= n) return;
-    const uint32_t key = dkey[ps];
-    if (key == KEY_NONE) return;
-    float4 dv[NV], uv[NV];
-    load_row<G, NV>(delta + (uint64_t)ps * g.stride4, g.d4, l, dv);
-    load_row<G, NV>(U + (uint64_t)key * g.stride4, g.d4, l, uv);
+    const uint32_t grp = (blockIdx.x * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
+    const uint32_t base = grp * (uint32_t)G;
+    if (base >= n) return;
+    const uint32_t mine = (base + l < n) ? dkey[base + l] : KEY_NONE;
+    for (int e = 0; e < G; ++e) {
+        const uint32_t key = __shfl(mine, e, G);
+        if (key == KEY_NONE) continue;
+        const uint32_t ps = base + e;
+        float4 dv[NV], uv[NV];
+        load_row<G, NV>(delta + (uint64_t)ps * g.stride4, g.d4, l, dv);
+        load_row<G, NV>(U + (uint64_t)key * g.stride4, g.d4, l, uv);
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-        uv[v].x = fmaf(alpha, dv[v].x, uv[v].x);
-        uv[v].y = fmaf(alpha, dv[v].y, uv[v].y);
-        uv[v].z = fmaf(alpha, dv[v].z, uv[v].z);
-        uv[v].w = fmaf(alpha, dv[v].w, uv[v].w);
+        for (int v = 0; v < NV; ++v) {
+            uv[v].x = fmaf(alpha, dv[v].x, uv[v].x);
+            uv[v].y = fmaf(alpha, dv[v].y, uv[v].y);
+            uv[v].z = fmaf(alpha, dv[v].z, uv[v].z);
+            uv[v].w = fmaf(alpha, dv[v].w, uv[v].w);
+        }
+        store_row<G, NV>(U + (uint64_t)key * g.stride4, g.d4, l, uv);
     }
-    store_row<G, NV>(U + (uint64_t)key * g.stride4, g.d4, l, uv);
 }
 
 void launch_apply_delta(float* U, RowGeom g, const float* delta, const uint32_t* dkey, uint32_t n,
                         float alpha, hipStream_t st) {
     if (n == 0) return;
 #define CALL(G, NV)                                                                              \
-    hipLaunchKernelGGL((apply_delta_kernel<G, NV>), dim3(blocks_for((uint64_t)n * G, ADJ_THREADS)), \
+    hipLaunchKernelGGL((apply_delta_kernel<G, NV>), dim3(blocks_for(n, ADJ_THREADS)),            \
                        dim3(ADJ_THREADS), 0, st, (float4*)U, g, (const float4*)delta, dkey, n, alpha)
     W2V_DISPATCH_GEOM(g.d4, CALL);
 #undef CALL

@@ -67,13 +67,36 @@ __device__ __forceinline__ void clear(float4 (&acc)[NV]) {
     for (int v = 0; v < NV; ++v) acc[v] = f4zero();
 }
 
-// Sum over the G lanes of a group by a butterfly; every lane ends with the same bits because each
-// step adds the same two operands in both partners.
+// Sum over the G lanes of a group; every lane of the group ends with the same bits.
+// Inside a 16-lane row the butterfly runs on DPP lane permutations (xor 1, xor 2, then the two
+// mirror patterns, in which both partners of a step still add the same two operands).  The four
+// row sums of a wavefront are then fetched with v_readlane and added in a fixed order.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+
+__device__ __forceinline__ float row16_sum(float x) {
+    x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
+    x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
+    x += dpp_move<0x141>(x);   // row_half_mirror: lane i <-> 7-i within 8
+    x += dpp_move<0x140>(x);   // row_mirror: lane i <-> 15-i within 16
+    return x;
+}
+
+__device__ __forceinline__ float lane_value(float x, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
+}
+
 template <int G>
 __device__ __forceinline__ float group_sum(float x) {
-#pragma unroll
-    for (int m = G / 2; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
-    return x;
+    x = row16_sum(x);
+    if (G == 16) return x;
+    const float lo = lane_value(x, 0) + lane_value(x, 16);
+    const float hi = lane_value(x, 32) + lane_value(x, 48);
+    if (G == 32) return (threadIdx.x & 32) ? hi : lo;
+    return lo + hi;
 }
 
 // Choice of group shape for a row of d4 float4.

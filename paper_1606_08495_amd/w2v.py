@@ -11,7 +11,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libw2v_shard.so")
+LIB_PATH = os.environ.get("W2V_LIB", os.path.join(_HERE, "libw2v_shard.so"))
 _lib = None
 
 PHASES = ["neg", "dot", "coeff", "sort", "uside", "wside", "apply", "pairs"]
