@@ -135,6 +135,7 @@ def main():
     ap.add_argument("--corpus-tokens", type=int, default=0, help="tokens of the corpus slice to generate")
     ap.add_argument("--cpu-sample-pairs", type=int, default=1 << 17)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-loss", action="store_true", help="do not request the minibatch loss")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates HBM counters)")
     args = ap.parse_args()
@@ -176,7 +177,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    loss = None if args.no_loss else torch.zeros(1, dtype=torch.float64, device="cuda")
     total_steps = K + Wm
     result_extra = {}
 

@@ -268,14 +268,14 @@ void join_output_sort(w2v_shard* sh, hipStream_t st) {
 // The update of one shard from given coefficients (or, fused, from its own dots).
 void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* sku,
                   const uint32_t* perm, const uint32_t* skw, const uint32_t* sidx,
-                  const float* coeffs_in, float* coeffs_out, double* pair_loss, bool fused,
-                  float alpha, hipStream_t st) {
+                  const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
+                  hipStream_t st) {
     {
         Phase ph(ws_owner, W2V_PH_USIDE, st);
         USideArgs a{};
         a.U = sh->U; a.W = sh->W; a.g = sh->g; a.skey = sku; a.perm = perm; a.keys = p.keys;
         a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
-        a.dots_out = nullptr; a.pair_loss = pair_loss; a.delta = p.delta; a.dkey = p.dkey;
+        a.dots_out = nullptr; a.delta = p.delta; a.dkey = p.dkey;
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
         launch_useg(a, st);
     }
@@ -584,7 +584,7 @@ extern "C" int w2v_adjust(w2v_shard* sh, const uint32_t* in_idx, const uint32_t*
     uint32_t *sku, *perm, *skw, *sidx;
     rc = sort_both_sides(sh, p, &sku, &perm, &skw, &sidx, st);
     if (rc) return rc;
-    queue_adjust(sh, sh, p, sku, perm, skw, sidx, coeffs, nullptr, nullptr, false, alpha, st);
+    queue_adjust(sh, sh, p, sku, perm, skw, sidx, coeffs, nullptr, false, alpha, st);
     HIP_TRY(hipGetLastError());
     return W2V_OK;
 }
@@ -613,7 +613,7 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (n == 0) {
-        if (loss) launch_sum_pair_loss(nullptr, 0, loss, st);
+        if (loss) launch_loss_from_coeffs(nullptr, 0, k + 1, nullptr, loss, st);
         return W2V_OK;
     }
     const bool fused = (S == 1);
@@ -630,9 +630,11 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
     if (fused) {
         rc = sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
         if (rc) return rc;
-        queue_adjust(s0, s0, p, sku, perm, skw, sidx, nullptr, p.coeffs, loss ? p.loss_tmp : nullptr,
-                     true, alpha, st);
-        if (loss) launch_sum_pair_loss(p.loss_tmp, n, loss, st);
+        queue_adjust(s0, s0, p, sku, perm, skw, sidx, nullptr, p.coeffs, true, alpha, st);
+        if (loss) {
+            Phase ph(s0, W2V_PH_COEFF, st);
+            launch_loss_from_coeffs(p.coeffs, n, p.T, p.loss_tmp, loss, st);
+        }
     } else {
         PartialPtrs pp{};
         {
@@ -650,8 +652,7 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
         rc = sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
         if (rc) return rc;
         for (uint32_t s = 0; s < S; ++s)
-            queue_adjust(s0, shards[s], p, sku, perm, skw, sidx, p.coeffs, nullptr, nullptr, false,
-                         alpha, st);
+            queue_adjust(s0, shards[s], p, sku, perm, skw, sidx, p.coeffs, nullptr, false, alpha, st);
     }
     HIP_TRY(hipGetLastError());
     return W2V_OK;

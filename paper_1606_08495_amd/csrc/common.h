@@ -97,21 +97,24 @@ uint32_t tail_entries_per_chunk();
 // A lane group sums coeffs[p][j] * W[keys[p][j]] over the pairs of its chunk; a run of equal keys
 // that lies inside the chunk is written to delta[first ps of run] with dkey[ps] = key (KEY_NONE
 // elsewhere); runs cut by a chunk border go to the partial slots (pkeys/prows), two per border.
-// With `fused` the group also loads u = U[key], forms the dots, writes coefficients (and block
-// losses) and uses those coefficients.
+// With `fused` the group also loads u = U[key], forms the dots, writes coefficients
+// and uses those coefficients.
 struct USideArgs {
     const float* U; const float* W; RowGeom g;
     const uint32_t* skey; const uint32_t* perm; const uint32_t* keys; uint32_t n; uint32_t T;
     const float* coeffs_in;      // unfused: coefficients to use
     float* coeffs_out;           // fused: coefficients written here [n][T]
     float* dots_out;             // fused, optional: the dots themselves
-    double* pair_loss;           // fused, optional: per-pair loss [n] (by pair number)
     float* delta; uint32_t* dkey;
     float* prows; uint32_t* pkeys;
     bool fused;
 };
 void launch_useg(const USideArgs& a, hipStream_t st);
-void launch_sum_pair_loss(const double* pair_loss, uint32_t n, double* loss_out, hipStream_t st);
+// Minibatch loss from the coefficients alone: a slot with coefficient g contributes
+// -log(1 - |g|), which is -log sigma(f) for the positive slot and -log(1 - sigma(f)) for a
+// negative one.  tmp holds coeffs_loss_scratch_doubles(n, T) doubles.
+void launch_loss_from_coeffs(const float* coeffs, uint32_t n, uint32_t T, double* tmp,
+                             double* loss_out, hipStream_t st);
 
 // Output-vector side, level 1.  Sorted contributions i = 0..M-1 with destination skey[i] and
 // original slot sidx[i] = p*T + j: adds alpha * sum coeffs[sidx] * U[in_idx[p]] to W[skey] for runs

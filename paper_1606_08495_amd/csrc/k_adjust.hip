@@ -209,9 +209,10 @@ void launch_tail(const TailArgs& t, hipStream_t st) {
 // FUSED: the group also holds u, forms the T dots of the pair, turns them into coefficients
 // (written out for the output side) and uses them at once -- the output rows are read only once.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float softplus_f(float x) {
-    return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
-}
+// sigma(-x) = 1 / (1 + e^x): the positive slot's coefficient 1 - sigma(f) is sigma(-f), a negative
+// slot's -sigma(f) is -sigma(-(-f)); written this way the coefficient keeps its relative accuracy
+// when it is small.
+__device__ __forceinline__ float sigmoid_of_minus(float x) { return 1.0f / (1.0f + expf(x)); }
 
 constexpr int USEG_MAXP = 16;     // pairs per chunk, at most
 constexpr int USEG_MAXE = 136;    // entries (pairs x slots) per chunk, at most
@@ -283,7 +284,6 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
             bool more = pi + 1 < cnt;
             load_row_if<G, NV>(more, U4p + (uint64_t)(more ? next : 0u) * s4, d4, l, un);
         }
-        double pair_loss = 0.0;
         for (uint32_t jb = 0; jb < T; jb += TB) {
             const bool last_batch = jb + TB >= T;
             const uint32_t npi = last_batch ? pi + 1 : pi;     // where the following batch starts
@@ -299,11 +299,8 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
                 for (int t = 0; t < TB; ++t) {
                     uint32_t j = jb + t;
                     float f = sdot[t];
-                    float gc;
-                    if (j == 0) gc = 1.0f / (1.0f + expf(f));
-                    else        gc = -1.0f / (1.0f + expf(-f));
+                    const float gc = (j == 0) ? sigmoid_of_minus(f) : -sigmoid_of_minus(-f);
                     gco[t] = (j < T) ? gc : 0.f;
-                    if (a.pair_loss && j < T) pair_loss += (double)softplus_f(j == 0 ? -f : f);
                     if (l == t && j < T) {
                         a.coeffs_out[p * T + j] = gc;
                         if (a.dots_out) a.dots_out[p * T + j] = f;
@@ -324,7 +321,6 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
                 load_row_if<G, NV>(on, W4p + (uint64_t)r * s4, d4, l, w[t]);
             }
         }
-        if (FUSED && a.pair_loss && l == 0) a.pair_loss[p] = pair_loss;
         if (next != key) {                       // the run of `key` ends with this pair
             if (run_start == ps0 && open_head) {
                 store_row<G, NV>(prows + (uint64_t)head_slot * s4, d4, l, acc);
@@ -359,6 +355,142 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same step for a compile-time number of slots per pair (T), taking PB pairs per batch: all
+// PB*T output rows and the PB input rows of a batch are requested before the first of them is
+// used, so a lane group keeps PB*(T+1) rows in flight instead of T+1.  The kernel is
+// latency-bound (rows in flight per SIMD x row size / memory latency), and registers spent on
+// rows in flight buy more than registers spent on extra resident waves.
+// ---------------------------------------------------------------------------------------------
+template <int G, int NV, int T, int PB, bool FUSED>
+__global__ __launch_bounds__(ADJ_THREADS) void useg_multi_kernel(USideArgs a, uint32_t CP) {
+    constexpr int GROUPS = ADJ_THREADS / G;
+    constexpr int MAXP = 16, MAXE = MAXP * T;
+    __shared__ uint32_t s_key[GROUPS][MAXE];
+    __shared__ float s_cf[FUSED ? 1 : GROUPS][FUSED ? 1 : MAXE];
+    __shared__ uint32_t s_pair[GROUPS][MAXP];
+    __shared__ uint32_t s_skey[GROUPS][MAXP + 2];
+    const int l = threadIdx.x % G, grp = threadIdx.x / G;
+    const uint32_t c = blockIdx.x * (uint32_t)GROUPS + grp;
+    const uint32_t nchunks = (a.n + CP - 1) / CP;
+    const bool active = c < nchunks;
+    const uint32_t ps0 = active ? c * CP : 0u;
+    const uint32_t cnt = active ? min(CP, a.n - ps0) : 0u;
+    for (uint32_t i = l; i < cnt; i += G) {
+        s_pair[grp][i] = a.perm[ps0 + i];
+        s_skey[grp][i + 1] = a.skey[ps0 + i];
+    }
+    if (active && l == 0) {
+        s_skey[grp][0] = ps0 > 0 ? a.skey[ps0 - 1] : NOKEY;
+        s_skey[grp][cnt + 1] = ps0 + cnt < a.n ? a.skey[ps0 + cnt] : NOKEY;
+    }
+    __syncthreads();
+    for (uint32_t i = l; i < cnt * T; i += G) {
+        uint32_t pi = i / T, j = i - pi * T;
+        uint32_t q = s_pair[grp][pi] * T + j;
+        s_key[grp][i] = a.keys[q];
+        if (!FUSED) s_cf[grp][i] = a.coeffs_in[q];
+    }
+    __syncthreads();
+    if (!active) return;
+
+    const uint32_t d4 = a.g.d4;
+    const uint64_t s4 = a.g.stride4;
+    const float4* U4p = (const float4*)a.U;
+    const float4* W4p = (const float4*)a.W;
+    float4* delta = (float4*)a.delta;
+    float4* prows = (float4*)a.prows;
+
+    uint32_t key = s_skey[grp][1];
+    const bool open_head = (s_skey[grp][0] == key);
+    uint32_t run_start = ps0;
+    uint32_t head_key = KEY_NONE, tail_key = KEY_NONE;
+    const uint32_t head_slot = 2 * c - 1, tail_slot = 2 * c;
+
+    float4 acc[NV];
+    clear<NV>(acc);
+    for (uint32_t pb = 0; pb < cnt; pb += PB) {
+        float4 w[PB][T][NV], u[PB][NV];
+#pragma unroll
+        for (int b = 0; b < PB; ++b) {
+            const uint32_t pi = pb + b;
+            const bool live = pi < cnt;
+            if (FUSED) {
+                const uint32_t k_in = live ? s_skey[grp][pi + 1] : 0u;
+                load_row_if<G, NV>(live, U4p + (uint64_t)k_in * s4, d4, l, u[b]);
+            }
+#pragma unroll
+            for (int j = 0; j < T; ++j) {
+                const uint32_t r = live ? s_key[grp][pi * T + j] : 0u;
+                load_row_if<G, NV>(live, W4p + (uint64_t)r * s4, d4, l, w[b][j]);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < PB; ++b) {
+            const uint32_t pi = pb + b;
+            if (pi < cnt) {
+                const uint32_t ps = ps0 + pi;
+                const uint32_t p = s_pair[grp][pi];
+                const uint32_t next = s_skey[grp][pi + 2];
+                if (l == 0) a.dkey[ps] = KEY_NONE;
+                float gco[T];
+                if (FUSED) {
+                    float sdot[T];
+#pragma unroll
+                    for (int j = 0; j < T; ++j) sdot[j] = dot_part<NV>(u[b], w[b][j]);
+#pragma unroll
+                    for (int j = 0; j < T; ++j) sdot[j] = group_sum<G>(sdot[j]);
+#pragma unroll
+                    for (int j = 0; j < T; ++j) {
+                        const float f = sdot[j];
+                        gco[j] = (j == 0) ? sigmoid_of_minus(f) : -sigmoid_of_minus(-f);
+                        if (l == j % G) {
+                            a.coeffs_out[p * T + j] = gco[j];
+                            if (a.dots_out) a.dots_out[p * T + j] = f;
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < T; ++j) gco[j] = s_cf[grp][pi * T + j];
+                }
+#pragma unroll
+                for (int j = 0; j < T; ++j) axpy<NV>(gco[j], w[b][j], acc);
+                if (next != key) {                       // the run of `key` ends with this pair
+                    if (run_start == ps0 && open_head) {
+                        store_row<G, NV>(prows + (uint64_t)head_slot * s4, d4, l, acc);
+                        head_key = key;
+                    } else {
+                        store_row<G, NV>(delta + (uint64_t)run_start * s4, d4, l, acc);
+                        if (l == 0) a.dkey[run_start] = key;
+                    }
+                    clear<NV>(acc);
+                    run_start = ps + 1;
+                }
+                key = next;
+            }
+        }
+    }
+    if (run_start < ps0 + cnt) {                 // the last run goes on into the next chunk
+        const uint32_t k_last = s_skey[grp][cnt];
+        if (run_start == ps0 && open_head) {
+            store_row<G, NV>(prows + (uint64_t)head_slot * s4, d4, l, acc);
+            head_key = k_last;
+            tail_key = k_last | KEY_ZERO;
+        } else {
+            store_row<G, NV>(prows + (uint64_t)tail_slot * s4, d4, l, acc);
+            tail_key = k_last;
+        }
+    }
+    if (l == 0) {
+        if (c > 0) a.pkeys[head_slot] = head_key;
+        if (c + 1 < nchunks) a.pkeys[tail_slot] = tail_key;
+    }
+}
+
+#ifndef USEG_PB
+#define USEG_PB 1     // pairs per batch of the fixed-T kernel (1 measured best on MI355X)
+#endif
+
 void launch_useg(const USideArgs& a, hipStream_t st) {
     if (a.n == 0) return;
     uint32_t CP = useg_pairs_per_chunk(a.T);
@@ -366,6 +498,15 @@ void launch_useg(const USideArgs& a, hipStream_t st) {
 #define CALL(G, NV)                                                                               \
     do {                                                                                          \
         dim3 grid(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)), block(ADJ_THREADS);            \
+        if (a.T == 6 && NV <= 2) {                                                                \
+            if (a.fused)                                                                          \
+                hipLaunchKernelGGL((useg_multi_kernel<G, (NV <= 2 ? NV : 1), 6, USEG_PB, true>),  \
+                                   grid, block, 0, st, a, CP);                                    \
+            else                                                                                  \
+                hipLaunchKernelGGL((useg_multi_kernel<G, (NV <= 2 ? NV : 1), 6, USEG_PB, false>), \
+                                   grid, block, 0, st, a, CP);                                    \
+            break;                                                                                \
+        }                                                                                         \
         if (a.fused)                                                                              \
             hipLaunchKernelGGL((useg_kernel<G, NV, (NV <= 2 ? 6 : 4), true>), grid, block, 0, st, \
                                a, CP);                                                            \

@@ -303,8 +303,29 @@ void launch_coeffs(PartialPtrs parts, uint32_t S, uint32_t n, uint32_t T, float*
     if (loss_out) launch_sum_doubles(block_loss, nb, block_loss + nb, loss_out, st);
 }
 
-void launch_sum_pair_loss(const double* pair_loss, uint32_t n, double* loss_out, hipStream_t st) {
-    launch_sum_doubles(pair_loss, n, const_cast<double*>(pair_loss) + n, loss_out, st);
+__global__ __launch_bounds__(256) void loss_from_coeffs_kernel(const float* __restrict__ coeffs,
+                                                               uint32_t total,
+                                                               double* __restrict__ block_loss) {
+    __shared__ double red[256];
+    uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    double term = 0.0;
+    if (i < total) term = -(double)log1pf(-fabsf(coeffs[i]));
+    red[threadIdx.x] = term;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) block_loss[blockIdx.x] = red[0];
+}
+
+void launch_loss_from_coeffs(const float* coeffs, uint32_t n, uint32_t T, double* tmp,
+                             double* loss_out, hipStream_t st) {
+    uint32_t total = n * T;
+    if (total == 0) { launch_sum_doubles(nullptr, 0, nullptr, loss_out, st); return; }
+    unsigned nb = blocks_for(total, 256);
+    hipLaunchKernelGGL(loss_from_coeffs_kernel, dim3(nb), dim3(256), 0, st, coeffs, total, tmp);
+    launch_sum_doubles(tmp, nb, tmp + nb, loss_out, st);
 }
 
 }  // namespace w2v
