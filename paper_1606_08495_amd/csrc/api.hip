@@ -69,7 +69,7 @@ struct w2v_shard {
     // second stream for work that only depends on the keys (the output-side sort), joined back
     // into the caller's stream by an event before its result is used
     hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_keys = nullptr, ev_join = nullptr;
     bool overlap = true;
     // timing
     bool timing = false;
@@ -230,17 +230,23 @@ int ensure_side_stream(w2v_shard* sh) {
     if (sh->side) return W2V_OK;
     HIP_TRY(hipStreamCreateWithFlags(&sh->side, hipStreamNonBlocking));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_fork, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&sh->ev_keys, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_join, hipEventDisableTiming));
     return W2V_OK;
 }
 
-// Sorts the destination keys of both sides.  The output-side sort (the large one) needs nothing
-// but the keys, so it is queued on the shard's second stream, forked from the caller's stream by
-// an event, and runs beside whatever the caller's stream does next (the input-side kernel); the
-// caller's stream waits for it (join_output_sort) just before the first kernel that reads it.
-int sort_both_sides(w2v_shard* sh, Plan& p, uint32_t** sku, uint32_t** perm, uint32_t** skw,
-                    uint32_t** sidx, hipStream_t st) {
-    uint32_t bits = key_bits(sh->V);
+// Everything adjust needs before its first row kernel: the checked input words, the destination
+// keys (positive word + regenerated negatives) and both sorts.
+// The input-side kernel needs the keys and the (small) input-side sort; the output-side sort is only
+// needed later.  So the key generation and the output-side sort are queued on the shard's second
+// stream, forked from the caller's stream by an event, while the caller's stream checks the inputs
+// and sorts the input side; the caller's stream then waits for the keys (ev_keys) and, just before
+// the first kernel that reads the output-side order, for that sort (join_output_sort).
+int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const uint32_t* out_idx,
+                         uint32_t k, uint64_t seed, uint32_t** sku, uint32_t** perm, uint32_t** skw,
+                         uint32_t** sidx, hipStream_t st) {
+    const uint32_t bits = key_bits(sh->V);
+    const NoiseTable nt{sh->bins, sh->V};
     hipStream_t wst = st;
     if (sh->overlap) {
         int rc = ensure_side_stream(sh);
@@ -250,14 +256,21 @@ int sort_both_sides(w2v_shard* sh, Plan& p, uint32_t** sku, uint32_t** perm, uin
         wst = sh->side;
     }
     {
+        Phase ph(sh, W2V_PH_NEG, wst);
+        launch_dest_keys(nt, out_idx, p.n, k, seed, p.keys, sh->err, wst);
+    }
+    if (sh->overlap) HIP_TRY(hipEventRecord(sh->ev_keys, sh->side));
+    {
         Phase ph(sh, W2V_PH_SORT, wst);
         launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp, skw, sidx, wst);
     }
     if (sh->overlap) HIP_TRY(hipEventRecord(sh->ev_join, sh->side));
     {
         Phase ph(sh, W2V_PH_SORT, st);
+        launch_check_inputs(in_idx, p.n, sh->V, p.in_safe, sh->err, st);
         launch_sort_pairs(p.in_safe, p.uk0, p.uv0, p.uk1, p.uv1, p.n, bits, p.sort_tmp_u, sku, perm, st);
     }
+    if (sh->overlap) HIP_TRY(hipStreamWaitEvent(st, sh->ev_keys, 0));
     return W2V_OK;
 }
 
@@ -382,6 +395,7 @@ extern "C" int w2v_shard_destroy(w2v_shard* sh) {
     if (sh->err) (void)hipFree(sh->err);
     if (sh->ws) (void)hipFree(sh->ws);
     if (sh->ev_fork) (void)hipEventDestroy(sh->ev_fork);
+    if (sh->ev_keys) (void)hipEventDestroy(sh->ev_keys);
     if (sh->ev_join) (void)hipEventDestroy(sh->ev_join);
     if (sh->side) (void)hipStreamDestroy(sh->side);
     delete sh;
@@ -501,8 +515,7 @@ extern "C" int w2v_negatives(w2v_shard* sh, const uint32_t* out_idx, uint32_t n,
     Plan p = make_plan(sh->ws, n, k, sh->g.stride4, 0, false, false);
     {
         Phase ph(sh, W2V_PH_NEG, st);
-        launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, out_idx, n, k, seed, p.keys,
-                         p.in_safe, sh->err, st);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, n, k, seed, p.keys, sh->err, st);
         launch_copy_negatives(p.keys, n, k, neg, st);
     }
     HIP_TRY(hipGetLastError());
@@ -525,8 +538,8 @@ extern "C" int w2v_dotprod(w2v_shard* sh, const uint32_t* in_idx, const uint32_t
     Plan p = make_plan(sh->ws, n, k, sh->g.stride4, 0, false, false);
     {
         Phase ph(sh, W2V_PH_NEG, st);
-        launch_dest_keys(NoiseTable{sh->bins, sh->V}, in_idx, out_idx, n, k, seed, p.keys,
-                         p.in_safe, sh->err, st);
+        launch_check_inputs(in_idx, n, sh->V, p.in_safe, sh->err, st);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, n, k, seed, p.keys, sh->err, st);
     }
     {
         Phase ph(sh, W2V_PH_DOT, st);
@@ -576,13 +589,8 @@ extern "C" int w2v_adjust(w2v_shard* sh, const uint32_t* in_idx, const uint32_t*
     rc = ensure_ws(sh, sz.bytes);
     if (rc) return rc;
     Plan p = make_plan(sh->ws, n, k, sh->g.stride4, 0, true, false);
-    {
-        Phase ph(sh, W2V_PH_NEG, st);
-        launch_dest_keys(NoiseTable{sh->bins, sh->V}, in_idx, out_idx, n, k, seed, p.keys,
-                         p.in_safe, sh->err, st);
-    }
     uint32_t *sku, *perm, *skw, *sidx;
-    rc = sort_both_sides(sh, p, &sku, &perm, &skw, &sidx, st);
+    rc = queue_keys_and_sorts(sh, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);
     if (rc) return rc;
     queue_adjust(sh, sh, p, sku, perm, skw, sidx, coeffs, nullptr, false, alpha, st);
     HIP_TRY(hipGetLastError());
@@ -621,15 +629,10 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
     rc = ensure_ws(s0, sz.bytes);
     if (rc) return rc;
     Plan p = make_plan(s0->ws, n, k, stride_max, fused ? 0 : S, true, true);
-    {
-        Phase ph(s0, W2V_PH_NEG, st);
-        launch_dest_keys(NoiseTable{s0->bins, s0->V}, in_idx, out_idx, n, k, seed, p.keys,
-                         p.in_safe, s0->err, st);
-    }
     uint32_t *sku, *perm, *skw, *sidx;
+    rc = queue_keys_and_sorts(s0, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);
+    if (rc) return rc;
     if (fused) {
-        rc = sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
-        if (rc) return rc;
         queue_adjust(s0, s0, p, sku, perm, skw, sidx, nullptr, p.coeffs, true, alpha, st);
         if (loss) {
             Phase ph(s0, W2V_PH_COEFF, st);
@@ -649,8 +652,6 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
             Phase ph(s0, W2V_PH_COEFF, st);
             launch_coeffs(pp, S, n, p.T, p.coeffs, p.loss_tmp, loss, st);
         }
-        rc = sort_both_sides(s0, p, &sku, &perm, &skw, &sidx, st);
-        if (rc) return rc;
         for (uint32_t s = 0; s < S; ++s)
             queue_adjust(s0, shards[s], p, sku, perm, skw, sidx, p.coeffs, nullptr, false, alpha, st);
     }

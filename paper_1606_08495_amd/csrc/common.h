@@ -58,11 +58,13 @@ void launch_gather_rows(const float* M, RowGeom g, uint32_t d_slice, const uint3
 void launch_scatter_rows(float* M, RowGeom g, uint32_t d_slice, const uint32_t* rows, uint32_t m,
                          uint32_t V, const float* src, uint32_t* err, hipStream_t st);
 
-// keys[p*T + 0] = out_idx[p], keys[p*T + j] = negative j.  Indices >= V raise *err and are
-// replaced by 0; in_safe[p] is the checked copy of in_idx[p] that every later kernel uses.
-void launch_dest_keys(NoiseTable nt, const uint32_t* in_idx, const uint32_t* out_idx, uint32_t n,
-                      uint32_t k, uint64_t seed, uint32_t* keys, uint32_t* in_safe, uint32_t* err,
-                      hipStream_t st);
+// keys[p*T + 0] = out_idx[p], keys[p*T + j] = negative j.  An output word >= V raises *err and is
+// replaced by 0.  in_safe[p] (launch_check_inputs) is the checked copy of in_idx[p] that every
+// later kernel uses.
+void launch_dest_keys(NoiseTable nt, const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed,
+                      uint32_t* keys, uint32_t* err, hipStream_t st);
+void launch_check_inputs(const uint32_t* in_idx, uint32_t n, uint32_t V, uint32_t* in_safe,
+                         uint32_t* err, hipStream_t st);
 void launch_copy_negatives(const uint32_t* keys, uint32_t n, uint32_t k, uint32_t* neg,
                            hipStream_t st);
 

@@ -107,11 +107,9 @@ void launch_scatter_rows(float* M, RowGeom g, uint32_t d_slice, const uint32_t* 
 // One thread per slot, so the generator runs with all 64 lanes busy.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void dest_keys_kernel(const uint2* __restrict__ bins, uint32_t V,
-                                                        const uint32_t* __restrict__ in_idx,
                                                         const uint32_t* __restrict__ out_idx,
                                                         uint32_t n, uint32_t T, uint32_t k0,
                                                         uint32_t k1, uint32_t* __restrict__ keys,
-                                                        uint32_t* __restrict__ in_safe,
                                                         uint32_t* err) {
     uint32_t i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n * T) return;
@@ -120,9 +118,6 @@ __global__ __launch_bounds__(256) void dest_keys_kernel(const uint2* __restrict_
     if (wo >= V) { wo = 0; if (j == 0) atomicOr(err, 1u); }
     uint32_t key;
     if (j == 0) {
-        uint32_t wi = in_idx[p];
-        if (wi >= V) { atomicOr(err, 1u); wi = 0; }
-        in_safe[p] = wi;
         key = wo;
     } else {
         key = wo + 1 == V ? 0u : wo + 1;           // the fallback
@@ -138,14 +133,33 @@ __global__ __launch_bounds__(256) void dest_keys_kernel(const uint2* __restrict_
     keys[i] = key;
 }
 
-void launch_dest_keys(NoiseTable nt, const uint32_t* in_idx, const uint32_t* out_idx, uint32_t n,
-                      uint32_t k, uint64_t seed, uint32_t* keys, uint32_t* in_safe, uint32_t* err,
-                      hipStream_t st) {
+void launch_dest_keys(NoiseTable nt, const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed,
+                      uint32_t* keys, uint32_t* err, hipStream_t st) {
     if (n == 0) return;
     uint32_t T = k + 1;
     hipLaunchKernelGGL(dest_keys_kernel, dim3(blocks_for((uint64_t)n * T, 256)), dim3(256), 0, st,
-                       nt.bins, nt.V, in_idx, out_idx, n, T, (uint32_t)seed,
-                       (uint32_t)(seed >> 32), keys, in_safe, err);
+                       nt.bins, nt.V, out_idx, n, T, (uint32_t)seed, (uint32_t)(seed >> 32), keys,
+                       err);
+}
+
+// Range-checked copy of the input words: an index >= V raises *err and is replaced by word 0, so no
+// later kernel can be sent outside the matrices.
+__global__ __launch_bounds__(256) void check_inputs_kernel(const uint32_t* __restrict__ in_idx,
+                                                           uint32_t n, uint32_t V,
+                                                           uint32_t* __restrict__ in_safe,
+                                                           uint32_t* err) {
+    uint32_t p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= n) return;
+    uint32_t wi = in_idx[p];
+    if (wi >= V) { atomicOr(err, 1u); wi = 0; }
+    in_safe[p] = wi;
+}
+
+void launch_check_inputs(const uint32_t* in_idx, uint32_t n, uint32_t V, uint32_t* in_safe,
+                         uint32_t* err, hipStream_t st) {
+    if (n == 0) return;
+    hipLaunchKernelGGL(check_inputs_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, in_idx, n, V,
+                       in_safe, err);
 }
 
 __global__ __launch_bounds__(256) void copy_negatives_kernel(const uint32_t* __restrict__ keys,
@@ -178,7 +192,7 @@ __global__ __launch_bounds__(256) void dots_kernel(const float4* __restrict__ U,
     uint32_t grp = (blockIdx.x * 256u + threadIdx.x) / G;
     const bool live = grp < n;
     const uint32_t p = live ? grp : n - 1;
-    const uint32_t wi = in_idx[p];          // already range-checked (launch_dest_keys)
+    const uint32_t wi = in_idx[p];          // already range-checked (launch_check_inputs)
     float4 u[NV];
     load_row<G, NV>(U + (uint64_t)wi * g.stride4, g.d4, l, u);
     for (uint32_t jb = 0; jb < T; jb += TB) {
