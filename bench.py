@@ -131,7 +131,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="full300", choices=["full300", "slice60", "tiny"])
+    ap.add_argument("--workload", default="full300",
+                    choices=["full300", "slice60", "tiny", "search200m", "stress25"])
     ap.add_argument("--corpus-tokens", type=int, default=0, help="tokens of the corpus slice to generate")
     ap.add_argument("--cpu-sample-pairs", type=int, default=1 << 17)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -184,7 +185,9 @@ def main():
     if wl.pairs_from_corpus:
         # ---- end-to-end: make_pairs + train_minibatch ------------------------------------------
         if wl.name != "tiny":
-            n_tok = args.corpus_tokens or 12_000_000
+            # tokens the timed run will consume, with a margin (pairs per token differ by workload)
+            n_tok = args.corpus_tokens or {"full300": 12_000_000, "search200m": 700_000 * (K + Wm + 2),
+                                           "stress25": 700_000 * (K + Wm + 2)}[wl.name]
             tokens, off = workloads.corpus(wl, n_tok, cdf=cdf)
         del cdf
         stream = PairStream(sh, wl, tokens, off, block_tokens=min(tokens.size, 1 << 21), torch=torch)

@@ -166,3 +166,65 @@ def test_slice60_dotprod_adjust_sampled():
     say("slice60 U error", eu, "W error", ew)
     assert eu <= TOL1 and ew <= TOL1
     sh.destroy()
+
+
+def reduced_n_step(name, n, n_tokens):
+    """Full vocabulary, dimension, k and token law of a large workload; one minibatch of n pairs."""
+    wl = workloads.WORKLOADS[name]
+    rng = np.random.default_rng(11)
+    say(name, ": tables for V =", wl.V)
+    cdf = workloads.zipf_cdf(wl.V, wl.zipf_s)
+    counts = workloads.analytic_counts(wl.V, wl.zipf_s, wl.corpus_tokens)
+    tokens, off = workloads.corpus(wl, n_tokens, cdf=cdf)
+    del cdf
+    sh = w2v.Shard(wl.V, wl.d_slice, wl.seed, d_total=wl.d_total, col_begin=wl.col_begin, init_mode=1)
+    sh.set_counts(counts, wl.subsample_t)
+    th, al = oracle.build_alias(counts)
+    gth, gal, _ = sh.get_tables()
+    assert np.array_equal(gth, th) and np.array_equal(gal, al)
+    del gth, gal, counts
+    say("   pairs")
+    cap = n_tokens * 2 * wl.window
+    gi = torch.empty(cap, dtype=torch.int32, device="cuda")
+    go = torch.empty(cap, dtype=torch.int32, device="cuda")
+    cnt = sh.make_pairs(dev(tokens), torch.from_numpy(off.astype(np.int64)).cuda(), 0, 0, wl.seed,
+                        wl.window, gi, go)
+    oi, oo, ocnt = oracle.make_pairs(tokens, off, 0, 0, wl.seed, wl.window, None)
+    assert cnt == ocnt and cnt >= n
+    assert np.array_equal(w2v.index_to_numpy(gi[:cnt]), oi) and np.array_equal(w2v.index_to_numpy(go[:cnt]), oo)
+    in_idx, out_idx = oi[:n], oo[:n]
+    a, b = gi[:n].contiguous(), go[:n].contiguous()
+    seed = w2v.minibatch_seed(wl.seed, 0)
+    say("   negatives")
+    neg = oracle.negatives(out_idx, wl.k, seed, th, al)
+    assert np.array_equal(w2v.index_to_numpy(sh.negatives(b, wl.k, seed)), neg)
+    rows = np.concatenate([out_idx[:, None], neg], axis=1)
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    w2v.train_minibatch([sh], a, b, wl.k, seed, wl.alpha, loss=loss)
+    sh.status()
+    samp_u = sample_rows(in_idx, 8, 100, rng)
+    samp_w = sample_rows(rows.ravel(), 8, 600, rng)
+    eu, ew = check_sampled_update(sh, wl, in_idx, rows, None, wl.alpha, True, samp_u, samp_w)
+    say("   U error", eu, "W error", ew)
+    assert eu <= TOL1 and ew <= TOL1
+    first = (sh.get_rows(0, dev(samp_u)).cpu().numpy(), sh.get_rows(1, dev(samp_w)).cpu().numpy(), loss.item())
+    sh.destroy()
+    # the same step on a fresh shard gives the same bits (fixed-order reduction, no float atomics)
+    sh = w2v.Shard(wl.V, wl.d_slice, wl.seed, d_total=wl.d_total, col_begin=wl.col_begin, init_mode=1)
+    sh.set_counts(workloads.analytic_counts(wl.V, wl.zipf_s, wl.corpus_tokens), wl.subsample_t)
+    w2v.train_minibatch([sh], a, b, wl.k, seed, wl.alpha, loss=loss)
+    assert np.array_equal(sh.get_rows(0, dev(samp_u)).cpu().numpy(), first[0])
+    assert np.array_equal(sh.get_rows(1, dev(samp_w)).cpu().numpy(), first[1])
+    assert loss.item() == first[2]
+    sh.destroy()
+
+
+def test_stress25_reduced_n_sampled():
+    """V = 50M, d = 200, k = 25, Zipf(1.2): the most frequent word is the input of ~18% of the pairs,
+    so its row collects hundreds of thousands of contributions through several reduction levels."""
+    reduced_n_step("stress25", 1 << 18, 40_000)
+
+
+def test_search200m_reduced_n_sampled():
+    """V = 200M, d_slice = 60 of 300, k = 10, Zipf(0.9): heavy tail, rows rarely reused."""
+    reduced_n_step("search200m", 1 << 18, 64_000)
