@@ -134,7 +134,8 @@ def main():
     ap.add_argument("--workload", default="full300",
                     choices=["full300", "slice60", "tiny", "search200m", "stress25"])
     ap.add_argument("--corpus-tokens", type=int, default=0, help="tokens of the corpus slice to generate")
-    ap.add_argument("--cpu-sample-pairs", type=int, default=1 << 17)
+    ap.add_argument("--cpu-sample-pairs", type=int, default=0,
+                    help="pairs the CPU oracle is timed on (default: about 10-30 s of one core)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loss", action="store_true", help="do not request the minibatch loss")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
@@ -154,6 +155,9 @@ def main():
     torch.cuda.set_device(0)
     wl = workloads.WORKLOADS[args.workload]
     K, Wm = args.steps, args.warmup
+    if not args.cpu_sample_pairs:
+        args.cpu_sample_pairs = {"full300": 1 << 20, "slice60": 1 << 20, "tiny": 1 << 16,
+                                 "search200m": 1 << 19, "stress25": 1 << 17}[wl.name]
     R = 4 * wl.d_slice
     T = wl.k + 1
 
@@ -284,13 +288,13 @@ def main():
               per_phase[p]["launches"])
     dom_ms = per_phase[dom]["ms_per_launch"]
     achieved = algo[dom] / (dom_ms * 1e-3) / 1e9
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % wl.name)
+    traffic = None          # L2<->fabric bytes per launch, from the committed rocprofv3 counter summary
+    tfile = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % wl.name)
     if os.path.exists(tfile):
-        try:
-            traffic = json.load(open(tfile)).get(dom)
-        except Exception:
-            traffic = None
+        for line in open(tfile):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic" and parts[1] == dom:
+                traffic = float(parts[2])
     step_algo = 3 * (wl.k + 2) * R * n
     out = {
         "metric": "SGNS training pairs/s (k negatives incl.) on 1 MI355X",
