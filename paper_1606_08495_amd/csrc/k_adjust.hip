@@ -18,12 +18,11 @@ static inline unsigned blocks_for(uint64_t items, unsigned per_block) {
 }
 
 constexpr int ADJ_THREADS = 256;
-constexpr int WSEG_C = 16;     // entries per chunk, output side level 1
 constexpr int TAIL_C = 16;     // entries per chunk, higher levels (even, so a border's two slots
                                // fall into one chunk)
 constexpr uint32_t NOKEY = 0xFFFFFFFFu;   // compares unequal to every masked key
 
-uint32_t wseg_entries_per_chunk() { return WSEG_C; }
+uint32_t wseg_entries_per_chunk() { return 16; }   // = WOWN_C, the ownership grid
 uint32_t tail_entries_per_chunk() { return TAIL_C; }
 uint32_t useg_pairs_per_chunk(uint32_t T) {     // about 48 entries, 2..16 pairs, <= 136 entries
     uint32_t c = (48 + T - 1) / T;
@@ -172,15 +171,150 @@ __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Output-vector side, level 1, with run ownership.  Chunks of C entries only decide WHO sums a
+// run, not where it is cut: a run that starts in chunk c and ends before the end of chunk c+1
+// ("short", at most 2C entries) is summed entirely by group c, which reads on past its chunk's end
+// and finishes the row with one read-modify-write; the group of chunk c+1 skips those entries.
+// No partial rows are written for short runs, whatever the chunk grid.  A run that reaches chunk
+// c+2 ("long": a frequent word) is cut at every chunk border as in seg_kernel, each chunk leaving
+// its piece in the border slots for the higher levels.  Whether a run is short or long follows
+// from its own extent on the chunk grid, so every group that meets the run decides alike, from the
+// keys at six fixed positions around its chunk.
+// ---------------------------------------------------------------------------------------------
+constexpr int WOWN_C = 16;
+constexpr int WOWN_WIN = 3 * WOWN_C + 2;     // keys staged: positions base-C-1 .. base+2C
+constexpr int WOWN_E = 2 * WOWN_C;           // positions a group may sum: base .. base+2C-1
+enum : uint32_t { ACT_SKIP = 0, ACT_ADD = 1, ACT_COMPLETE = 2, ACT_HEAD = 3, ACT_TAIL = 4, ACT_WHOLE = 5 };
+
+template <int G, int NV, int D>
+__global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
+    constexpr int GROUPS = ADJ_THREADS / G;
+    constexpr int C = WOWN_C;
+    __shared__ uint32_t s_key[GROUPS][WOWN_WIN];
+    __shared__ uint32_t s_srow[GROUPS][WOWN_E];
+    __shared__ float s_coef[GROUPS][WOWN_E];
+    __shared__ uint32_t s_act[GROUPS][WOWN_E];
+    const int l = threadIdx.x % G, grp = threadIdx.x / G;
+    const uint32_t c = blockIdx.x * (uint32_t)GROUPS + grp;
+    const uint32_t nchunks = (a.entries + C - 1) / C;
+    const bool active = c < nchunks;
+    const int64_t base = (int64_t)c * C;
+    for (int i = l; i < WOWN_WIN; i += G) {
+        int64_t pos = base - C - 1 + i;
+        s_key[grp][i] = (active && pos >= 0 && pos < (int64_t)a.entries) ? a.skey[pos] : NOKEY;
+    }
+    __syncthreads();
+    auto K = [&](int rel) -> uint32_t { return s_key[grp][rel + C + 1]; };   // rel = position - base
+    const uint32_t kbm = K(-C - 1), kb = K(-1), k0 = K(0), kC = K(C), k2C = K(2 * C), klast = K(C - 1);
+    const bool head_exists = active && kb == k0;
+    const bool head_long = head_exists && !(kbm != k0 && kC != k0);
+    const bool ext_ok = klast != NOKEY && !(head_exists && klast == k0) && k2C != klast;
+    int my_lo = WOWN_E, my_hi = 0;
+    for (int i = l; i < WOWN_E; i += G) {
+        const uint32_t k = K(i), kn = K(i + 1);
+        uint32_t act = ACT_SKIP;
+        if (active && k != NOKEY) {
+            if (i < C) {
+                if (head_exists && k == k0) {            // a run that came in from the left
+                    if (head_long) act = (kn != k) ? ACT_HEAD : (i == C - 1 ? ACT_WHOLE : ACT_ADD);
+                } else if (k2C != k) {                   // starts here and is short: ours entirely
+                    act = (kn != k) ? ACT_COMPLETE : ACT_ADD;
+                } else {                                 // starts here and is long: our piece of it
+                    act = (i == C - 1) ? ACT_TAIL : ACT_ADD;
+                }
+            } else if (ext_ok && k == klast) {           // the rest of our last short run
+                act = (kn != k) ? ACT_COMPLETE : ACT_ADD;
+            }
+        }
+        s_act[grp][i] = act;
+        if (act != ACT_SKIP) {
+            const uint32_t q = a.sidx[base + i];
+            s_srow[grp][i] = a.in_idx[q / a.T];          // range-checked copy
+            s_coef[grp][i] = a.coeffs[q];
+            my_lo = min(my_lo, i);
+            my_hi = max(my_hi, i + 1);
+        }
+    }
+#pragma unroll
+    for (int m = G / 2; m >= 1; m >>= 1) {                // the active positions form one range
+        my_lo = min(my_lo, __shfl_xor(my_lo, m, 64));
+        my_hi = max(my_hi, __shfl_xor(my_hi, m, 64));
+    }
+    __syncthreads();
+    if (!active || my_lo >= my_hi) {
+        if (active && l == 0) {
+            if (c > 0) a.pkeys[2 * c - 1] = KEY_NONE;
+            if (c + 1 < nchunks) a.pkeys[2 * c] = KEY_NONE;
+        }
+        return;
+    }
+    const int lo = my_lo, hi = my_hi;
+    const uint32_t d4 = a.g.d4;
+    const uint64_t s4 = a.g.stride4;
+    const uint32_t head_slot = 2 * c - 1, tail_slot = 2 * c;
+    uint32_t head_key = KEY_NONE, tail_key = KEY_NONE;
+
+    float4 acc[NV], srcv[D][NV], dstv[D][NV];
+    clear<NV>(acc);
+    auto fetch = [&](int i, float4 (&sv)[NV], float4 (&dv)[NV]) {
+        const bool on = i < hi;
+        const uint32_t sr = on ? s_srow[grp][i] : 0u;
+        const bool cm = on && s_act[grp][i] == ACT_COMPLETE;
+        const uint32_t dk = cm ? K(i) : 0u;
+        load_row_if<G, NV>(on, a.src + (uint64_t)sr * s4, d4, l, sv);
+        load_row_if<G, NV>(cm, a.dst + (uint64_t)dk * s4, d4, l, dv);
+    };
+#pragma unroll
+    for (int t = 0; t < D; ++t) fetch(lo + t, srcv[t], dstv[t]);
+    for (int b = lo; b < hi; b += D) {
+#pragma unroll
+        for (int t = 0; t < D; ++t) {
+            const int i = b + t;
+            if (i < hi) {
+                const uint32_t act = s_act[grp][i];
+                const uint32_t dk = K(i);
+                axpy<NV>(s_coef[grp][i], srcv[t], acc);
+                if (act == ACT_COMPLETE) {
+                    float4 out[NV];
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) {
+                        out[v].x = fmaf(a.alpha, acc[v].x, dstv[t][v].x);
+                        out[v].y = fmaf(a.alpha, acc[v].y, dstv[t][v].y);
+                        out[v].z = fmaf(a.alpha, acc[v].z, dstv[t][v].z);
+                        out[v].w = fmaf(a.alpha, acc[v].w, dstv[t][v].w);
+                    }
+                    store_row<G, NV>(a.dst + (uint64_t)dk * s4, d4, l, out);
+                    clear<NV>(acc);
+                } else if (act == ACT_HEAD || act == ACT_WHOLE) {
+                    store_row<G, NV>(a.prows + (uint64_t)head_slot * s4, d4, l, acc);
+                    head_key = dk;
+                    if (act == ACT_WHOLE) tail_key = dk | KEY_ZERO;
+                    clear<NV>(acc);
+                } else if (act == ACT_TAIL) {
+                    store_row<G, NV>(a.prows + (uint64_t)tail_slot * s4, d4, l, acc);
+                    tail_key = dk;
+                    clear<NV>(acc);
+                }
+            }
+            fetch(i + D, srcv[t], dstv[t]);
+        }
+    }
+    if (l == 0) {
+        if (c > 0) a.pkeys[head_slot] = head_key;
+        if (c + 1 < nchunks) a.pkeys[tail_slot] = tail_key;
+    }
+}
+
 void launch_wseg(const WSideArgs& w, hipStream_t st) {
     if (w.M == 0) return;
     SegArgs a;
     a.src = (const float4*)w.U; a.dst = (float4*)w.W; a.g = w.g; a.skey = w.skey; a.sidx = w.sidx;
     a.in_idx = w.in_idx; a.coeffs = w.coeffs; a.entries = w.M; a.T = w.T;
     a.alpha = w.alpha; a.prows = (float4*)w.prows; a.pkeys = w.pkeys;
-    uint32_t nchunks = (w.M + WSEG_C - 1) / WSEG_C;
+    uint32_t nchunks = (w.M + WOWN_C - 1) / WOWN_C;
 #define CALL(G, NV)                                                                              \
-    hipLaunchKernelGGL((seg_kernel<G, NV, WSEG_C, (NV <= 2 ? 4 : 2), 0>),                        \
+    hipLaunchKernelGGL((wown_kernel<G, NV, (NV <= 2 ? 4 : 2)>),                                   \
                        dim3(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)), dim3(ADJ_THREADS), 0, \
                        st, a)
     W2V_DISPATCH_GEOM(w.g.d4, CALL);
