@@ -22,7 +22,6 @@ constexpr int TAIL_C = 16;     // entries per chunk, higher levels (even, so a b
                                // fall into one chunk)
 constexpr uint32_t NOKEY = 0xFFFFFFFFu;   // compares unequal to every masked key
 
-uint32_t wseg_entries_per_chunk() { return 16; }   // = WOWN_C, the ownership grid
 uint32_t tail_entries_per_chunk() { return TAIL_C; }
 uint32_t useg_pairs_per_chunk(uint32_t T) {     // about 48 entries, 2..16 pairs, <= 136 entries
     uint32_t c = (48 + T - 1) / T;
@@ -172,25 +171,33 @@ __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Output-vector side, level 1, with run ownership.  Chunks of C entries only decide WHO sums a
-// run, not where it is cut: a run that starts in chunk c and ends before the end of chunk c+1
-// ("short", at most 2C entries) is summed entirely by group c, which reads on past its chunk's end
-// and finishes the row with one read-modify-write; the group of chunk c+1 skips those entries.
-// No partial rows are written for short runs, whatever the chunk grid.  A run that reaches chunk
-// c+2 ("long": a frequent word) is cut at every chunk border as in seg_kernel, each chunk leaving
-// its piece in the border slots for the higher levels.  Whether a run is short or long follows
-// from its own extent on the chunk grid, so every group that meets the run decides alike, from the
-// keys at six fixed positions around its chunk.
+// Output-vector side, level 1, with run ownership.  A grid of chunks of C entries only decides WHO
+// sums a run, not where it is cut:
+//  * a run that starts in chunk c and ends before the end of chunk c+1 ("short", at most 2C entries)
+//    is summed entirely by group c, which reads on past its chunk's end and finishes the row with
+//    one read-modify-write; the group of chunk c+1 skips those entries;
+//  * a run that reaches chunk c+2 ("long": a frequent word) is cut only at multiples of L entries
+//    (cells).  Each piece is summed by one group -- the group of the chunk in which the run starts,
+//    or of the chunk at the cell's start -- which streams on through the cell.  A piece that is the
+//    whole run is finished at once; otherwise it is left in the cell's border slots (two per cell
+//    border, as in seg_kernel) for the higher levels.
+// Short or long follows from the run's own extent on the chunk grid, so every group that meets a
+// run decides alike, from the keys at six fixed positions around its chunk.  No partial row is
+// written unless a word collects more than L contributions or so.
 // ---------------------------------------------------------------------------------------------
 constexpr int WOWN_C = 16;
+constexpr int WOWN_L = 128;                  // cell size for long runs, a multiple of C
 constexpr int WOWN_WIN = 3 * WOWN_C + 2;     // keys staged: positions base-C-1 .. base+2C
-constexpr int WOWN_E = 2 * WOWN_C;           // positions a group may sum: base .. base+2C-1
-enum : uint32_t { ACT_SKIP = 0, ACT_ADD = 1, ACT_COMPLETE = 2, ACT_HEAD = 3, ACT_TAIL = 4, ACT_WHOLE = 5 };
+constexpr int WOWN_E = 2 * WOWN_C;           // positions summed from LDS facts: base .. base+2C-1
+enum : uint32_t { ACT_SKIP = 0, ACT_ADD = 1, ACT_COMPLETE = 2, ACT_HEAD = 3 };
+
+uint32_t wseg_entries_per_chunk() { return WOWN_L; }
 
 template <int G, int NV, int D>
 __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
     constexpr int GROUPS = ADJ_THREADS / G;
-    constexpr int C = WOWN_C;
+    constexpr int C = WOWN_C, L = WOWN_L;
+    static_assert(L % C == 0 && C == 16 && G >= 16, "grid shapes");
     __shared__ uint32_t s_key[GROUPS][WOWN_WIN];
     __shared__ uint32_t s_srow[GROUPS][WOWN_E];
     __shared__ float s_coef[GROUPS][WOWN_E];
@@ -209,7 +216,11 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
     const uint32_t kbm = K(-C - 1), kb = K(-1), k0 = K(0), kC = K(C), k2C = K(2 * C), klast = K(C - 1);
     const bool head_exists = active && kb == k0;
     const bool head_long = head_exists && !(kbm != k0 && kC != k0);
-    const bool ext_ok = klast != NOKEY && !(head_exists && klast == k0) && k2C != klast;
+    const bool own_head = head_long && (base % L) == 0;          // a cell begins here: the piece is ours
+    const bool last_in_head = head_exists && klast == k0;
+    const bool ext_ok = klast != NOKEY && !last_in_head && k2C != klast;
+    // does the run through the chunk's last entry go on, as a long piece that this group owns?
+    const bool cont = active && klast != NOKEY && kC == klast && (last_in_head ? own_head : k2C == klast);
     int my_lo = WOWN_E, my_hi = 0;
     for (int i = l; i < WOWN_E; i += G) {
         const uint32_t k = K(i), kn = K(i + 1);
@@ -217,11 +228,11 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
         if (active && k != NOKEY) {
             if (i < C) {
                 if (head_exists && k == k0) {            // a run that came in from the left
-                    if (head_long) act = (kn != k) ? ACT_HEAD : (i == C - 1 ? ACT_WHOLE : ACT_ADD);
+                    if (own_head) act = (kn != k) ? ACT_HEAD : ACT_ADD;
                 } else if (k2C != k) {                   // starts here and is short: ours entirely
                     act = (kn != k) ? ACT_COMPLETE : ACT_ADD;
-                } else {                                 // starts here and is long: our piece of it
-                    act = (i == C - 1) ? ACT_TAIL : ACT_ADD;
+                } else {                                 // starts here and is long: first piece
+                    act = ACT_ADD;
                 }
             } else if (ext_ok && k == klast) {           // the rest of our last short run
                 act = (kn != k) ? ACT_COMPLETE : ACT_ADD;
@@ -242,21 +253,26 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
         my_hi = max(my_hi, __shfl_xor(my_hi, m, 64));
     }
     __syncthreads();
-    if (!active || my_lo >= my_hi) {
-        if (active && l == 0) {
-            if (c > 0) a.pkeys[2 * c - 1] = KEY_NONE;
-            if (c + 1 < nchunks) a.pkeys[2 * c] = KEY_NONE;
-        }
-        return;
-    }
+    if (!active || my_lo >= my_hi) return;
     const int lo = my_lo, hi = my_hi;
     const uint32_t d4 = a.g.d4;
     const uint64_t s4 = a.g.stride4;
-    const uint32_t head_slot = 2 * c - 1, tail_slot = 2 * c;
-    uint32_t head_key = KEY_NONE, tail_key = KEY_NONE;
+    const uint32_t cell = (uint32_t)(base / L);
+    const uint32_t head_slot = 2 * cell - 1, tail_slot = 2 * cell;   // used only when they exist
 
     float4 acc[NV], srcv[D][NV], dstv[D][NV];
     clear<NV>(acc);
+    auto finish_row = [&](uint32_t row, const float4 (&old)[NV]) {
+        float4 out[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            out[v].x = fmaf(a.alpha, acc[v].x, old[v].x);
+            out[v].y = fmaf(a.alpha, acc[v].y, old[v].y);
+            out[v].z = fmaf(a.alpha, acc[v].z, old[v].z);
+            out[v].w = fmaf(a.alpha, acc[v].w, old[v].w);
+        }
+        store_row<G, NV>(a.dst + (uint64_t)row * s4, d4, l, out);
+    };
     auto fetch = [&](int i, float4 (&sv)[NV], float4 (&dv)[NV]) {
         const bool on = i < hi;
         const uint32_t sr = on ? s_srow[grp][i] : 0u;
@@ -273,37 +289,74 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
             const int i = b + t;
             if (i < hi) {
                 const uint32_t act = s_act[grp][i];
-                const uint32_t dk = K(i);
                 axpy<NV>(s_coef[grp][i], srcv[t], acc);
                 if (act == ACT_COMPLETE) {
-                    float4 out[NV];
-#pragma unroll
-                    for (int v = 0; v < NV; ++v) {
-                        out[v].x = fmaf(a.alpha, acc[v].x, dstv[t][v].x);
-                        out[v].y = fmaf(a.alpha, acc[v].y, dstv[t][v].y);
-                        out[v].z = fmaf(a.alpha, acc[v].z, dstv[t][v].z);
-                        out[v].w = fmaf(a.alpha, acc[v].w, dstv[t][v].w);
-                    }
-                    store_row<G, NV>(a.dst + (uint64_t)dk * s4, d4, l, out);
+                    finish_row(K(i), dstv[t]);
                     clear<NV>(acc);
-                } else if (act == ACT_HEAD || act == ACT_WHOLE) {
+                } else if (act == ACT_HEAD) {            // our piece of a long run ends in the chunk
                     store_row<G, NV>(a.prows + (uint64_t)head_slot * s4, d4, l, acc);
-                    head_key = dk;
-                    if (act == ACT_WHOLE) tail_key = dk | KEY_ZERO;
-                    clear<NV>(acc);
-                } else if (act == ACT_TAIL) {
-                    store_row<G, NV>(a.prows + (uint64_t)tail_slot * s4, d4, l, acc);
-                    tail_key = dk;
+                    if (l == 0) a.pkeys[head_slot] = K(i);
                     clear<NV>(acc);
                 }
             }
             fetch(i + D, srcv[t], dstv[t]);
         }
     }
-    if (l == 0) {
-        if (c > 0) a.pkeys[head_slot] = head_key;
-        if (c + 1 < nchunks) a.pkeys[tail_slot] = tail_key;
+    if (!cont) return;
+
+    // ---- the long piece goes on past the chunk: stream through the rest of the cell ----
+    const uint32_t key = klast;
+    const int64_t limit = min((int64_t)(cell + 1) * L, (int64_t)a.entries);
+    const int group_lane0 = ((int)(threadIdx.x & 63) / G) * G;
+    bool ended = false;
+    for (int64_t x0 = base + C; x0 < limit; x0 += 16) {
+        const int nblk = (int)min((int64_t)16, limit - x0);
+        const bool same = l < nblk && a.skey[x0 + l] == key;
+        const uint32_t bits = (uint32_t)(__ballot(same) >> group_lane0) & 0xFFFFu;
+        const int cnt = __builtin_ctz(~bits);             // entries of the run at the block's front
+        uint32_t sr = 0;
+        float cf = 0.f;
+        if (l < cnt) {
+            const uint32_t q = a.sidx[x0 + l];
+            sr = a.in_idx[q / a.T];
+            cf = a.coeffs[q];
+        }
+#pragma unroll
+        for (int b = 0; b < 16; b += D) {
+            if (b < cnt) {
+#pragma unroll
+                for (int t = 0; t < D; ++t)
+                    load_row_if<G, NV>(b + t < cnt, a.src + (uint64_t)__shfl(sr, b + t, G) * s4, d4, l,
+                                       srcv[t]);
+#pragma unroll
+                for (int t = 0; t < D; ++t) axpy<NV>(__shfl(cf, b + t, G), srcv[t], acc);
+            }
+        }
+        if (cnt < nblk) { ended = true; break; }
     }
+    if (!ended) ended = limit >= (int64_t)a.entries || a.skey[limit] != key;
+    if (!last_in_head) {
+        if (ended) {                                      // the whole run lay inside the cell
+            float4 old[NV];
+            load_row<G, NV>(a.dst + (uint64_t)key * s4, d4, l, old);
+            finish_row(key, old);
+        } else {                                          // first piece of a run that leaves the cell
+            store_row<G, NV>(a.prows + (uint64_t)tail_slot * s4, d4, l, acc);
+            if (l == 0) a.pkeys[tail_slot] = key;
+        }
+    } else {                                              // a piece that began at the cell's start
+        store_row<G, NV>(a.prows + (uint64_t)head_slot * s4, d4, l, acc);
+        if (l == 0) {
+            a.pkeys[head_slot] = key;
+            if (!ended) a.pkeys[tail_slot] = key | KEY_ZERO;   // the run fills the cell and goes on
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ x, uint32_t n,
+                                                       uint32_t value) {
+    uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) x[i] = value;
 }
 
 void launch_wseg(const WSideArgs& w, hipStream_t st) {
@@ -312,6 +365,12 @@ void launch_wseg(const WSideArgs& w, hipStream_t st) {
     a.src = (const float4*)w.U; a.dst = (float4*)w.W; a.g = w.g; a.skey = w.skey; a.sidx = w.sidx;
     a.in_idx = w.in_idx; a.coeffs = w.coeffs; a.entries = w.M; a.T = w.T;
     a.alpha = w.alpha; a.prows = (float4*)w.prows; a.pkeys = w.pkeys;
+    // border slots of the cells: only pieces of long runs write them
+    uint32_t ncells = (w.M + WOWN_L - 1) / WOWN_L;
+    uint32_t slots = 2 * (ncells - 1);
+    if (slots)
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(slots, 256)), dim3(256), 0, st, w.pkeys,
+                           slots, KEY_NONE);
     uint32_t nchunks = (w.M + WOWN_C - 1) / WOWN_C;
 #define CALL(G, NV)                                                                              \
     hipLaunchKernelGGL((wown_kernel<G, NV, (NV <= 2 ? 4 : 2)>),                                   \
