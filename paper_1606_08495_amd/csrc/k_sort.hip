@@ -112,8 +112,8 @@ void launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32
 // Radix sort pass.  A block owns a tile of 256 x 8 consecutive elements; wave w of the block owns
 // the w-th quarter of the tile and walks it in order, 64 elements at a time.
 //   histogram : per-block digit counts, stored digit-major [256][blocks]
-//   (scan of that array gives, for every (digit, block), where the block's elements of that digit
-//    start in the output)
+//   digit scan: per digit, exclusive prefix of its counts over the blocks, and the digit's total
+//   (prefix of the totals + that prefix = where a block's elements of a digit start in the output)
 //   scatter   : each element's position = that start + its rank among the block's elements with
 //               the same digit, counted in tile order -> stable.
 // ---------------------------------------------------------------------------------------------
@@ -143,9 +143,13 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_hist_kernel(const uint32_t*
 __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
     uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, uint32_t n, uint32_t shift,
-    uint32_t nblocks, const uint32_t* __restrict__ offsets) {
+    uint32_t nblocks, const uint32_t* __restrict__ offsets, const uint32_t* __restrict__ digit_total) {
     __shared__ uint32_t cnt[SORT_WAVES][256];
+    __shared__ uint32_t wave_sums[4];
+    __shared__ uint32_t total_all;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // where each digit's elements start in the output: exclusive scan of the 256 digit totals
+    const uint32_t digit_base = block_exclusive_scan(digit_total[threadIdx.x], wave_sums, &total_all);
 #pragma unroll
     for (int w = 0; w < SORT_WAVES; ++w) cnt[w][threadIdx.x] = 0;
     __syncthreads();
@@ -181,7 +185,7 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     __syncthreads();
     {   // thread t owns digit t: turn per-wave counts into per-wave starts in the output
         uint32_t d = threadIdx.x;
-        uint32_t run = offsets[(uint64_t)d * nblocks + blockIdx.x];
+        uint32_t run = digit_base + offsets[(uint64_t)d * nblocks + blockIdx.x];
 #pragma unroll
         for (int w = 0; w < SORT_WAVES; ++w) {
             uint32_t c = cnt[w][d];
@@ -202,10 +206,30 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     }
 }
 
+// Block d turns the per-block counts of digit d into exclusive prefixes over the blocks (in place)
+// and writes the digit's total.
+__global__ __launch_bounds__(SCAN_THREADS) void sort_digit_scan_kernel(uint32_t* __restrict__ hist,
+                                                                       uint32_t nblocks,
+                                                                       uint32_t* __restrict__ digit_total) {
+    __shared__ uint32_t wave_sums[4];
+    __shared__ uint32_t total;
+    uint32_t* row = hist + (uint64_t)blockIdx.x * nblocks;
+    uint32_t carry = 0;
+    for (uint32_t start = 0; start < nblocks; start += SCAN_THREADS) {
+        uint32_t i = start + threadIdx.x;
+        uint32_t x = i < nblocks ? row[i] : 0u;
+        uint32_t ex = block_exclusive_scan(x, wave_sums, &total);
+        if (i < nblocks) row[i] = carry + ex;
+        carry += total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) digit_total[blockIdx.x] = carry;
+}
+
 size_t sort_scratch_u32(uint32_t n) {
     uint32_t nblocks = blocks_for(n, SORT_TILE);
     uint32_t hist = 256u * (nblocks ? nblocks : 1u);
-    return (size_t)hist + scan_scratch_u32(hist) + 8;
+    return (size_t)hist + 256 + 8;
 }
 
 void launch_sort_pairs(const uint32_t* keys_in, uint32_t* k0, uint32_t* v0, uint32_t* k1, uint32_t* v1,
@@ -216,7 +240,7 @@ void launch_sort_pairs(const uint32_t* keys_in, uint32_t* k0, uint32_t* v0, uint
     uint32_t nblocks = blocks_for(n, SORT_TILE);
     uint32_t hist_len = 256u * nblocks;
     uint32_t* hist = tmp;
-    uint32_t* scan_tmp = tmp + hist_len;
+    uint32_t* digit_total = tmp + hist_len;
     *out_keys = k0;
     *out_vals = v0;
     if (n == 0) return;
@@ -227,9 +251,10 @@ void launch_sort_pairs(const uint32_t* keys_in, uint32_t* k0, uint32_t* v0, uint
         uint32_t shift = ps * 8;
         hipLaunchKernelGGL(sort_hist_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, st, kin, n,
                            shift, nblocks, hist);
-        launch_exclusive_scan(hist, hist, hist_len, scan_tmp, nullptr, st);
+        hipLaunchKernelGGL(sort_digit_scan_kernel, dim3(256), dim3(SCAN_THREADS), 0, st, hist,
+                           nblocks, digit_total);
         hipLaunchKernelGGL(sort_scatter_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, st, kin, vin,
-                           kout, vout, n, shift, nblocks, hist);
+                           kout, vout, n, shift, nblocks, hist, digit_total);
         *out_keys = kout;
         *out_vals = vout;
         kin = kout; vin = vout;
