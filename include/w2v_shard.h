@@ -144,6 +144,18 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
                    uint64_t corpus_seed, uint32_t B, uint32_t* in_idx_dev, uint32_t* out_idx_dev,
                    uint64_t capacity, uint64_t* n_pairs_host, void* stream);
 
+/* ---- interleaved minibatch formation (Section 5.1, last paragraph) -------------------------------
+ * Same arguments and the same set of pairs as w2v_make_pairs, in another order: the centers are
+ * visited round-robin over the sentences of the block -- every sentence's first surviving token (in
+ * sentence order), then every sentence's second, ... -- so that a minibatch cut from the pair stream
+ * takes its input words from many different sentences, and the input words of one sentence fall
+ * into successive minibatches.  Contexts of a center keep their order. */
+int w2v_make_pairs_interleaved(w2v_shard* shard, const uint32_t* tokens_dev,
+                               const uint64_t* sent_off_dev, uint32_t n_sent, uint32_t n_tokens,
+                               uint64_t token_base, uint32_t epoch, uint64_t corpus_seed,
+                               uint32_t B, uint32_t* in_idx_dev, uint32_t* out_idx_dev,
+                               uint64_t capacity, uint64_t* n_pairs_host, void* stream);
+
 /* Seed of minibatch number h (the client picks a fresh seed per minibatch), a function of a master seed. */
 uint64_t w2v_minibatch_seed(uint64_t master_seed, uint64_t h);
 

@@ -35,6 +35,7 @@ def lib():
         L.orc_minibatch_seed.restype = ctypes.c_uint64
         L.orc_minibatch_seed.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
         L.orc_make_pairs.restype = ctypes.c_uint64
+        L.orc_make_pairs_interleaved.restype = ctypes.c_uint64
         L.orc_lazy_create.restype = ctypes.c_void_p
         L.orc_lazy_rows_held.restype = ctypes.c_uint64
         _lib = L
@@ -218,7 +219,8 @@ class LazyShard:
         return loss.value
 
 
-def make_pairs(tokens, sent_off, token_base, epoch, corpus_seed, B, keep_thresh, capacity=None):
+def make_pairs(tokens, sent_off, token_base, epoch, corpus_seed, B, keep_thresh, capacity=None,
+               interleaved=False):
     tokens = _u32(tokens)
     sent_off = np.ascontiguousarray(sent_off, dtype=np.uint64)
     kt = None if keep_thresh is None else np.ascontiguousarray(keep_thresh, dtype=np.uint64)
@@ -226,9 +228,9 @@ def make_pairs(tokens, sent_off, token_base, epoch, corpus_seed, B, keep_thresh,
         capacity = int(tokens.size) * 2 * B
     a = np.empty(capacity, np.uint32)
     b = np.empty(capacity, np.uint32)
-    cnt = lib().orc_make_pairs(_p(tokens), _p(sent_off), U64(sent_off.size - 1), U64(token_base),
-                               U32(epoch), U64(corpus_seed), U32(B), _p(kt), _p(a), _p(b),
-                               U64(capacity))
+    fn = lib().orc_make_pairs_interleaved if interleaved else lib().orc_make_pairs
+    cnt = fn(_p(tokens), _p(sent_off), U64(sent_off.size - 1), U64(token_base), U32(epoch),
+             U64(corpus_seed), U32(B), _p(kt), _p(a), _p(b), U64(capacity))
     cnt = int(cnt)
     m = min(cnt, capacity)
     return a[:m].copy(), b[:m].copy(), cnt

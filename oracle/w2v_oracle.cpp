@@ -25,6 +25,7 @@
 // invariant; chi-square of the sampler; alias-table reconstruction; window / subsample laws.
 // Nothing in this file is "parity unpinned".
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -445,6 +446,47 @@ uint64_t orc_make_pairs(const uint32_t* tokens, const uint64_t* sent_off, uint64
                 if (count < capacity) { in_idx[count] = kept_word[j]; out_idx[count] = kept_word[c]; }
                 ++count;
             }
+        }
+    }
+    return count;
+}
+
+// Interleaved minibatch formation (Section 5.1, last paragraph: an option that keeps the input words
+// of one minibatch far apart in the corpus, ideally in different sentences).  Reading taken here:
+// the same pairs as orc_make_pairs, but the centers are visited round-robin over the sentences of
+// the token block -- first every sentence's first surviving token (in sentence order), then every
+// sentence's second, and so on -- so that a minibatch cut from the pair stream takes at most a few
+// centers from any one sentence.  The contexts of a center keep their order.
+uint64_t orc_make_pairs_interleaved(const uint32_t* tokens, const uint64_t* sent_off,
+                                    uint64_t n_sent, uint64_t token_base, uint32_t epoch,
+                                    uint64_t corpus_seed, uint32_t B, const uint64_t* keep_thresh,
+                                    uint32_t* in_idx, uint32_t* out_idx, uint64_t capacity) {
+    struct Center { uint64_t sentence; int64_t j; };
+    std::vector<std::vector<uint32_t>> words(n_sent), widths(n_sent);
+    std::vector<Center> centers;
+    for (uint64_t s = 0; s < n_sent; ++s) {
+        for (uint64_t t = sent_off[s]; t < sent_off[s + 1]; ++t) {
+            uint64_t g = token_base + t;
+            Quad q = philox((uint32_t)g, (uint32_t)(g >> 32), epoch, DOMAIN_TOKEN, corpus_seed);
+            uint32_t w = tokens[t];
+            bool keep = keep_thresh ? ((uint64_t)q.r[0] < keep_thresh[w]) : true;
+            if (!keep) continue;
+            centers.push_back(Center{s, (int64_t)words[s].size()});
+            words[s].push_back(w);
+            widths[s].push_back(1 + (uint32_t)(((uint64_t)q.r[1] * (uint64_t)B) >> 32));
+        }
+    }
+    // by position within the sentence; sentences stay in order among equal positions
+    std::stable_sort(centers.begin(), centers.end(),
+                     [](const Center& a, const Center& b) { return a.j < b.j; });
+    uint64_t count = 0;
+    for (const Center& ce : centers) {
+        const std::vector<uint32_t>& sw = words[ce.sentence];
+        int64_t m = (int64_t)sw.size(), j = ce.j, b = (int64_t)widths[ce.sentence][j];
+        for (int64_t c = j - b; c <= j + b; ++c) {
+            if (c == j || c < 0 || c >= m) continue;
+            if (count < capacity) { in_idx[count] = sw[j]; out_idx[count] = sw[c]; }
+            ++count;
         }
     }
     return count;

@@ -662,11 +662,10 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
 // ---------------------------------------------------------------------------------------------
 // pair formation
 // ---------------------------------------------------------------------------------------------
-extern "C" int w2v_make_pairs(w2v_shard* sh, const uint32_t* tokens, const uint64_t* sent_off,
-                              uint32_t n_sent, uint32_t n_tokens, uint64_t token_base,
-                              uint32_t epoch, uint64_t corpus_seed, uint32_t B, uint32_t* in_idx,
-                              uint32_t* out_idx, uint64_t capacity, uint64_t* n_pairs,
-                              void* stream) {
+static int make_pairs_impl(w2v_shard* sh, const uint32_t* tokens, const uint64_t* sent_off,
+                           uint32_t n_sent, uint32_t n_tokens, uint64_t token_base, uint32_t epoch,
+                           uint64_t corpus_seed, uint32_t B, uint32_t* in_idx, uint32_t* out_idx,
+                           uint64_t capacity, uint64_t* n_pairs, bool interleave, void* stream) {
     if (!sh || !n_pairs) return fail(W2V_ERR_NULL, "NULL argument");
     *n_pairs = 0;
     if (n_tokens && (!tokens || !sent_off)) return fail(W2V_ERR_NULL, "NULL argument");
@@ -679,14 +678,14 @@ extern "C" int w2v_make_pairs(w2v_shard* sh, const uint32_t* tokens, const uint6
     if (rc) return rc;
     if (n_tokens == 0) return W2V_OK;
     hipStream_t st = (hipStream_t)stream;
-    size_t need = sizeof(uint32_t) * (pairs_scratch_u32(n_tokens) + 64) + 512;
+    size_t need = sizeof(uint32_t) * (pairs_scratch_u32(n_tokens, interleave) + 64) + 512;
     rc = ensure_ws(sh, need);
     if (rc) return rc;
     PairArgs a{};
     a.tokens = tokens; a.sent_off = sent_off; a.n_sent = n_sent; a.n_tokens = n_tokens;
     a.token_base = token_base; a.epoch = epoch; a.seed = corpus_seed; a.B = B;
     a.keep = sh->has_tables ? sh->keep : nullptr; a.V = sh->V;
-    a.in_idx = in_idx; a.out_idx = out_idx; a.capacity = capacity;
+    a.in_idx = in_idx; a.out_idx = out_idx; a.capacity = capacity; a.interleave = interleave;
     a.total_pairs = (uint32_t*)sh->ws;
     a.scratch = (uint32_t*)sh->ws + 64;
     a.err = sh->err;
@@ -700,6 +699,25 @@ extern "C" int w2v_make_pairs(w2v_shard* sh, const uint32_t* tokens, const uint6
     HIP_TRY(hipStreamSynchronize(st));
     *n_pairs = total;
     return W2V_OK;
+}
+
+extern "C" int w2v_make_pairs(w2v_shard* sh, const uint32_t* tokens, const uint64_t* sent_off,
+                              uint32_t n_sent, uint32_t n_tokens, uint64_t token_base,
+                              uint32_t epoch, uint64_t corpus_seed, uint32_t B, uint32_t* in_idx,
+                              uint32_t* out_idx, uint64_t capacity, uint64_t* n_pairs,
+                              void* stream) {
+    return make_pairs_impl(sh, tokens, sent_off, n_sent, n_tokens, token_base, epoch, corpus_seed,
+                           B, in_idx, out_idx, capacity, n_pairs, false, stream);
+}
+
+extern "C" int w2v_make_pairs_interleaved(w2v_shard* sh, const uint32_t* tokens,
+                                          const uint64_t* sent_off, uint32_t n_sent,
+                                          uint32_t n_tokens, uint64_t token_base, uint32_t epoch,
+                                          uint64_t corpus_seed, uint32_t B, uint32_t* in_idx,
+                                          uint32_t* out_idx, uint64_t capacity, uint64_t* n_pairs,
+                                          void* stream) {
+    return make_pairs_impl(sh, tokens, sent_off, n_sent, n_tokens, token_base, epoch, corpus_seed,
+                           B, in_idx, out_idx, capacity, n_pairs, true, stream);
 }
 
 extern "C" uint64_t w2v_minibatch_seed(uint64_t master_seed, uint64_t h) {

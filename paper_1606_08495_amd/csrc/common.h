@@ -147,11 +147,12 @@ struct PairArgs {
     const uint32_t* tokens; const uint64_t* sent_off; uint32_t n_sent; uint32_t n_tokens;
     uint64_t token_base; uint32_t epoch; uint64_t seed; uint32_t B; const uint64_t* keep; uint32_t V;
     uint32_t* in_idx; uint32_t* out_idx; uint64_t capacity;
-    uint32_t* scratch;      // pairs_scratch_u32(n_tokens) uint32
+    bool interleave;        // centers round-robin over the sentences instead of corpus order
+    uint32_t* scratch;      // pairs_scratch_u32(n_tokens, interleave) uint32
     uint32_t* total_pairs;  // device, one uint32
     uint32_t* err;
 };
-size_t pairs_scratch_u32(uint32_t n_tokens);
+size_t pairs_scratch_u32(uint32_t n_tokens, bool interleave);
 void launch_make_pairs(const PairArgs& a, hipStream_t st);
 
 }  // namespace w2v

@@ -45,7 +45,8 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint32_t* __restrict
                                                       uint32_t V, uint32_t* __restrict__ kword,
                                                       uint32_t* __restrict__ klo,
                                                       uint32_t* __restrict__ khi,
-                                                      uint32_t* __restrict__ kcnt) {
+                                                      uint32_t* __restrict__ kcnt,
+                                                      uint32_t* __restrict__ kj) {
     uint32_t t = blockIdx.x * 256 + threadIdx.x;
     if (t >= n_tokens || !flag[t]) return;
     // sentence of t: the last s with sent_off[s] <= t
@@ -66,11 +67,24 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint32_t* __restrict
     klo[q] = q - left;
     khi[q] = q + right;
     kcnt[q] = left + right;
+    if (kj) kj[q] = j;                        // position among the sentence's survivors
 }
 
-__global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ x, uint32_t n) {
+__global__ __launch_bounds__(256) void set_u32_kernel(uint32_t* __restrict__ x, uint32_t n,
+                                                      uint32_t value) {
     uint32_t i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) x[i] = 0u;
+    if (i < n) x[i] = value;
+}
+
+// Interleaved order: pair counts of the survivors taken in the order perm[0], perm[1], ...
+__global__ __launch_bounds__(256) void permuted_counts_kernel(const uint32_t* __restrict__ kcnt,
+                                                              const uint32_t* __restrict__ perm,
+                                                              const uint32_t* __restrict__ n_kept,
+                                                              uint32_t n,
+                                                              uint32_t* __restrict__ out) {
+    uint32_t r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= n) return;
+    out[r] = r < *n_kept ? kcnt[perm[r]] : 0u;
 }
 
 __global__ __launch_bounds__(256) void emit_pairs_kernel(const uint32_t* __restrict__ kword,
@@ -78,13 +92,15 @@ __global__ __launch_bounds__(256) void emit_pairs_kernel(const uint32_t* __restr
                                                          const uint32_t* __restrict__ khi,
                                                          const uint32_t* __restrict__ poff,
                                                          const uint32_t* __restrict__ n_kept,
+                                                         const uint32_t* __restrict__ perm,
                                                          uint32_t* __restrict__ in_idx,
                                                          uint32_t* __restrict__ out_idx,
                                                          uint64_t capacity) {
-    uint32_t q = blockIdx.x * 256 + threadIdx.x;
-    if (q >= *n_kept) return;
+    uint32_t r = blockIdx.x * 256 + threadIdx.x;        // place in the order of emission
+    if (r >= *n_kept) return;
+    uint32_t q = perm ? perm[r] : r;                      // which survivor is the center
     uint32_t w = kword[q];
-    uint64_t o = poff[q];
+    uint64_t o = poff[r];
     uint32_t last = khi[q] < *n_kept ? khi[q] : *n_kept - 1;   // holds for well-formed sentences
     for (uint32_t c = klo[q]; c <= last; ++c) {
         if (c == q) continue;
@@ -94,10 +110,12 @@ __global__ __launch_bounds__(256) void emit_pairs_kernel(const uint32_t* __restr
 }
 
 // scratch layout (uint32): flag[n+1] kpos[n+1] width[n] kword[n] klo[n] khi[n] kcnt[n] poff[n]
-// n_kept[1] scan_tmp[...]
-size_t pairs_scratch_u32(uint32_t n_tokens) {
+// n_kept[8] scan_tmp[...]; interleaved order adds kj[n] cs[n] k0[n] v0[n] k1[n] v1[n] sort_tmp[...]
+size_t pairs_scratch_u32(uint32_t n_tokens, bool interleave) {
     size_t n = n_tokens;
-    return 2 * (n + 1) + 6 * n + 8 + scan_scratch_u32(n_tokens + 1);
+    size_t base = 2 * (n + 1) + 6 * n + 8 + scan_scratch_u32(n_tokens + 1);
+    if (interleave) base += 6 * n + sort_scratch_u32(n_tokens ? n_tokens : 1);
+    return base;
 }
 
 void launch_make_pairs(const PairArgs& a, hipStream_t st) {
@@ -112,20 +130,37 @@ void launch_make_pairs(const PairArgs& a, hipStream_t st) {
     uint32_t* poff = kcnt + n;
     uint32_t* n_kept = poff + n;
     uint32_t* scan_tmp = n_kept + 8;
+    uint32_t* extra = scan_tmp + scan_scratch_u32(n + 1);
+    uint32_t* kj = a.interleave ? extra : nullptr;
+    uint32_t* cs = extra + n;
+    uint32_t *k0 = cs + n, *v0 = k0 + n, *k1 = v0 + n, *v1 = k1 + n, *sort_tmp = v1 + n;
     hipLaunchKernelGGL(token_draws_kernel, dim3(blocks_for((uint64_t)n + 1, 256)), dim3(256), 0, st,
                        a.tokens, n, a.token_base, a.epoch, (uint32_t)a.seed,
                        (uint32_t)(a.seed >> 32), a.B, a.keep, a.V, flag, width, a.err);
     launch_exclusive_scan(flag, kpos, n + 1, scan_tmp, n_kept, st);
     // pair counts of the survivors; entries of kcnt beyond n_kept must read as zero for the scan
-    if (n > 0)
-        hipLaunchKernelGGL(zero_u32_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, kcnt, n);
-    if (n > 0)
-        hipLaunchKernelGGL(compact_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, a.tokens, n,
-                           a.sent_off, a.n_sent, flag, kpos, width, a.V, kword, klo, khi, kcnt);
-    launch_exclusive_scan(kcnt, poff, n, scan_tmp, a.total_pairs, st);
-    if (n > 0)
-        hipLaunchKernelGGL(emit_pairs_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, kword, klo,
-                           khi, poff, n_kept, a.in_idx, a.out_idx, a.capacity);
+    if (n == 0) { launch_exclusive_scan(kcnt, poff, 0, scan_tmp, a.total_pairs, st); return; }
+    const dim3 grid(blocks_for(n, 256)), block(256);
+    hipLaunchKernelGGL(set_u32_kernel, grid, block, 0, st, kcnt, n, 0u);
+    if (a.interleave) hipLaunchKernelGGL(set_u32_kernel, grid, block, 0, st, kj, n, n);   // sorts last
+    hipLaunchKernelGGL(compact_kernel, grid, block, 0, st, a.tokens, n, a.sent_off, a.n_sent, flag,
+                       kpos, width, a.V, kword, klo, khi, kcnt, kj);
+    if (!a.interleave) {
+        launch_exclusive_scan(kcnt, poff, n, scan_tmp, a.total_pairs, st);
+        hipLaunchKernelGGL(emit_pairs_kernel, grid, block, 0, st, kword, klo, khi, poff, n_kept,
+                           (const uint32_t*)nullptr, a.in_idx, a.out_idx, a.capacity);
+        return;
+    }
+    // Round-robin over the sentences: a stable sort of the survivors by their position within the
+    // sentence keeps the sentences in order among equal positions.
+    uint32_t bits = 1;
+    while (bits < 32 && (1ull << bits) <= (uint64_t)n) ++bits;
+    uint32_t *sk = nullptr, *perm = nullptr;
+    launch_sort_pairs(kj, k0, v0, k1, v1, n, bits, sort_tmp, &sk, &perm, st);
+    hipLaunchKernelGGL(permuted_counts_kernel, grid, block, 0, st, kcnt, perm, n_kept, n, cs);
+    launch_exclusive_scan(cs, poff, n, scan_tmp, a.total_pairs, st);
+    hipLaunchKernelGGL(emit_pairs_kernel, grid, block, 0, st, kword, klo, khi, poff, n_kept,
+                       (const uint32_t*)perm, a.in_idx, a.out_idx, a.capacity);
 }
 
 }  // namespace w2v

@@ -38,6 +38,9 @@ _SIGNATURES = {
                                            c_u64, ctypes.c_float, c_vp, c_vp]),
     "w2v_make_pairs": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_u32, c_u64, c_u32,
                                       c_vp, c_vp, c_u64, ctypes.POINTER(c_u64), c_vp]),
+    "w2v_make_pairs_interleaved": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_u32, c_u64,
+                                                  c_u32, c_vp, c_vp, c_u64, ctypes.POINTER(c_u64),
+                                                  c_vp]),
     "w2v_minibatch_seed": (c_u64, [c_u64, c_u64]),
     "w2v_shard_timing_enable": (ctypes.c_int, [c_vp, ctypes.c_int]),
     "w2v_shard_timing_read": (ctypes.c_int, [c_vp, c_vp, c_vp]),
@@ -196,11 +199,13 @@ class Shard:
                                 float(alpha), _stream(stream)))
 
     def make_pairs(self, tokens, sent_off, token_base, epoch, corpus_seed, B, in_idx, out_idx,
-                   stream=None):
+                   stream=None, interleaved=False):
         """tokens int32[n] (uint32 bits), sent_off int64[m+1] on the device; fills in_idx/out_idx
-        (capacity = their length) and returns the full pair count."""
+        (capacity = their length) and returns the full pair count.  ``interleaved`` calls
+        w2v_make_pairs_interleaved instead of w2v_make_pairs."""
         cnt = c_u64(0)
-        _check(lib().w2v_make_pairs(self.h, _dev(tokens, IDX, "tokens"),
+        fn = lib().w2v_make_pairs_interleaved if interleaved else lib().w2v_make_pairs
+        _check(fn(self.h, _dev(tokens, IDX, "tokens"),
                                     _dev(sent_off, torch.int64, "sent_off"), sent_off.numel() - 1,
                                     tokens.numel(), int(token_base), int(epoch), int(corpus_seed),
                                     int(B), _dev(in_idx, IDX, "in_idx"), _dev(out_idx, IDX, "out_idx"),

@@ -385,6 +385,45 @@ def test_make_pairs_bit_exact(B, t):
     sh.destroy()
 
 
+@pytest.mark.parametrize("B,t,n_tok,n_sent", [(1, 0.0, 5_000, 600), (5, 1e-3, 20_011, 2000),
+                                              (4, 1e-2, 70_001, 90), (3, 1e9, 3, 1)])
+def test_make_pairs_interleaved_bit_exact(B, t, n_tok, n_sent):
+    rng = np.random.default_rng(100 + B)
+    V = 300
+    tokens = workloads.zipf_draw(workloads.zipf_cdf(V, 1.0), n_tok, rng)
+    counts = workloads.counted(tokens, V)
+    lens = rng.integers(0, 2 * max(1, n_tok // n_sent) + 2, n_sent)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    off = np.append(off[off < n_tok], n_tok).astype(np.uint64)
+    sh = make_shard(V, 4, 1, counts, t)
+    kt = oracle.build_keep(counts, t) if t > 0 else None
+    base = (1 << 34) + 777
+    cap = n_tok * 2 * B
+    doff = torch.from_numpy(off.astype(np.int64)).cuda()
+    gi = torch.empty(cap, dtype=torch.int32, device="cuda")
+    go = torch.empty(cap, dtype=torch.int32, device="cuda")
+    cnt = sh.make_pairs(dev(tokens), doff, base, 2, 5, B, gi, go, interleaved=True)
+    oi, oo, ocnt = oracle.make_pairs(tokens, off, base, 2, 5, B, kt, interleaved=True)
+    assert cnt == ocnt
+    assert np.array_equal(w2v.index_to_numpy(gi[:cnt]), oi)
+    assert np.array_equal(w2v.index_to_numpy(go[:cnt]), oo)
+    # the plain order is unchanged by a call of the other entry point on the same shard
+    cnt0 = sh.make_pairs(dev(tokens), doff, base, 2, 5, B, gi, go)
+    pi, po, pcnt = oracle.make_pairs(tokens, off, base, 2, 5, B, kt)
+    assert cnt0 == pcnt and np.array_equal(w2v.index_to_numpy(gi[:cnt0]), pi)
+    assert np.array_equal(w2v.index_to_numpy(go[:cnt0]), po)
+    # a short output holds the first pairs of the interleaved order
+    m = min(500, max(1, cnt // 2))
+    gi2 = torch.empty(m, dtype=torch.int32, device="cuda")
+    go2 = torch.empty(m, dtype=torch.int32, device="cuda")
+    cnt2 = sh.make_pairs(dev(tokens), doff, base, 2, 5, B, gi2, go2, interleaved=True)
+    k = min(m, cnt)
+    assert cnt2 == cnt and np.array_equal(w2v.index_to_numpy(gi2)[:k], oi[:k])
+    assert np.array_equal(w2v.index_to_numpy(go2)[:k], oo[:k])
+    sh.status()
+    sh.destroy()
+
+
 # --- errors are reported, never faults -------------------------------------------------------------------
 
 def test_argument_errors():

@@ -231,6 +231,53 @@ def test_T11_window_one_without_subsampling_gives_adjacent_tokens():
     assert cnt == len(want) and list(zip(a.tolist(), b.tolist())) == want
 
 
+def test_T11_interleaved_order_on_a_hand_case():
+    # Section 5.1, last paragraph: centers are taken round-robin over the sentences.  Sentences of
+    # 4, 1 and 5 tokens, window 1, no subsampling: first tokens 0 and 5 (the one-word sentence has
+    # no pair), second tokens 1 and 6, third 2 and 7, fourth 3 and 8, and 9 alone at the end.
+    tokens = np.arange(10, dtype=np.uint32)
+    off = np.array([0, 4, 5, 10], np.uint64)
+    a, b, cnt = oracle.make_pairs(tokens, off, 0, 0, 1, 1, None, interleaved=True)
+    want = [(0, 1), (5, 6), (1, 0), (1, 2), (6, 5), (6, 7), (2, 1), (2, 3), (7, 6), (7, 8),
+            (3, 2), (8, 7), (8, 9), (9, 8)]
+    assert cnt == len(want) and list(zip(a.tolist(), b.tolist())) == want
+
+
+def test_T11_interleaved_is_a_reordering_with_centers_round_robin():
+    rng = np.random.default_rng(113)
+    V, n = 5000, 4000
+    tokens = rng.permutation(V)[:n].astype(np.uint32)     # distinct words: a pair names its positions
+    lens = rng.integers(0, 30, 400)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    off = np.append(off[off < n], n).astype(np.uint64)
+    kt = np.full(V, int(0.7 * 2 ** 32), np.uint64)
+    for B in (1, 4):
+        a0, b0, c0 = oracle.make_pairs(tokens, off, 77, 1, 9, B, kt)
+        a1, b1, c1 = oracle.make_pairs(tokens, off, 77, 1, 9, B, kt, interleaved=True)
+        assert c0 == c1
+        key0 = a0.astype(np.uint64) << 32 | b0
+        key1 = a1.astype(np.uint64) << 32 | b1
+        assert np.array_equal(np.sort(key0), np.sort(key1)) and not np.array_equal(key0, key1)
+        # rank of every word among its sentence's survivors, and its sentence, from the draws
+        keep, _ = oracle.token_draws(tokens, 77, 1, 9, B, kt)
+        sent = np.searchsorted(off, np.arange(n), side="right") - 1
+        rank = np.zeros(V, np.int64)
+        sent_of = np.zeros(V, np.int64)
+        for s in range(off.size - 1):
+            pos = [t for t in range(int(off[s]), int(off[s + 1])) if keep[t]]
+            for j, t in enumerate(pos):
+                rank[tokens[t]], sent_of[tokens[t]] = j, s
+        order = rank[a1] * (off.size + 1) + sent_of[a1]
+        assert np.all(np.diff(order) >= 0)                # by rank, then by sentence
+        # contexts of one center stay in corpus order, as in the plain walk
+        for w in rng.choice(np.unique(a1), 50, replace=False):
+            assert np.array_equal(b1[a1 == w], b0[a0 == w])
+        # the truncated call returns a prefix of the full one
+        a2, _, c2 = oracle.make_pairs(tokens, off, 77, 1, 9, B, kt, capacity=37, interleaved=True)
+        assert c2 == c1 and np.array_equal(a2, a1[:37])
+        assert sent.max() == off.size - 2
+
+
 def test_T11_pair_count_is_the_sum_of_clipped_windows_and_no_pair_crosses_a_sentence():
     rng = np.random.default_rng(112)
     n, L, B = 3000, 15, 4
