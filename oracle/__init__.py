@@ -36,6 +36,7 @@ def lib():
         L.orc_minibatch_seed.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
         L.orc_make_pairs.restype = ctypes.c_uint64
         L.orc_make_pairs_interleaved.restype = ctypes.c_uint64
+        L.orc_make_cbow_examples.restype = ctypes.c_uint64
         L.orc_lazy_create.restype = ctypes.c_void_p
         L.orc_lazy_rows_held.restype = ctypes.c_uint64
         _lib = L
@@ -244,3 +245,79 @@ def token_draws(tokens, token_base, epoch, corpus_seed, B, keep_thresh):
     lib().orc_token_draws(_p(tokens), U64(tokens.size), U64(token_base), U32(epoch),
                           U64(corpus_seed), U32(B), _p(kt), _p(keep), _p(b))
     return keep, b
+
+
+# --- continuous bag of words ------------------------------------------------------------------------
+
+def cbow_dots(U, W, ctx_off, ctx_idx, rows):
+    U, W, ctx_off, ctx_idx, rows = _f32(U), _f32(W), _u32(ctx_off), _u32(ctx_idx), _u32(rows)
+    n, T = rows.shape
+    out = np.empty((n, T), np.float32)
+    lib().orc_cbow_dots(_p(U), _p(W), U32(U.shape[1]), _p(ctx_off), _p(ctx_idx), _p(rows), U64(n),
+                        U32(T), _p(out))
+    return out
+
+
+def cbow_adjust_rows(U, W, ctx_off, ctx_idx, rows, coeffs_, alpha):
+    """In place on U and W (float32, C-contiguous)."""
+    assert U.dtype == np.float32 and W.dtype == np.float32
+    assert U.flags.c_contiguous and W.flags.c_contiguous
+    ctx_off, ctx_idx, rows, g = _u32(ctx_off), _u32(ctx_idx), _u32(rows), _f32(coeffs_)
+    n, T = rows.shape
+    lib().orc_cbow_adjust_rows(_p(U), _p(W), U32(U.shape[1]), _p(ctx_off), _p(ctx_idx), _p(rows),
+                               U64(n), U32(T), _p(g), ctypes.c_float(alpha))
+
+
+def cbow_dotprod(U, W, ctx_off, ctx_idx, out_idx, k, seed, thresh, alias):
+    U, W, ctx_off, ctx_idx, out_idx = _f32(U), _f32(W), _u32(ctx_off), _u32(ctx_idx), _u32(out_idx)
+    n = out_idx.size
+    out = np.empty((n, k + 1), np.float32)
+    lib().orc_cbow_dotprod(_p(U), _p(W), U32(U.shape[0]), U32(U.shape[1]), _p(ctx_off), _p(ctx_idx),
+                           _p(out_idx), U64(n), U32(k), U64(seed), _p(thresh), _p(alias), _p(out))
+    return out
+
+
+def cbow_adjust(U, W, ctx_off, ctx_idx, out_idx, k, seed, thresh, alias, coeffs_, alpha):
+    assert U.dtype == np.float32 and W.dtype == np.float32
+    assert U.flags.c_contiguous and W.flags.c_contiguous
+    ctx_off, ctx_idx, out_idx, g = _u32(ctx_off), _u32(ctx_idx), _u32(out_idx), _f32(coeffs_)
+    lib().orc_cbow_adjust(_p(U), _p(W), U32(U.shape[0]), U32(U.shape[1]), _p(ctx_off), _p(ctx_idx),
+                          _p(out_idx), U64(out_idx.size), U32(k), U64(seed), _p(thresh), _p(alias),
+                          _p(g), ctypes.c_float(alpha))
+
+
+def cbow_train_minibatch(Us, Ws, ctx_off, ctx_idx, out_idx, k, seed, thresh, alias, alpha):
+    S = len(Us)
+    for a in list(Us) + list(Ws):
+        assert a.dtype == np.float32 and a.flags.c_contiguous
+    ctx_off, ctx_idx, out_idx = _u32(ctx_off), _u32(ctx_idx), _u32(out_idx)
+    up = (ctypes.c_void_p * S)(*[a.ctypes.data for a in Us])
+    wp = (ctypes.c_void_p * S)(*[a.ctypes.data for a in Ws])
+    ds = np.array([a.shape[1] for a in Us], np.uint32)
+    loss = ctypes.c_double(0.0)
+    lib().orc_cbow_train_minibatch(up, wp, _p(ds), U32(S), U32(Us[0].shape[0]), _p(ctx_off),
+                                   _p(ctx_idx), _p(out_idx), U64(out_idx.size), U32(k), U64(seed),
+                                   _p(thresh), _p(alias), ctypes.c_float(alpha), ctypes.byref(loss))
+    return loss.value
+
+
+def make_cbow_examples(tokens, sent_off, token_base, epoch, corpus_seed, B, keep_thresh,
+                       cap_examples=None, cap_ctx=None):
+    """Returns (ctx_off[m+1], ctx_idx, out_idx[m], n_examples, n_ctx) with m = min(n_examples, cap)."""
+    tokens = _u32(tokens)
+    sent_off = np.ascontiguousarray(sent_off, dtype=np.uint64)
+    kt = None if keep_thresh is None else np.ascontiguousarray(keep_thresh, dtype=np.uint64)
+    if cap_examples is None:
+        cap_examples = int(tokens.size)
+    if cap_ctx is None:
+        cap_ctx = int(tokens.size) * 2 * B
+    off = np.zeros(cap_examples + 1, np.uint32)
+    ctx = np.empty(cap_ctx, np.uint32)
+    out = np.empty(cap_examples, np.uint32)
+    nctx = ctypes.c_uint64(0)
+    cnt = int(lib().orc_make_cbow_examples(_p(tokens), _p(sent_off), U64(sent_off.size - 1),
+                                           U64(token_base), U32(epoch), U64(corpus_seed), U32(B),
+                                           _p(kt), _p(off), _p(ctx), _p(out), U64(cap_examples),
+                                           U64(cap_ctx), ctypes.byref(nctx)))
+    m = min(cnt, cap_examples)
+    return off[:m + 1].copy(), ctx[:min(int(nctx.value), cap_ctx)].copy(), out[:m].copy(), cnt, int(nctx.value)

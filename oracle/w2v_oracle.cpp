@@ -12,6 +12,8 @@
 //                                  sum the partial dots and form G+ / G-)
 //   * Eq.1 / Eq.3 (objective), Eq.4 (gradient), Eq.5 (update), Section 5.1 (column slices, and
 //     the rule that adjust reads the vectors as they stood when the call began).
+//   * Section 5.1's two extensions: interleaved minibatch formation (last paragraph) and the
+//     continuous-bag-of-words variant (footnote), the latter with the word2vec paper's model.
 // Where the paper only names a seeded random number generator, or defers to the word2vec paper
 // for the noise distribution and the subsampling rule, the readings taken are:
 // Philox4x32-10 (Salmon et al., SC'11) as a counter-based generator, the unigram^0.75 noise
@@ -22,7 +24,9 @@
 //
 // Parity pins (tests/test_oracle_*.py): Philox known-answer vectors; brute-force tiny cases;
 // closed forms for zero output vectors; finite differences of the objective; the column-slice
-// invariant; chi-square of the sampler; alias-table reconstruction; window / subsample laws.
+// invariant; chi-square of the sampler; alias-table reconstruction; window / subsample laws;
+// for the bag-of-words variant a matrix formulation, finite differences, and its reduction to
+// skip-gram when every example has one context word.
 // Nothing in this file is "parity unpinned".
 
 #include <algorithm>
@@ -490,6 +494,178 @@ uint64_t orc_make_pairs_interleaved(const uint32_t* tokens, const uint64_t* sent
         }
     }
     return count;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Continuous-bag-of-words variant (Section 5.1, footnote: the same architecture carries over to
+// it; the model itself is the word2vec paper's).  An example p has a center word out_idx[p], which
+// plays the output role, and the list of its context words ctx_idx[ctx_off[p] .. ctx_off[p+1]),
+// which play the input role.  The hidden vector is the mean of the context words' input vectors,
+//     h_p = (1/|C_p|) sum_{c in C_p} u_c ,
+// and the objective is Eq.1's with u replaced by h:  log sigma(h.v_center) + sum log sigma(-h.v_neg).
+// A column slice of h is the mean of the column slices, so the partial dots of the shards still
+// add up (Eq.3's decomposition), and the update is gradient ascent as in Eq.4 / Eq.5:
+//     v_row += alpha * g * h              (row = center or negative, g its coefficient)
+//     u_c   += alpha * (1/|C_p|) * sum_j g_j v_row_j     for every occurrence c in C_p
+// (the exact derivative of the mean; a word that occurs twice in C_p receives it twice).
+// An example with no context has h = 0: zero dots, no change.
+// ---------------------------------------------------------------------------------------------
+void orc_cbow_dots(const float* U, const float* W, uint32_t d, const uint32_t* ctx_off,
+                   const uint32_t* ctx_idx, const uint32_t* rows, uint64_t n, uint32_t T,
+                   float* dots) {
+    std::vector<double> h(d);
+    for (uint64_t p = 0; p < n; ++p) {
+        uint32_t lo = ctx_off[p], hi = ctx_off[p + 1];
+        std::fill(h.begin(), h.end(), 0.0);
+        for (uint32_t e = lo; e < hi; ++e) {
+            const float* u = U + (uint64_t)ctx_idx[e] * d;
+            for (uint32_t c = 0; c < d; ++c) h[c] += (double)u[c];
+        }
+        if (hi > lo) for (uint32_t c = 0; c < d; ++c) h[c] /= (double)(hi - lo);
+        for (uint32_t j = 0; j < T; ++j) {
+            const float* v = W + (uint64_t)rows[p * T + j] * d;
+            double acc = 0.0;
+            for (uint32_t c = 0; c < d; ++c) acc += h[c] * (double)v[c];
+            dots[p * T + j] = (float)acc;
+        }
+    }
+}
+
+void orc_cbow_adjust_rows(float* U, float* W, uint32_t d, const uint32_t* ctx_off,
+                          const uint32_t* ctx_idx, const uint32_t* rows, uint64_t n, uint32_t T,
+                          const float* coeffs, float alpha) {
+    std::unordered_map<uint32_t, std::vector<double>> dU, dW;   // the scratch area
+    std::vector<double> h(d), e(d);
+    for (uint64_t p = 0; p < n; ++p) {
+        uint32_t lo = ctx_off[p], hi = ctx_off[p + 1];
+        std::fill(h.begin(), h.end(), 0.0);
+        std::fill(e.begin(), e.end(), 0.0);
+        for (uint32_t x = lo; x < hi; ++x) {
+            const float* u = U + (uint64_t)ctx_idx[x] * d;
+            for (uint32_t c = 0; c < d; ++c) h[c] += (double)u[c];
+        }
+        if (hi > lo) for (uint32_t c = 0; c < d; ++c) h[c] /= (double)(hi - lo);
+        for (uint32_t j = 0; j < T; ++j) {
+            uint32_t wo = rows[p * T + j];
+            const float* v = W + (uint64_t)wo * d;
+            std::vector<double>& dv = dW[wo];
+            if (dv.empty()) dv.assign(d, 0.0);
+            double g = (double)coeffs[p * T + j];
+            for (uint32_t c = 0; c < d; ++c) {
+                e[c] += g * (double)v[c];
+                dv[c] += g * h[c];
+            }
+        }
+        for (uint32_t x = lo; x < hi; ++x) {
+            std::vector<double>& du = dU[ctx_idx[x]];
+            if (du.empty()) du.assign(d, 0.0);
+            for (uint32_t c = 0; c < d; ++c) du[c] += e[c] / (double)(hi - lo);
+        }
+    }
+    for (auto& kv : dU) {
+        float* u = U + (uint64_t)kv.first * d;
+        for (uint32_t c = 0; c < d; ++c) u[c] = (float)((double)u[c] + (double)alpha * kv.second[c]);
+    }
+    for (auto& kv : dW) {
+        float* v = W + (uint64_t)kv.first * d;
+        for (uint32_t c = 0; c < d; ++c) v[c] = (float)((double)v[c] + (double)alpha * kv.second[c]);
+    }
+}
+
+static void cbow_rows(const uint32_t* out_idx, uint64_t n, uint32_t k, uint64_t seed, uint32_t V,
+                      const uint32_t* thresh, const uint32_t* alias, std::vector<uint32_t>& rows) {
+    uint32_t T = k + 1;
+    rows.resize(n * T);
+    for (uint64_t p = 0; p < n; ++p) {
+        rows[p * T] = out_idx[p];
+        for (uint32_t j = 1; j <= k; ++j)
+            rows[p * T + j] = negative(seed, (uint32_t)p, j, out_idx[p], V, thresh, alias);
+    }
+}
+
+// The two server calls and the client step, with the negatives drawn exactly as for skip-gram
+// (k words different from the example's center word, from the seed).
+void orc_cbow_dotprod(const float* U, const float* W, uint32_t V, uint32_t d,
+                      const uint32_t* ctx_off, const uint32_t* ctx_idx, const uint32_t* out_idx,
+                      uint64_t n, uint32_t k, uint64_t seed, const uint32_t* thresh,
+                      const uint32_t* alias, float* dots) {
+    std::vector<uint32_t> rows;
+    cbow_rows(out_idx, n, k, seed, V, thresh, alias, rows);
+    orc_cbow_dots(U, W, d, ctx_off, ctx_idx, rows.data(), n, k + 1, dots);
+}
+
+void orc_cbow_adjust(float* U, float* W, uint32_t V, uint32_t d, const uint32_t* ctx_off,
+                     const uint32_t* ctx_idx, const uint32_t* out_idx, uint64_t n, uint32_t k,
+                     uint64_t seed, const uint32_t* thresh, const uint32_t* alias,
+                     const float* coeffs, float alpha) {
+    std::vector<uint32_t> rows;
+    cbow_rows(out_idx, n, k, seed, V, thresh, alias, rows);
+    orc_cbow_adjust_rows(U, W, d, ctx_off, ctx_idx, rows.data(), n, k + 1, coeffs, alpha);
+}
+
+void orc_cbow_train_minibatch(float* const* Us, float* const* Ws, const uint32_t* ds, uint32_t S,
+                              uint32_t V, const uint32_t* ctx_off, const uint32_t* ctx_idx,
+                              const uint32_t* out_idx, uint64_t n, uint32_t k, uint64_t seed,
+                              const uint32_t* thresh, const uint32_t* alias, float alpha,
+                              double* loss) {
+    uint32_t T = k + 1;
+    std::vector<std::vector<float>> partial(S, std::vector<float>(n * T));
+    std::vector<const float*> ptrs(S);
+    for (uint32_t s = 0; s < S; ++s) {
+        orc_cbow_dotprod(Us[s], Ws[s], V, ds[s], ctx_off, ctx_idx, out_idx, n, k, seed, thresh,
+                         alias, partial[s].data());
+        ptrs[s] = partial[s].data();
+    }
+    std::vector<float> coeffs(n * T);
+    orc_coeffs(ptrs.data(), S, n, T, coeffs.data(), loss);
+    for (uint32_t s = 0; s < S; ++s)
+        orc_cbow_adjust(Us[s], Ws[s], V, ds[s], ctx_off, ctx_idx, out_idx, n, k, seed, thresh,
+                        alias, coeffs.data(), alpha);
+}
+
+// Examples from text: the same subsampling and window draws as orc_make_pairs; every surviving
+// center with at least one surviving neighbour in its window gives one example whose contexts are
+// those neighbours in increasing position.  Returns the number of examples, *n_ctx the number of
+// context entries; writes at most cap_examples / cap_ctx of them (ctx_off is filled for the examples
+// written, plus the closing offset).
+uint64_t orc_make_cbow_examples(const uint32_t* tokens, const uint64_t* sent_off, uint64_t n_sent,
+                                uint64_t token_base, uint32_t epoch, uint64_t corpus_seed,
+                                uint32_t B, const uint64_t* keep_thresh, uint32_t* ctx_off,
+                                uint32_t* ctx_idx, uint32_t* out_idx, uint64_t cap_examples,
+                                uint64_t cap_ctx, uint64_t* n_ctx) {
+    uint64_t examples = 0, entries = 0;
+    ctx_off[0] = 0;
+    std::vector<uint32_t> kept_word, kept_b;
+    for (uint64_t s = 0; s < n_sent; ++s) {
+        kept_word.clear(); kept_b.clear();
+        for (uint64_t t = sent_off[s]; t < sent_off[s + 1]; ++t) {
+            uint64_t g = token_base + t;
+            Quad q = philox((uint32_t)g, (uint32_t)(g >> 32), epoch, DOMAIN_TOKEN, corpus_seed);
+            uint32_t w = tokens[t];
+            bool keep = keep_thresh ? ((uint64_t)q.r[0] < keep_thresh[w]) : true;
+            if (!keep) continue;
+            kept_word.push_back(w);
+            kept_b.push_back(1 + (uint32_t)(((uint64_t)q.r[1] * (uint64_t)B) >> 32));
+        }
+        int64_t m = (int64_t)kept_word.size();
+        for (int64_t j = 0; j < m; ++j) {
+            int64_t b = (int64_t)kept_b[j];
+            int64_t lo = std::max<int64_t>(0, j - b), hi = std::min<int64_t>(m - 1, j + b);
+            if (hi - lo == 0) continue;                   // no neighbour survives
+            for (int64_t c = lo; c <= hi; ++c) {
+                if (c == j) continue;
+                if (entries < cap_ctx) ctx_idx[entries] = kept_word[c];
+                ++entries;
+            }
+            if (examples < cap_examples) {
+                out_idx[examples] = kept_word[j];
+                ctx_off[examples + 1] = (uint32_t)entries;
+            }
+            ++examples;
+        }
+    }
+    *n_ctx = entries;
+    return examples;
 }
 
 // Per-token view of the same decisions, for the statistical pins: keep[t] in {0,1}, b[t].
