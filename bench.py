@@ -118,6 +118,182 @@ def cpu_baseline_slice(wl, counts, in_idx, out_idx, coeffs, seed, sample_pairs):
                       "the touched rows, %.1f s" % (m, wl.name, dt)}
 
 
+def copy_probe(torch, mb):
+    """One plain device copy of mb MiB (calibrates the HBM traffic counters of a profiler run)."""
+    if not mb:
+        return
+    src = torch.ones(mb << 18, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)              # one copy kernel: reads and writes mb MiB
+    torch.cuda.synchronize()
+    del src, dst
+
+
+class ExampleStream:
+    """Feeds minibatches of n bag-of-words examples formed from a token corpus (device side).  A
+    token block gives a run of examples; whole minibatches are cut from it and the block's last,
+    incomplete minibatch is dropped (its formation cost still counts)."""
+
+    def __init__(self, shard, wl, tokens, sent_off, block_tokens, n, torch):
+        self.torch, self.sh, self.wl, self.n = torch, shard, wl, n
+        self.tok = torch.from_numpy(tokens.view(np.int32)).cuda()
+        self.off_host = sent_off.astype(np.int64)
+        self.block_tokens = block_tokens
+        self.co = torch.empty(block_tokens + 64, dtype=torch.int32, device="cuda")
+        self.ce = torch.empty(block_tokens + 63, dtype=torch.int32, device="cuda")
+        self.cx = torch.empty((block_tokens + 63) * 2 * wl.window, dtype=torch.int32, device="cuda")
+        self.have = self.pos = self.sent = self.epoch = 0
+        self.tokens_used = 0
+
+    def _refill(self):
+        torch, off = self.torch, self.off_host
+        if self.sent >= off.size - 1:
+            self.sent, self.epoch = 0, self.epoch + 1
+        s0 = self.sent
+        t0 = int(off[s0])
+        s1 = int(np.searchsorted(off, t0 + self.block_tokens, side="right")) - 1
+        s1 = min(max(s1, s0 + 1), off.size - 1)
+        t1 = int(off[s1])
+        rel = torch.from_numpy(off[s0:s1 + 1] - t0).cuda()
+        n_ex, n_ctx = self.sh.make_cbow_examples(self.tok[t0:t1], rel, t0, self.epoch, self.wl.seed,
+                                                 self.wl.window, self.co, self.cx, self.ce)
+        assert n_ex <= self.ce.numel() and n_ctx <= self.cx.numel()
+        self.have, self.pos, self.sent = n_ex, 0, s1
+        self.co_host = self.co[:n_ex + 1].cpu().numpy()      # offsets, to slice the context words
+        self.tokens_used += t1 - t0
+
+    def next(self):
+        while self.have - self.pos < self.n:
+            self._refill()
+        a, b = self.pos, self.pos + self.n
+        self.pos = b
+        lo, hi = int(self.co_host[a]), int(self.co_host[b])
+        return (self.co[a:b + 1] - lo), self.cx[lo:hi], self.ce[a:b]
+
+
+def run_cbow(args, torch, w2v, workloads):
+    """Bag-of-words variant on the full300 shape: make_cbow_examples + cbow_train_minibatch."""
+    wl = workloads.WORKLOADS[args.workload]
+    if not wl.pairs_from_corpus or wl.name == "tiny":
+        print("bench.py: --variant cbow runs on a text workload (full300, search200m, stress25)",
+              file=sys.stderr)
+        sys.exit(2)
+    K, Wm = args.steps, args.warmup
+    n = args.cbow_examples
+    R, T = 4 * wl.d_slice, wl.k + 1
+    cdf = workloads.zipf_cdf(wl.V, wl.zipf_s)
+    counts = workloads.analytic_counts(wl.V, wl.zipf_s, wl.corpus_tokens)
+    sh = w2v.Shard(wl.V, wl.d_slice, wl.seed, d_total=wl.d_total, col_begin=wl.col_begin,
+                   init_mode=1 if wl.w_uniform else 0)
+    sh.set_counts(counts, wl.subsample_t)
+    copy_probe(torch, args.copy_probe_mb)
+    tokens, off = workloads.corpus(wl, args.corpus_tokens or 12_000_000, cdf=cdf)
+    del cdf
+    stream = ExampleStream(sh, wl, tokens, off, min(tokens.size, 1 << 21), n, torch)
+    loss = None if args.no_loss else torch.zeros(1, dtype=torch.float64, device="cuda")
+    H = max(1, wl.corpus_tokens // (2 * n))
+
+    def step(h):
+        co, cx, ce = stream.next()
+        w2v.cbow_train_minibatch([sh], co, cx, ce, wl.k, w2v.minibatch_seed(wl.seed, h),
+                                 workloads.alpha_schedule(wl, h, H), loss=loss)
+        return co, cx, ce
+
+    first = None
+    for h in range(max(Wm, 1)):
+        e = step(h)
+        if first is None:
+            first = tuple(w2v.index_to_numpy(x).copy() for x in e)
+    Wm = max(Wm, 1)
+    sh.status()
+    sh.timing_enable(True)
+    sh.timing_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx_total = 0
+    for h in range(Wm, Wm + K):
+        last = step(h)
+        ctx_total += last[1].numel()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    phases = sh.timing_read()
+    sh.timing_enable(False)
+    sh.status()
+    m = ctx_total / K
+    neg = sh.negatives(last[2], wl.k, w2v.minibatch_seed(wl.seed, Wm + K - 1))
+    du = int(torch.unique(last[1]).numel())
+    dw = int(torch.unique(torch.cat([last[2], neg.reshape(-1)])).numel())
+    M = n * T
+    # algorithmic bytes per launch (= per minibatch):
+    #   dot   (hidden vectors)      : m input rows read + n rows written + 4 B per entry
+    #   uside (per-example pass)    : T output rows + the hidden row per example, one row written
+    #   wside (output-side update)  : one hidden row per contribution + 12 B + RMW of distinct rows
+    #   apply (input-side update)   : one summed row per context entry + 12 B + RMW of distinct rows
+    algo = {
+        "dot": (m + n) * R + 4 * m,
+        "uside": n * (T + 2) * R + 8 * M,
+        "wside": M * R + 12 * M + 2 * dw * R,
+        "apply": m * R + 12 * m + 2 * du * R,
+    }
+    per_phase = {name: {"ms_per_launch": ms / cnt, "launches": cnt}
+                 for name, (ms, cnt) in phases.items() if cnt}
+    dom = max((p for p in per_phase if p in algo),
+              key=lambda p: per_phase[p]["ms_per_launch"] * per_phase[p]["launches"])
+    launches_per_step = per_phase[dom]["launches"] / K
+    dom_ms = per_phase[dom]["ms_per_launch"] * launches_per_step      # per minibatch
+    achieved = algo[dom] / (dom_ms * 1e-3) / 1e9
+    traffic = None          # L2<->fabric bytes per launch, from the committed rocprofv3 counter summary
+    tfile = os.path.join(ROOT, "profiles", "%s_cbow_hbm_traffic.txt" % wl.name)
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic" and parts[1] == dom:
+                traffic = float(parts[2])
+    out = {
+        "metric": "CBOW training examples/s (k negatives incl.) on 1 MI355X",
+        "value": n * K / dt, "unit": "examples/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": dt * 1e3 / K, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name + "/cbow", "V": wl.V, "d_slice": wl.d_slice,
+                   "examples_per_minibatch": n, "context_words_per_minibatch": m, "k": wl.k,
+                   "zipf_s": wl.zipf_s, "window": wl.window, "subsample_t": wl.subsample_t,
+                   "path": "make_cbow_examples+cbow_train_minibatch",
+                   "distinct_input_rows": du, "distinct_output_rows": dw},
+        "context_words_per_s": ctx_total / dt,
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": algo[dom], "ms_per_launch": dom_ms},
+        "phases": per_phase,
+        "tokens_per_minibatch": stream.tokens_used / (K + Wm),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        th, al = oracle.build_alias(counts)
+        co, cx, ce = first
+        e = min(args.cpu_sample_pairs or (1 << 17), ce.size)
+        co, cx, ce = co[:e + 1], cx[:int(co[e])], ce[:e]
+        seed0 = w2v.minibatch_seed(wl.seed, 0)
+        rows = np.concatenate([ce[:, None], oracle.negatives(ce, wl.k, seed0, th, al)], axis=1)
+        words, inv = np.unique(np.concatenate([cx, rows.ravel()]), return_inverse=True)
+        U = oracle.init_rows(wl.seed, wl.d_total, wl.col_begin, wl.d_slice, 0, words.astype(np.uint32))
+        W = (oracle.init_rows(wl.seed, wl.d_total, wl.col_begin, wl.d_slice, 1, words.astype(np.uint32))
+             if wl.w_uniform else np.zeros_like(U))
+        cc = inv[:cx.size].astype(np.uint32)
+        cr = inv[cx.size:].reshape(rows.shape).astype(np.uint32)
+        t0 = time.perf_counter()
+        oracle.negatives(ce, wl.k, seed0, th, al)
+        g = oracle.coeffs([oracle.cbow_dots(U, W, co, cc, cr)])
+        oracle.negatives(ce, wl.k, seed0, th, al)
+        oracle.cbow_adjust_rows(U, W, co, cc, cr, g, wl.alpha)
+        dtc = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": e / dtc, "unit": "examples/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d examples of minibatch 0, oracle cbow dots + "
+                                         "coefficients + adjust on the touched rows, %.1f s" % (e, dtc)}
+    sh.destroy()
+    print(json.dumps(out), flush=True)
+
+
 def distinct_rows(torch, shard, in_idx, out_idx, k, seed):
     """Distinct input rows and distinct output/negative rows of one minibatch (for byte counts)."""
     neg = shard.negatives(out_idx, k, seed)
@@ -133,6 +309,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="full300",
                     choices=["full300", "slice60", "tiny", "search200m", "stress25"])
+    ap.add_argument("--variant", default="sgns", choices=["sgns", "cbow"],
+                    help="cbow: the bag-of-words variant on the same text workload")
+    ap.add_argument("--cbow-examples", type=int, default=1 << 17, help="examples per cbow minibatch")
     ap.add_argument("--corpus-tokens", type=int, default=0, help="tokens of the corpus slice to generate")
     ap.add_argument("--cpu-sample-pairs", type=int, default=0,
                     help="pairs the CPU oracle is timed on (default: about 10-30 s of one core)")
@@ -153,6 +332,8 @@ def main():
         from paper_1606_08495_amd import build as hip_build
         hip_build.build()
     torch.cuda.set_device(0)
+    if args.variant == "cbow":
+        return run_cbow(args, torch, w2v, workloads)
     wl = workloads.WORKLOADS[args.workload]
     K, Wm = args.steps, args.warmup
     if not args.cpu_sample_pairs:
@@ -174,13 +355,7 @@ def main():
     log("setup: shard V=%d d_slice=%d (%.1f GB of vectors) ready in %.1f s"
         % (wl.V, wl.d_slice, 2.0 * wl.V * R / 1e9, time.perf_counter() - t_setup))
 
-    if args.copy_probe_mb:
-        src = torch.ones(args.copy_probe_mb << 18, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)              # one copy kernel: reads and writes copy_probe_mb MiB
-        torch.cuda.synchronize()
-        del src, dst
+    copy_probe(torch, args.copy_probe_mb)
 
     loss = None if args.no_loss else torch.zeros(1, dtype=torch.float64, device="cuda")
     total_steps = K + Wm

@@ -156,6 +156,47 @@ int w2v_make_pairs_interleaved(w2v_shard* shard, const uint32_t* tokens_dev,
                                uint32_t B, uint32_t* in_idx_dev, uint32_t* out_idx_dev,
                                uint64_t capacity, uint64_t* n_pairs_host, void* stream);
 
+/* ---- continuous-bag-of-words variant (Section 5.1, footnote: the architecture carries over) ----------
+ * Example p (p = 0..n-1) has a center word out_idx[p], which plays the output role, and the context
+ * words ctx_idx[ctx_off[p] .. ctx_off[p+1]), which play the input role.  Its hidden vector is the
+ * mean of the context words' input vectors, h_p = (1/|C_p|) sum u_c, and it takes the place of the
+ * input vector in Eq.1: the dots are h_p . v_row for row = center word and the k negatives (drawn as
+ * for w2v_dotprod: functions of seed, p and the slot, different from the center word).  A column
+ * slice of h_p is the mean of the slices, so partial dots of the shards add up as in Eq.3.  The update
+ * is gradient ascent on that objective (Eq.4 / Eq.5 with h in place of u), from start-of-call
+ * vectors:  v_row += alpha * g_pj * h_p  and, for every entry c of C_p,
+ * u_c += alpha * (1/|C_p|) * sum_j g_pj * v_row_pj  (a word listed twice receives it twice).
+ * An example with an empty context list has h = 0: zero dots, no change.
+ *
+ * ctx_off_dev[n+1] (first 0, non-decreasing, last m), ctx_idx_dev[m], out_idx_dev[n] are device
+ * arrays owned by the caller; m < 2^31.  Offsets that break these rules, and words >= V, raise the
+ * sticky index flag (w2v_shard_status) and are made harmless; they never fault.  Other arguments,
+ * layouts of partial_dots / coeffs, errors and stream behaviour are those of w2v_dotprod,
+ * w2v_adjust and w2v_train_minibatch. */
+int w2v_cbow_dotprod(w2v_shard* shard, const uint32_t* ctx_off_dev, const uint32_t* ctx_idx_dev,
+                     uint32_t m, const uint32_t* out_idx_dev, uint32_t n, uint32_t k, uint64_t seed,
+                     float* partial_dots_dev, void* stream);
+int w2v_cbow_adjust(w2v_shard* shard, const uint32_t* ctx_off_dev, const uint32_t* ctx_idx_dev,
+                    uint32_t m, const uint32_t* out_idx_dev, uint32_t n, uint32_t k, uint64_t seed,
+                    const float* coeffs_dev, float alpha, void* stream);
+int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S, const uint32_t* ctx_off_dev,
+                             const uint32_t* ctx_idx_dev, uint32_t m, const uint32_t* out_idx_dev,
+                             uint32_t n, uint32_t k, uint64_t seed, float alpha, double* loss_dev,
+                             void* stream);
+
+/* Examples from text: the same subsampling and window draws as w2v_make_pairs.  Every surviving
+ * center with at least one surviving neighbour inside its window gives one example; its contexts are
+ * those neighbours by increasing position (the pair stream's output words, grouped by center).
+ * Writes at most cap_examples centers (out_idx_dev) with their offsets (ctx_off_dev, cap_examples+1
+ * entries, always starting with 0) and at most cap_ctx context words; *n_examples_host and
+ * *n_ctx_host receive the full counts.  Synchronises the stream, like w2v_make_pairs. */
+int w2v_make_cbow_examples(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t* sent_off_dev,
+                           uint32_t n_sent, uint32_t n_tokens, uint64_t token_base, uint32_t epoch,
+                           uint64_t corpus_seed, uint32_t B, uint32_t* ctx_off_dev,
+                           uint32_t* ctx_idx_dev, uint32_t* out_idx_dev, uint64_t cap_examples,
+                           uint64_t cap_ctx, uint64_t* n_examples_host, uint64_t* n_ctx_host,
+                           void* stream);
+
 /* Seed of minibatch number h (the client picks a fresh seed per minibatch), a function of a master seed. */
 uint64_t w2v_minibatch_seed(uint64_t master_seed, uint64_t h);
 

@@ -660,24 +660,286 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
 }
 
 // ---------------------------------------------------------------------------------------------
+// continuous bag of words (Section 5.1, footnote)
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+// Scratch of one bag-of-words minibatch: n examples, M = n(k+1) dot slots, m context entries.
+struct CbowPlan {
+    uint32_t n, T, M, m;
+    uint32_t* keys;                                  // [M] center word + negatives per example
+    uint32_t* ctx_safe; uint32_t* ex_of; float* weight;   // [m]
+    uint32_t* iota;                                  // [n] 0, 1, 2, ...
+    float* H; float* E; uint32_t* dkey;              // [n] rows: hidden vectors, summed output rows
+    float* coeffs; float* dots; double* loss_tmp;
+    uint32_t *wk0, *wv0, *wk1, *wv1, *sort_tmp_w;    // sort of the M destinations
+    uint32_t *ck0, *cv0, *ck1, *cv1, *sort_tmp_c;    // sort of the m context entries
+    float* pa_rows; uint32_t* pa_keys;               // unused slots of the per-example pass
+    float* pb_rows; uint32_t* pb_keys;               // output side, level 1
+    float* pd_rows; uint32_t* pd_keys;               // input side, level 1
+    float* pc_rows; uint32_t* pc_keys;               // level 2 of either side
+    uint32_t slots_a, slots_w1, slots_c1, slots_2;
+    size_t bytes;
+};
+
+CbowPlan make_cbow_plan(char* base, uint32_t n, uint32_t k, uint32_t m, uint32_t stride4_max,
+                        uint32_t S_dots, bool want_adjust, bool want_coeffs) {
+    CbowPlan p{};
+    p.n = n; p.T = k + 1; p.M = n * p.T; p.m = m;
+    Carver c(base);
+    const size_t row = (size_t)stride4_max * 4;
+    p.keys = c.take<uint32_t>(p.M);
+    p.ctx_safe = c.take<uint32_t>(m); p.ex_of = c.take<uint32_t>(m); p.weight = c.take<float>(m);
+    p.iota = c.take<uint32_t>(n);
+    p.H = c.take<float>((size_t)n * row);
+    if (want_coeffs) p.coeffs = c.take<float>(p.M);
+    if (S_dots) p.dots = c.take<float>((size_t)S_dots * p.M);
+    p.loss_tmp = c.take<double>(coeffs_loss_scratch_doubles(n, p.T));
+    if (want_adjust) {
+        p.E = c.take<float>((size_t)n * row);
+        p.dkey = c.take<uint32_t>(n);
+        p.wk0 = c.take<uint32_t>(p.M); p.wv0 = c.take<uint32_t>(p.M);
+        p.wk1 = c.take<uint32_t>(p.M); p.wv1 = c.take<uint32_t>(p.M);
+        p.sort_tmp_w = c.take<uint32_t>(sort_scratch_u32(p.M ? p.M : 1));
+        p.ck0 = c.take<uint32_t>(m); p.cv0 = c.take<uint32_t>(m);
+        p.ck1 = c.take<uint32_t>(m); p.cv1 = c.take<uint32_t>(m);
+        p.sort_tmp_c = c.take<uint32_t>(sort_scratch_u32(m ? m : 1));
+        p.slots_a = slots_after(n, useg_pairs_per_chunk(p.T));
+        p.slots_w1 = slots_after(p.M, wseg_entries_per_chunk());
+        p.slots_c1 = slots_after(m, wseg_entries_per_chunk());
+        p.slots_2 = std::max(slots_after(p.slots_w1, tail_entries_per_chunk()),
+                             slots_after(p.slots_c1, tail_entries_per_chunk()));
+        p.pa_rows = c.take<float>((size_t)p.slots_a * row);  p.pa_keys = c.take<uint32_t>(p.slots_a + 1);
+        p.pb_rows = c.take<float>((size_t)p.slots_w1 * row); p.pb_keys = c.take<uint32_t>(p.slots_w1 + 1);
+        p.pd_rows = c.take<float>((size_t)p.slots_c1 * row); p.pd_keys = c.take<uint32_t>(p.slots_c1 + 1);
+        p.pc_rows = c.take<float>((size_t)p.slots_2 * row);  p.pc_keys = c.take<uint32_t>(p.slots_2 + 1);
+    }
+    p.bytes = c.off + 256;
+    return p;
+}
+
+int check_cbow_batch(const w2v_shard* sh, uint32_t n, uint32_t k, uint32_t m) {
+    int rc = check_batch(sh, n, k, true);
+    if (rc) return rc;
+    if (m >= (1u << 31)) return fail(W2V_ERR_ARG, "m = %u context entries must stay below 2^31", m);
+    return W2V_OK;
+}
+
+// Checked context entries, example numbers and weights, the destination keys, and (for adjust)
+// both sorts: destinations of the M output-side contributions, words of the m context entries.
+void queue_cbow_indices(w2v_shard* sh, CbowPlan& p, const uint32_t* ctx_off, const uint32_t* ctx_idx,
+                        const uint32_t* out_idx, uint32_t k, uint64_t seed, bool sorts,
+                        uint32_t** skw, uint32_t** sidx, uint32_t** skc, uint32_t** cidx,
+                        hipStream_t st) {
+    {
+        Phase ph(sh, W2V_PH_NEG, st);
+        launch_cbow_entries(ctx_off, ctx_idx, p.n, p.m, sh->V, p.ctx_safe, p.ex_of, p.weight,
+                            sh->err, st);
+        launch_iota(p.iota, p.n, st);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, p.n, k, seed, p.keys, sh->err, st);
+    }
+    if (!sorts) return;
+    Phase ph(sh, W2V_PH_SORT, st);
+    const uint32_t bits = key_bits(sh->V);
+    launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp_w, skw, sidx, st);
+    launch_sort_pairs(p.ctx_safe, p.ck0, p.cv0, p.ck1, p.cv1, p.m, bits, p.sort_tmp_c, skc, cidx, st);
+}
+
+void queue_cbow_hidden(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint32_t* ctx_off,
+                       hipStream_t st) {
+    Phase ph(owner, W2V_PH_DOT, st);
+    launch_cbow_hidden(sh->U, sh->g, ctx_off, p.ctx_safe, p.n, p.m, p.H, st);
+}
+
+// The update of one shard.  The hidden vectors stand in for the input vectors in the skip-gram
+// kernels: the per-example pass (every example is its own run) leaves e_p = sum_j g_pj v_row_pj in
+// E, forming dots and coefficients on the way when fused; the output side adds g_pj h_p to its
+// rows; the input side adds e_p / |C_p| to the input vector of every context entry.  H holds the
+// start-of-call input vectors and E the start-of-call output vectors, so the order of the two
+// write-backs does not matter.
+void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint32_t* skw,
+                       const uint32_t* sidx, const uint32_t* skc, const uint32_t* cidx,
+                       const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
+                       hipStream_t st) {
+    {
+        Phase ph(owner, W2V_PH_USIDE, st);
+        USideArgs a{};
+        a.U = p.H; a.W = sh->W; a.g = sh->g; a.skey = p.iota; a.perm = p.iota; a.keys = p.keys;
+        a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
+        a.dots_out = nullptr; a.delta = p.E; a.dkey = p.dkey;
+        a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
+        launch_useg(a, st);
+    }
+    {
+        Phase ph(owner, W2V_PH_WSIDE, st);
+        WSideArgs w{};
+        w.U = p.H; w.W = sh->W; w.g = sh->g; w.skey = skw; w.sidx = sidx; w.M = p.M; w.T = p.T;
+        w.in_idx = p.iota; w.coeffs = fused ? coeffs_out : coeffs_in; w.alpha = alpha;
+        w.prows = p.pb_rows; w.pkeys = p.pb_keys;
+        launch_wseg(w, st);
+        run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st);
+    }
+    {
+        Phase ph(owner, W2V_PH_APPLY, st);
+        WSideArgs u{};
+        u.U = p.E; u.W = sh->U; u.g = sh->g; u.skey = skc; u.sidx = cidx; u.M = p.m; u.T = 1;
+        u.in_idx = p.ex_of; u.coeffs = p.weight; u.alpha = alpha;
+        u.prows = p.pd_rows; u.pkeys = p.pd_keys;
+        launch_wseg(u, st);
+        run_tails(sh, sh->U, alpha, p.pd_rows, p.pd_keys, p.slots_c1, p.pc_rows, p.pc_keys, st);
+    }
+}
+
+int check_cbow_pointers(const uint32_t* ctx_off, const uint32_t* ctx_idx, uint32_t m,
+                        const uint32_t* out_idx, uint32_t n) {
+    if (n && (!ctx_off || !out_idx)) return fail(W2V_ERR_NULL, "NULL argument");
+    if (m && !ctx_idx) return fail(W2V_ERR_NULL, "ctx_idx is NULL");
+    if (n == 0 && m != 0) return fail(W2V_ERR_ARG, "context entries without examples");
+    return W2V_OK;
+}
+
+}  // namespace
+
+extern "C" int w2v_cbow_dotprod(w2v_shard* sh, const uint32_t* ctx_off, const uint32_t* ctx_idx,
+                                uint32_t m, const uint32_t* out_idx, uint32_t n, uint32_t k,
+                                uint64_t seed, float* partial_dots, void* stream) {
+    if (!sh || (n && !partial_dots)) return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_cbow_pointers(ctx_off, ctx_idx, m, out_idx, n);
+    if (!rc) rc = check_device(sh);
+    if (!rc) rc = check_cbow_batch(sh, n, k, m);
+    if (rc) return rc;
+    if (n == 0) return W2V_OK;
+    hipStream_t st = (hipStream_t)stream;
+    CbowPlan sz = make_cbow_plan(nullptr, n, k, m, sh->g.stride4, 0, false, false);
+    rc = ensure_ws(sh, sz.bytes);
+    if (rc) return rc;
+    CbowPlan p = make_cbow_plan(sh->ws, n, k, m, sh->g.stride4, 0, false, false);
+    queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, false, nullptr, nullptr, nullptr,
+                       nullptr, st);
+    queue_cbow_hidden(sh, sh, p, ctx_off, st);
+    {
+        Phase ph(sh, W2V_PH_DOT, st);
+        launch_dots(p.H, sh->W, sh->g, p.iota, p.keys, n, p.T, partial_dots, st);
+    }
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+extern "C" int w2v_cbow_adjust(w2v_shard* sh, const uint32_t* ctx_off, const uint32_t* ctx_idx,
+                               uint32_t m, const uint32_t* out_idx, uint32_t n, uint32_t k,
+                               uint64_t seed, const float* coeffs, float alpha, void* stream) {
+    if (!sh || (n && !coeffs)) return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_cbow_pointers(ctx_off, ctx_idx, m, out_idx, n);
+    if (!rc) rc = check_device(sh);
+    if (!rc) rc = check_cbow_batch(sh, n, k, m);
+    if (rc) return rc;
+    if (n == 0) return W2V_OK;
+    hipStream_t st = (hipStream_t)stream;
+    CbowPlan sz = make_cbow_plan(nullptr, n, k, m, sh->g.stride4, 0, true, false);
+    rc = ensure_ws(sh, sz.bytes);
+    if (rc) return rc;
+    CbowPlan p = make_cbow_plan(sh->ws, n, k, m, sh->g.stride4, 0, true, false);
+    uint32_t *skw, *sidx, *skc, *cidx;
+    queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, true, &skw, &sidx, &skc, &cidx, st);
+    queue_cbow_hidden(sh, sh, p, ctx_off, st);
+    queue_cbow_adjust(sh, sh, p, skw, sidx, skc, cidx, coeffs, nullptr, false, alpha, st);
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
+                                        const uint32_t* ctx_off, const uint32_t* ctx_idx,
+                                        uint32_t m, const uint32_t* out_idx, uint32_t n, uint32_t k,
+                                        uint64_t seed, float alpha, double* loss, void* stream) {
+    if (!shards) return fail(W2V_ERR_NULL, "NULL argument");
+    if (S == 0 || S > W2V_S_MAX) return fail(W2V_ERR_ARG, "S = %u outside 1..%d", S, W2V_S_MAX);
+    uint32_t stride_max = 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        if (!shards[s]) return fail(W2V_ERR_NULL, "shards[%u] is NULL", s);
+        if (shards[s]->V != shards[0]->V || shards[s]->device != shards[0]->device)
+            return fail(W2V_ERR_MISMATCH, "shard %u differs from shard 0 in V or device", s);
+        if (k > 0 && shards[s]->has_tables && shards[0]->has_tables &&
+            shards[s]->table_tag != shards[0]->table_tag)
+            return fail(W2V_ERR_MISMATCH, "shard %u holds a different noise table", s);
+        stride_max = std::max(stride_max, shards[s]->g.stride4);
+    }
+    w2v_shard* s0 = shards[0];
+    int rc = check_cbow_pointers(ctx_off, ctx_idx, m, out_idx, n);
+    if (!rc) rc = check_device(s0);
+    if (!rc) rc = check_cbow_batch(s0, n, k, m);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (n == 0) {
+        if (loss) launch_loss_from_coeffs(nullptr, 0, k + 1, nullptr, loss, st);
+        return W2V_OK;
+    }
+    const bool fused = (S == 1);
+    CbowPlan sz = make_cbow_plan(nullptr, n, k, m, stride_max, fused ? 0 : S, true, true);
+    rc = ensure_ws(s0, sz.bytes);
+    if (rc) return rc;
+    CbowPlan p = make_cbow_plan(s0->ws, n, k, m, stride_max, fused ? 0 : S, true, true);
+    uint32_t *skw, *sidx, *skc, *cidx;
+    queue_cbow_indices(s0, p, ctx_off, ctx_idx, out_idx, k, seed, true, &skw, &sidx, &skc, &cidx, st);
+    if (fused) {
+        queue_cbow_hidden(s0, s0, p, ctx_off, st);
+        queue_cbow_adjust(s0, s0, p, skw, sidx, skc, cidx, nullptr, p.coeffs, true, alpha, st);
+        if (loss) {
+            Phase ph(s0, W2V_PH_COEFF, st);
+            launch_loss_from_coeffs(p.coeffs, n, p.T, p.loss_tmp, loss, st);
+        }
+    } else {
+        // As in the two-call protocol, every shard forms its hidden vectors once for the dots and
+        // once more for the update (its input vectors do not change in between).
+        PartialPtrs pp{};
+        for (uint32_t s = 0; s < S; ++s) {
+            float* d = p.dots + (size_t)s * p.M;
+            queue_cbow_hidden(s0, shards[s], p, ctx_off, st);
+            Phase ph(s0, W2V_PH_DOT, st);
+            launch_dots(p.H, shards[s]->W, shards[s]->g, p.iota, p.keys, n, p.T, d, st);
+            pp.p[s] = d;
+        }
+        {
+            Phase ph(s0, W2V_PH_COEFF, st);
+            launch_coeffs(pp, S, n, p.T, p.coeffs, p.loss_tmp, loss, st);
+        }
+        for (uint32_t s = 0; s < S; ++s) {
+            queue_cbow_hidden(s0, shards[s], p, ctx_off, st);
+            queue_cbow_adjust(s0, shards[s], p, skw, sidx, skc, cidx, p.coeffs, nullptr, false, alpha, st);
+        }
+    }
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // pair formation
 // ---------------------------------------------------------------------------------------------
+// Outputs of the bag-of-words example formation on top of the pair stream.
+struct CbowOut { uint32_t* ctx_off; uint32_t* centers; uint64_t cap_examples; uint64_t* n_examples; };
+
 static int make_pairs_impl(w2v_shard* sh, const uint32_t* tokens, const uint64_t* sent_off,
                            uint32_t n_sent, uint32_t n_tokens, uint64_t token_base, uint32_t epoch,
                            uint64_t corpus_seed, uint32_t B, uint32_t* in_idx, uint32_t* out_idx,
-                           uint64_t capacity, uint64_t* n_pairs, bool interleave, void* stream) {
+                           uint64_t capacity, uint64_t* n_pairs, bool interleave,
+                           const CbowOut* cbow, void* stream) {
     if (!sh || !n_pairs) return fail(W2V_ERR_NULL, "NULL argument");
     *n_pairs = 0;
     if (n_tokens && (!tokens || !sent_off)) return fail(W2V_ERR_NULL, "NULL argument");
-    if (capacity && (!in_idx || !out_idx)) return fail(W2V_ERR_NULL, "NULL output");
+    if (capacity && ((!in_idx && !cbow) || !out_idx)) return fail(W2V_ERR_NULL, "NULL output");
     if (B == 0) return fail(W2V_ERR_ARG, "window B must be at least 1");
     if (n_tokens && n_sent == 0) return fail(W2V_ERR_ARG, "tokens without sentences");
     if ((uint64_t)n_tokens * 2 * B >= (1ull << 32))
         return fail(W2V_ERR_ARG, "n_tokens * 2B must stay below 2^32; pass the corpus in blocks");
     int rc = check_device(sh);
     if (rc) return rc;
-    if (n_tokens == 0) return W2V_OK;
     hipStream_t st = (hipStream_t)stream;
+    if (n_tokens == 0) {
+        if (cbow) {                          // the closing offset of an empty example list
+            launch_iota(cbow->ctx_off, 1, st);
+            HIP_TRY(hipStreamSynchronize(st));
+        }
+        return W2V_OK;
+    }
     size_t need = sizeof(uint32_t) * (pairs_scratch_u32(n_tokens, interleave) + 64) + 512;
     rc = ensure_ws(sh, need);
     if (rc) return rc;
@@ -687,6 +949,10 @@ static int make_pairs_impl(w2v_shard* sh, const uint32_t* tokens, const uint64_t
     a.keep = sh->has_tables ? sh->keep : nullptr; a.V = sh->V;
     a.in_idx = in_idx; a.out_idx = out_idx; a.capacity = capacity; a.interleave = interleave;
     a.total_pairs = (uint32_t*)sh->ws;
+    if (cbow) {
+        a.ctx_off = cbow->ctx_off; a.centers = cbow->centers; a.cap_examples = cbow->cap_examples;
+        a.total_examples = (uint32_t*)sh->ws + 1;
+    }
     a.scratch = (uint32_t*)sh->ws + 64;
     a.err = sh->err;
     {
@@ -694,11 +960,27 @@ static int make_pairs_impl(w2v_shard* sh, const uint32_t* tokens, const uint64_t
         launch_make_pairs(a, st);
     }
     HIP_TRY(hipGetLastError());
-    uint32_t total = 0;
-    HIP_TRY(hipMemcpyAsync(&total, a.total_pairs, sizeof(total), hipMemcpyDeviceToHost, st));
+    uint32_t total[2] = {0, 0};
+    HIP_TRY(hipMemcpyAsync(total, a.total_pairs, sizeof(uint32_t) * (cbow ? 2 : 1),
+                           hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
-    *n_pairs = total;
+    *n_pairs = total[0];
+    if (cbow) *cbow->n_examples = total[1];
     return W2V_OK;
+}
+
+extern "C" int w2v_make_cbow_examples(w2v_shard* sh, const uint32_t* tokens,
+                                      const uint64_t* sent_off, uint32_t n_sent, uint32_t n_tokens,
+                                      uint64_t token_base, uint32_t epoch, uint64_t corpus_seed,
+                                      uint32_t B, uint32_t* ctx_off, uint32_t* ctx_idx,
+                                      uint32_t* out_idx, uint64_t cap_examples, uint64_t cap_ctx,
+                                      uint64_t* n_examples, uint64_t* n_ctx, void* stream) {
+    if (!n_examples || !ctx_off) return fail(W2V_ERR_NULL, "NULL argument");
+    *n_examples = 0;
+    if (cap_examples && !out_idx) return fail(W2V_ERR_NULL, "NULL output");
+    CbowOut co{ctx_off, out_idx, cap_examples, n_examples};
+    return make_pairs_impl(sh, tokens, sent_off, n_sent, n_tokens, token_base, epoch, corpus_seed,
+                           B, nullptr, ctx_idx, cap_ctx, n_ctx, false, &co, stream);
 }
 
 extern "C" int w2v_make_pairs(w2v_shard* sh, const uint32_t* tokens, const uint64_t* sent_off,
@@ -707,7 +989,7 @@ extern "C" int w2v_make_pairs(w2v_shard* sh, const uint32_t* tokens, const uint6
                               uint32_t* out_idx, uint64_t capacity, uint64_t* n_pairs,
                               void* stream) {
     return make_pairs_impl(sh, tokens, sent_off, n_sent, n_tokens, token_base, epoch, corpus_seed,
-                           B, in_idx, out_idx, capacity, n_pairs, false, stream);
+                           B, in_idx, out_idx, capacity, n_pairs, false, nullptr, stream);
 }
 
 extern "C" int w2v_make_pairs_interleaved(w2v_shard* sh, const uint32_t* tokens,
@@ -717,7 +999,7 @@ extern "C" int w2v_make_pairs_interleaved(w2v_shard* sh, const uint32_t* tokens,
                                           uint32_t* out_idx, uint64_t capacity, uint64_t* n_pairs,
                                           void* stream) {
     return make_pairs_impl(sh, tokens, sent_off, n_sent, n_tokens, token_base, epoch, corpus_seed,
-                           B, in_idx, out_idx, capacity, n_pairs, true, stream);
+                           B, in_idx, out_idx, capacity, n_pairs, true, nullptr, stream);
 }
 
 extern "C" uint64_t w2v_minibatch_seed(uint64_t master_seed, uint64_t h) {

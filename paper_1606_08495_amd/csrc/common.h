@@ -148,11 +148,28 @@ struct PairArgs {
     uint64_t token_base; uint32_t epoch; uint64_t seed; uint32_t B; const uint64_t* keep; uint32_t V;
     uint32_t* in_idx; uint32_t* out_idx; uint64_t capacity;
     bool interleave;        // centers round-robin over the sentences instead of corpus order
+    // bag-of-words examples (plain order only; in_idx may then be null): ctx_off[cap_examples+1],
+    // centers[cap_examples], *total_examples; out_idx holds the context words
+    uint32_t* ctx_off; uint32_t* centers; uint64_t cap_examples; uint32_t* total_examples;
     uint32_t* scratch;      // pairs_scratch_u32(n_tokens, interleave) uint32
     uint32_t* total_pairs;  // device, one uint32
     uint32_t* err;
 };
 size_t pairs_scratch_u32(uint32_t n_tokens, bool interleave);
 void launch_make_pairs(const PairArgs& a, hipStream_t st);
+
+// ---- continuous bag of words ----------------------------------------------------------------------
+// Per context entry: checked word, example number, weight 1/|C|; offsets are validated (error flag).
+void launch_cbow_entries(const uint32_t* ctx_off, const uint32_t* ctx_idx, uint32_t n, uint32_t m,
+                         uint32_t V, uint32_t* ctx_safe, uint32_t* ex_of, float* weight,
+                         uint32_t* err, hipStream_t st);
+void launch_iota(uint32_t* x, uint32_t n, hipStream_t st);
+// H[p] = mean of U[ctx_safe[e]] over the entries of example p (row geometry g).
+void launch_cbow_hidden(const float* U, RowGeom g, const uint32_t* ctx_off, const uint32_t* ctx_safe,
+                        uint32_t n, uint32_t m, float* H, hipStream_t st);
+void launch_cbow_examples(const uint32_t* kcnt, const uint32_t* kword, const uint32_t* poff,
+                          const uint32_t* n_kept, uint32_t n, uint32_t* flag, uint32_t* ex,
+                          uint32_t* scan_tmp, uint32_t* ctx_off, uint32_t* out_idx,
+                          uint64_t cap_examples, uint32_t* total_examples, hipStream_t st);
 
 }  // namespace w2v

@@ -104,7 +104,10 @@ __global__ __launch_bounds__(256) void emit_pairs_kernel(const uint32_t* __restr
     uint32_t last = khi[q] < *n_kept ? khi[q] : *n_kept - 1;   // holds for well-formed sentences
     for (uint32_t c = klo[q]; c <= last; ++c) {
         if (c == q) continue;
-        if (o < capacity) { in_idx[o] = w; out_idx[o] = kword[c]; }
+        if (o < capacity) {
+            if (in_idx) in_idx[o] = w;
+            out_idx[o] = kword[c];
+        }
         ++o;
     }
 }
@@ -139,7 +142,13 @@ void launch_make_pairs(const PairArgs& a, hipStream_t st) {
                        (uint32_t)(a.seed >> 32), a.B, a.keep, a.V, flag, width, a.err);
     launch_exclusive_scan(flag, kpos, n + 1, scan_tmp, n_kept, st);
     // pair counts of the survivors; entries of kcnt beyond n_kept must read as zero for the scan
-    if (n == 0) { launch_exclusive_scan(kcnt, poff, 0, scan_tmp, a.total_pairs, st); return; }
+    if (n == 0) {
+        launch_exclusive_scan(kcnt, poff, 0, scan_tmp, a.total_pairs, st);
+        if (a.ctx_off)
+            launch_cbow_examples(kcnt, kword, poff, n_kept, 0, flag, kpos, scan_tmp, a.ctx_off,
+                                 a.centers, a.cap_examples, a.total_examples, st);
+        return;
+    }
     const dim3 grid(blocks_for(n, 256)), block(256);
     hipLaunchKernelGGL(set_u32_kernel, grid, block, 0, st, kcnt, n, 0u);
     if (a.interleave) hipLaunchKernelGGL(set_u32_kernel, grid, block, 0, st, kj, n, n);   // sorts last
@@ -149,6 +158,10 @@ void launch_make_pairs(const PairArgs& a, hipStream_t st) {
         launch_exclusive_scan(kcnt, poff, n, scan_tmp, a.total_pairs, st);
         hipLaunchKernelGGL(emit_pairs_kernel, grid, block, 0, st, kword, klo, khi, poff, n_kept,
                            (const uint32_t*)nullptr, a.in_idx, a.out_idx, a.capacity);
+        // bag-of-words examples: flag and kpos are free again after the compaction
+        if (a.ctx_off)
+            launch_cbow_examples(kcnt, kword, poff, n_kept, n, flag, kpos, scan_tmp, a.ctx_off,
+                                 a.centers, a.cap_examples, a.total_examples, st);
         return;
     }
     // Round-robin over the sentences: a stable sort of the survivors by their position within the

@@ -41,6 +41,14 @@ _SIGNATURES = {
     "w2v_make_pairs_interleaved": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_u32, c_u64,
                                                   c_u32, c_vp, c_vp, c_u64, ctypes.POINTER(c_u64),
                                                   c_vp]),
+    "w2v_cbow_dotprod": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_vp, c_u32, c_u32, c_u64, c_vp, c_vp]),
+    "w2v_cbow_adjust": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_vp, c_u32, c_u32, c_u64, c_vp,
+                                       ctypes.c_float, c_vp]),
+    "w2v_cbow_train_minibatch": (ctypes.c_int, [ctypes.POINTER(c_vp), c_u32, c_vp, c_vp, c_u32, c_vp,
+                                                c_u32, c_u32, c_u64, ctypes.c_float, c_vp, c_vp]),
+    "w2v_make_cbow_examples": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_u32, c_u64,
+                                              c_u32, c_vp, c_vp, c_vp, c_u64, c_u64,
+                                              ctypes.POINTER(c_u64), ctypes.POINTER(c_u64), c_vp]),
     "w2v_minibatch_seed": (c_u64, [c_u64, c_u64]),
     "w2v_shard_timing_enable": (ctypes.c_int, [c_vp, ctypes.c_int]),
     "w2v_shard_timing_read": (ctypes.c_int, [c_vp, c_vp, c_vp]),
@@ -213,6 +221,38 @@ class Shard:
                                     _stream(stream)))
         return int(cnt.value)
 
+    # -- continuous bag of words -----------------------------------------------------------------
+    def cbow_dotprod(self, ctx_off, ctx_idx, out_idx, k, seed, out=None, stream=None):
+        """ctx_off int32[n+1], ctx_idx int32[m], out_idx int32[n] (uint32 bits) on the device."""
+        n = out_idx.numel()
+        if out is None:
+            out = torch.empty((n, k + 1), dtype=torch.float32, device=out_idx.device)
+        _check(lib().w2v_cbow_dotprod(self.h, _dev(ctx_off, IDX, "ctx_off"),
+                                      _dev(ctx_idx, IDX, "ctx_idx"), ctx_idx.numel(),
+                                      _dev(out_idx, IDX, "out_idx"), n, int(k), int(seed),
+                                      _dev(out, torch.float32, "partial_dots"), _stream(stream)))
+        return out
+
+    def cbow_adjust(self, ctx_off, ctx_idx, out_idx, k, seed, coeffs, alpha, stream=None):
+        _check(lib().w2v_cbow_adjust(self.h, _dev(ctx_off, IDX, "ctx_off"),
+                                     _dev(ctx_idx, IDX, "ctx_idx"), ctx_idx.numel(),
+                                     _dev(out_idx, IDX, "out_idx"), out_idx.numel(), int(k), int(seed),
+                                     _dev(coeffs, torch.float32, "coeffs"), float(alpha),
+                                     _stream(stream)))
+
+    def make_cbow_examples(self, tokens, sent_off, token_base, epoch, corpus_seed, B, ctx_off, ctx_idx,
+                           out_idx, stream=None):
+        """Fills ctx_off (length cap+1), ctx_idx and out_idx (length cap) on the device; returns
+        the full (number of examples, number of context entries)."""
+        n_ex, n_ctx = c_u64(0), c_u64(0)
+        cap = min(out_idx.numel(), ctx_off.numel() - 1)
+        _check(lib().w2v_make_cbow_examples(
+            self.h, _dev(tokens, IDX, "tokens"), _dev(sent_off, torch.int64, "sent_off"),
+            sent_off.numel() - 1, tokens.numel(), int(token_base), int(epoch), int(corpus_seed), int(B),
+            _dev(ctx_off, IDX, "ctx_off"), _dev(ctx_idx, IDX, "ctx_idx"), _dev(out_idx, IDX, "out_idx"),
+            cap, ctx_idx.numel(), ctypes.byref(n_ex), ctypes.byref(n_ctx), _stream(stream)))
+        return int(n_ex.value), int(n_ctx.value)
+
     # -- timing ----------------------------------------------------------------------------------
     def timing_enable(self, on=True):
         _check(lib().w2v_shard_timing_enable(self.h, int(bool(on))))
@@ -234,3 +274,15 @@ def train_minibatch(shards, in_idx, out_idx, k, seed, alpha, loss=None, stream=N
                                      _dev(out_idx, IDX, "out_idx"), n, int(k), int(seed),
                                      float(alpha), _dev(loss, torch.float64, "loss"),
                                      _stream(stream)))
+
+
+def cbow_train_minibatch(shards, ctx_off, ctx_idx, out_idx, k, seed, alpha, loss=None, stream=None):
+    """One client step of the bag-of-words variant over the given shards
+    (w2v_cbow_train_minibatch)."""
+    S = len(shards)
+    arr = (c_vp * S)(*[s.h.value for s in shards])
+    _check(lib().w2v_cbow_train_minibatch(arr, S, _dev(ctx_off, IDX, "ctx_off"),
+                                          _dev(ctx_idx, IDX, "ctx_idx"), ctx_idx.numel(),
+                                          _dev(out_idx, IDX, "out_idx"), out_idx.numel(), int(k),
+                                          int(seed), float(alpha), _dev(loss, torch.float64, "loss"),
+                                          _stream(stream)))
