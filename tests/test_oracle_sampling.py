@@ -278,6 +278,31 @@ def test_T11_interleaved_is_a_reordering_with_centers_round_robin():
         assert sent.max() == off.size - 2
 
 
+def test_T11_interleaved_minibatches_take_every_center_from_a_different_sentence():
+    # The purpose of the option (Section 5.1, last paragraph): with more sentences in the block than
+    # centers in a minibatch, the input words of a minibatch come from (nearly) as many sentences --
+    # a sentence gives a second one only where the minibatch runs over the end of a round -- while
+    # the corpus-order walk takes them from a handful of sentences.
+    n_sent, L, B, n = 3000, 20, 5, 4096
+    tokens = np.arange(n_sent * L, dtype=np.uint32)       # word id == position
+    off = np.arange(0, n_sent * L + 1, L).astype(np.uint64)
+    kt = np.full(tokens.size, int(0.4 * 2 ** 32), np.uint64)
+    per_batch = {}
+    for inter in (False, True):
+        a, _, cnt = oracle.make_pairs(tokens, off, 0, 0, 3, B, kt, interleaved=inter)
+        got = []
+        for h in range(cnt // n):
+            centers = np.unique(a[h * n:(h + 1) * n])
+            got.append((centers.size, np.unique(centers // L).size))
+        per_batch[inter] = np.array(got)
+    plain, inter = per_batch[False], per_batch[True]
+    assert inter[0, 0] == inter[0, 1]                     # first round: one center per sentence
+    assert np.all(inter[:, 1] * 2 >= inter[:, 0])         # a minibatch spans at most two rounds ...
+    assert inter[:, 1].sum() > 0.85 * inter[:, 0].sum()   # ... and mostly one
+    assert np.all(plain[:, 1] * 4 < plain[:, 0])          # corpus order: several centers per sentence
+    assert abs(plain[:, 0].mean() - inter[:, 0].mean()) < 0.1 * plain[:, 0].mean()
+
+
 def test_T11_pair_count_is_the_sum_of_clipped_windows_and_no_pair_crosses_a_sentence():
     rng = np.random.default_rng(112)
     n, L, B = 3000, 15, 4
