@@ -321,3 +321,29 @@ def make_cbow_examples(tokens, sent_off, token_base, epoch, corpus_seed, B, keep
                                            U64(cap_ctx), ctypes.byref(nctx)))
     m = min(cnt, cap_examples)
     return off[:m + 1].copy(), ctx[:min(int(nctx.value), cap_ctx)].copy(), out[:m].copy(), cnt, int(nctx.value)
+
+
+# --- export and retrieval ----------------------------------------------------------------------------
+
+def export_rows(Ms, col_begins, d_total, rows):
+    """Vector export (Section 6.1.4): the shards' column slices of the listed rows, joined into
+    full vectors [m, d_total].  Ms[s] is the dense [V, d_s] matrix of shard s."""
+    rows = np.asarray(rows, dtype=np.int64)
+    out = np.zeros((rows.size, d_total), np.float32)
+    for M, c0 in zip(Ms, col_begins):
+        out[:, c0:c0 + M.shape[1]] = M[rows]
+    return out
+
+
+def topk_cosine(Qm, Cm, K, tau=-2.0):
+    """(idx uint32[Q,K], score float64[Q,K], count uint32[Q]) of orc_topk_cosine."""
+    Qm, Cm = _f32(Qm), _f32(Cm)
+    Q, d = Qm.shape
+    N = Cm.shape[0]
+    assert Cm.shape[1] == d
+    idx = np.empty((Q, K), np.uint32)
+    score = np.empty((Q, K), np.float64)
+    count = np.empty(Q, np.uint32)
+    lib().orc_topk_cosine(_p(Qm), U32(Q), _p(Cm), U32(N), U32(d), U32(K), ctypes.c_double(tau),
+                          _p(idx), _p(score), _p(count))
+    return idx, score, count

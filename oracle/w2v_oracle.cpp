@@ -12,6 +12,8 @@
 //                                  sum the partial dots and form G+ / G-)
 //   * Eq.1 / Eq.3 (objective), Eq.4 (gradient), Eq.5 (update), Section 5.1 (column slices, and
 //     the rule that adjust reads the vectors as they stood when the call began).
+//   * Section 6.1.4 (vector export: the shards' partial vectors joined column-wise) and the
+//     retrieval the vectors are trained for (Section 2, Section 7.3: top-K by cosine similarity).
 //   * Section 5.1's two extensions: interleaved minibatch formation (last paragraph) and the
 //     continuous-bag-of-words variant (footnote), the latter with the word2vec paper's model.
 // Where the paper only names a seeded random number generator, or defers to the word2vec paper
@@ -26,7 +28,8 @@
 // closed forms for zero output vectors; finite differences of the objective; the column-slice
 // invariant; chi-square of the sampler; alias-table reconstruction; window / subsample laws;
 // for the bag-of-words variant a matrix formulation, finite differences, and its reduction to
-// skip-gram when every example has one context word.
+// skip-gram when every example has one context word; for the retrieval, planar vectors with
+// known angles, scaled basis vectors, and an independent library's cosine matrix.
 // Nothing in this file is "parity unpinned".
 
 #include <algorithm>
@@ -677,6 +680,50 @@ void orc_token_draws(const uint32_t* tokens, uint64_t n_tokens, uint64_t token_b
         Quad q = philox((uint32_t)g, (uint32_t)(g >> 32), epoch, DOMAIN_TOKEN, corpus_seed);
         keep[t] = keep_thresh ? (uint8_t)((uint64_t)q.r[0] < keep_thresh[tokens[t]]) : (uint8_t)1;
         b[t] = 1 + (uint32_t)(((uint64_t)q.r[1] * (uint64_t)B) >> 32);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Retrieval by cosine similarity (Section 2: the K candidates most similar to a query vector are
+// retrieved; Section 7.3: K = 30, and only similarities above a threshold tau are kept).
+// Qm is [Q][d], Cm is [N][d], both dense row-major.  For query q the similarity with candidate c is
+//     (q . c) / (|q| |c|)          (0 when either vector is all zeros),
+// everything in double.  The candidates are ranked by decreasing similarity, equal similarities by
+// increasing index; the first K with similarity > tau are returned: idx[q][0..count[q]) and
+// score[q][0..count[q]), the rest of the K slots filled with 0xFFFFFFFF and 0.
+// ---------------------------------------------------------------------------------------------
+void orc_topk_cosine(const float* Qm, uint32_t Q, const float* Cm, uint32_t N, uint32_t d,
+                     uint32_t K, double tau, uint32_t* idx, double* score, uint32_t* count) {
+    std::vector<double> cnorm(N);
+    for (uint32_t c = 0; c < N; ++c) {
+        double s = 0.0;
+        for (uint32_t i = 0; i < d; ++i) s += (double)Cm[(uint64_t)c * d + i] * (double)Cm[(uint64_t)c * d + i];
+        cnorm[c] = std::sqrt(s);
+    }
+    std::vector<double> sim(N);
+    std::vector<uint32_t> order(N);
+    for (uint32_t q = 0; q < Q; ++q) {
+        const float* qv = Qm + (uint64_t)q * d;
+        double qs = 0.0;
+        for (uint32_t i = 0; i < d; ++i) qs += (double)qv[i] * (double)qv[i];
+        double qnorm = std::sqrt(qs);
+        for (uint32_t c = 0; c < N; ++c) {
+            const float* cv = Cm + (uint64_t)c * d;
+            double dot = 0.0;
+            for (uint32_t i = 0; i < d; ++i) dot += (double)qv[i] * (double)cv[i];
+            sim[c] = (qnorm > 0.0 && cnorm[c] > 0.0) ? dot / (qnorm * cnorm[c]) : 0.0;
+            order[c] = c;
+        }
+        std::stable_sort(order.begin(), order.end(),
+                         [&](uint32_t a, uint32_t b) { return sim[a] > sim[b]; });
+        uint32_t kept = 0;
+        for (uint32_t r = 0; r < K; ++r) {
+            bool ok = r < N && sim[order[r]] > tau;
+            idx[(uint64_t)q * K + r] = ok ? order[r] : 0xFFFFFFFFu;
+            score[(uint64_t)q * K + r] = ok ? sim[order[r]] : 0.0;
+            if (ok) ++kept;
+        }
+        count[q] = kept;
     }
 }
 
