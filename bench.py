@@ -294,6 +294,59 @@ def run_cbow(args, torch, w2v, workloads):
     print(json.dumps(out), flush=True)
 
 
+def run_topk(args, torch, w2v, workloads):
+    """Retrieval: the K most similar of N candidate vectors for each of Q queries (w2v_topk_cosine).
+    One step = one whole search.  The contraction runs on the fp32 matrix cores, so the roofline is
+    the dense fp32 MFMA peak; flops counted: 2 Q N d."""
+    Q, N, d, K = args.topk_queries, args.topk_candidates, 300, args.topk_k
+    steps, Wm = args.steps, max(args.warmup, 1)
+    t0 = time.perf_counter()
+    C = workloads.embedding_like(N, d, 7)
+    Qm = workloads.embedding_like(Q, d, 8)
+    log("setup: %d x %d candidates, %d queries generated in %.1f s" % (N, d, Q, time.perf_counter() - t0))
+    cd, qd = torch.from_numpy(C).cuda(), torch.from_numpy(Qm).cuda()
+    need = int(w2v.lib().w2v_topk_cosine_workspace(Q, N, args.topk_round))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    copy_probe(torch, args.copy_probe_mb)
+    for _ in range(Wm):
+        out = w2v.topk_cosine(qd, cd, K, -2.0, workspace=ws)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        out = w2v.topk_cosine(qd, cd, K, -2.0, workspace=ws)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    flops = 2.0 * Q * N * d
+    achieved = flops / (np.mean(ms) * 1e-3) / 1e12
+    res = {
+        "metric": "top-K cosine retrieval, queries/s on 1 MI355X", "value": Q * steps / dt,
+        "unit": "queries/s", "n_gpus": 1, "steps": steps, "warmup": Wm, "ms_per_step": dt * 1e3 / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "topk_cosine", "Q": Q, "N": N, "d": d, "K": K, "tau": None,
+                   "round_candidates": args.topk_round, "workspace_bytes": need},
+        "roofline": {"bound": "mfma", "kernel": "topk_scores_kernel (+ selection, whole call)",
+                     "achieved": achieved, "peak": 157.3, "unit": "TFLOP/s", "frac": achieved / 157.3,
+                     "traffic": None, "algorithmic_flops_per_launch": flops,
+                     "ms_per_launch": float(np.mean(ms))},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        m = min(Q, args.cpu_sample_pairs or 6)
+        t0 = time.perf_counter()
+        oi, osc, oc = oracle.topk_cosine(Qm[:m], C, K)
+        dtc = time.perf_counter() - t0
+        gi = w2v.index_to_numpy(out[0][:m])
+        res["cpu_baseline"] = {"value": m / dtc, "unit": "queries/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d queries against all %d candidates, %.1f s; %d of %d "
+                                         "indices equal the GPU's" % (m, N, dtc, int((gi == oi).sum()), m * K)}
+    print(json.dumps(res), flush=True)
+
+
 def distinct_rows(torch, shard, in_idx, out_idx, k, seed):
     """Distinct input rows and distinct output/negative rows of one minibatch (for byte counts)."""
     neg = shard.negatives(out_idx, k, seed)
@@ -309,8 +362,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="full300",
                     choices=["full300", "slice60", "tiny", "search200m", "stress25"])
-    ap.add_argument("--variant", default="sgns", choices=["sgns", "cbow"],
-                    help="cbow: the bag-of-words variant on the same text workload")
+    ap.add_argument("--variant", default="sgns", choices=["sgns", "cbow", "topk"],
+                    help="cbow: the bag-of-words variant on the same text workload; "
+                         "topk: cosine retrieval over exported vectors")
+    ap.add_argument("--topk-queries", type=int, default=4096)
+    ap.add_argument("--topk-candidates", type=int, default=1 << 20)
+    ap.add_argument("--topk-k", type=int, default=30)
+    ap.add_argument("--topk-round", type=int, default=8192, help="candidates per round")
     ap.add_argument("--cbow-examples", type=int, default=1 << 17, help="examples per cbow minibatch")
     ap.add_argument("--corpus-tokens", type=int, default=0, help="tokens of the corpus slice to generate")
     ap.add_argument("--cpu-sample-pairs", type=int, default=0,
@@ -334,6 +392,8 @@ def main():
     torch.cuda.set_device(0)
     if args.variant == "cbow":
         return run_cbow(args, torch, w2v, workloads)
+    if args.variant == "topk":
+        return run_topk(args, torch, w2v, workloads)
     wl = workloads.WORKLOADS[args.workload]
     K, Wm = args.steps, args.warmup
     if not args.cpu_sample_pairs:

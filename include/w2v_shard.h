@@ -197,6 +197,37 @@ int w2v_make_cbow_examples(w2v_shard* shard, const uint32_t* tokens_dev, const u
                            uint64_t cap_ctx, uint64_t* n_examples_host, uint64_t* n_ctx_host,
                            void* stream);
 
+/* ---- vector export (Section 6.1.4) ------------------------------------------------------------------
+ * Joins the partial vectors of the column shards into whole vectors: dst_dev[i][0..d_total) is row
+ * rows_dev[i] of matrix `which` (0 = input vectors, 1 = output vectors), shard s contributing columns
+ * [col_begin_s, col_begin_s + d_slice_s).  The shards must agree in V and d_total and their column
+ * ranges must tile [0, d_total) exactly (W2V_ERR_MISMATCH otherwise); any order.  dst_dev is a dense
+ * [m][d_total] device array owned by the caller.  A row >= V raises the sticky index flag of the shard
+ * and yields row 0. */
+int w2v_export_rows(w2v_shard* const* shards, uint32_t S, int which, const uint32_t* rows_dev,
+                    uint32_t m, float* dst_dev, void* stream);
+
+/* ---- retrieval by cosine similarity (Section 2; Section 7.3: K = 30, threshold 0.65) ----------------
+ * For each of the Q query vectors (queries_dev, dense [Q][d]) the K candidates (cands_dev, dense
+ * [N][d]) with the highest cosine similarity (q.c)/(|q||c|), ranked by decreasing similarity, equal
+ * similarities by increasing index; an all-zero vector has similarity 0 with everything.  Only
+ * similarities strictly above tau are returned (pass tau <= -2 for no threshold):
+ * out_idx_dev[q][0..count) / out_score_dev[q][0..count) hold them, the remaining slots of the K hold
+ * 0xFFFFFFFF / 0, and out_count_dev[q] (may be NULL) the count.  fp32 throughout; 1 <= K <=
+ * W2V_TOPK_MAX.
+ *
+ * The call allocates nothing: workspace_dev (256-byte aligned device memory, contents irrelevant
+ * before and after) holds the norms, the running best lists and, per query, room for one round of
+ * candidates.  w2v_topk_cosine_workspace(Q, N, r) is the size for rounds of r candidates (r = 0 or
+ * r >= N: a single round); a smaller workspace means more, shorter rounds (the minimum is r = 128),
+ * never a different result.  All work is queued on the stream; nothing is synchronised. */
+#define W2V_TOPK_MAX 64
+size_t w2v_topk_cosine_workspace(uint32_t Q, uint32_t N, uint32_t round_candidates);
+int w2v_topk_cosine(const float* queries_dev, uint32_t Q, const float* cands_dev, uint32_t N,
+                    uint32_t d, uint32_t K, float tau, uint32_t* out_idx_dev, float* out_score_dev,
+                    uint32_t* out_count_dev, void* workspace_dev, size_t workspace_bytes,
+                    void* stream);
+
 /* Seed of minibatch number h (the client picks a fresh seed per minibatch), a function of a master seed. */
 uint64_t w2v_minibatch_seed(uint64_t master_seed, uint64_t h);
 

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libw2v_shard.so")
 
-HIP_SOURCES = ["api.hip", "k_gather.hip", "k_sort.hip", "k_adjust.hip", "k_pairs.hip", "k_cbow.hip"]
+HIP_SOURCES = ["api.hip", "k_gather.hip", "k_sort.hip", "k_adjust.hip", "k_pairs.hip", "k_cbow.hip", "k_topk.hip"]
 CPP_SOURCES = ["tables.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -3,6 +3,7 @@
 // contract of every entry point.
 #include "../../include/w2v_shard.h"
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -907,6 +908,75 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
             queue_cbow_adjust(s0, shards[s], p, skw, sidx, skc, cidx, p.coeffs, nullptr, false, alpha, st);
         }
     }
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// export and retrieval
+// ---------------------------------------------------------------------------------------------
+extern "C" int w2v_export_rows(w2v_shard* const* shards, uint32_t S, int which,
+                               const uint32_t* rows, uint32_t m, float* dst, void* stream) {
+    if (!shards || (m && (!rows || !dst))) return fail(W2V_ERR_NULL, "NULL argument");
+    if (S == 0 || S > W2V_S_MAX) return fail(W2V_ERR_ARG, "S = %u outside 1..%d", S, W2V_S_MAX);
+    if (which != 0 && which != 1) return fail(W2V_ERR_ARG, "which must be 0 (input) or 1 (output)");
+    for (uint32_t s = 0; s < S; ++s) {
+        if (!shards[s]) return fail(W2V_ERR_NULL, "shards[%u] is NULL", s);
+        if (shards[s]->V != shards[0]->V || shards[s]->device != shards[0]->device ||
+            shards[s]->d_total != shards[0]->d_total)
+            return fail(W2V_ERR_MISMATCH, "shard %u differs from shard 0 in V, d_total or device", s);
+    }
+    // the column ranges must tile [0, d_total) exactly
+    std::vector<uint32_t> order(S);
+    for (uint32_t s = 0; s < S; ++s) order[s] = s;
+    std::sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) {
+        return shards[x]->col_begin < shards[y]->col_begin;
+    });
+    uint32_t next = 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        if (shards[order[s]]->col_begin != next)
+            return fail(W2V_ERR_MISMATCH, "the shards' columns do not tile [0, d_total): gap or "
+                        "overlap at column %u", next);
+        next += shards[order[s]]->d_slice;
+    }
+    if (next != shards[0]->d_total)
+        return fail(W2V_ERR_MISMATCH, "the shards cover %u of %u columns", next, shards[0]->d_total);
+    int rc = check_device(shards[0]);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    for (uint32_t s = 0; s < S; ++s) {
+        w2v_shard* sh = shards[s];
+        launch_export_rows(which ? sh->W : sh->U, sh->g, sh->d_slice, rows, m, sh->V, dst,
+                           sh->d_total, sh->col_begin, sh->err, st);
+    }
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+extern "C" size_t w2v_topk_cosine_workspace(uint32_t Q, uint32_t N, uint32_t round_candidates) {
+    if (Q == 0 || N == 0) return 0;
+    if (round_candidates == 0 || round_candidates > N) round_candidates = N;
+    return topk_workspace_bytes(Q, N, round_candidates);
+}
+
+extern "C" int w2v_topk_cosine(const float* queries, uint32_t Q, const float* cands, uint32_t N,
+                               uint32_t d, uint32_t K, float tau, uint32_t* out_idx,
+                               float* out_score, uint32_t* out_count, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    if (Q == 0) return W2V_OK;
+    if (K == 0 || K > W2V_TOPK_MAX) return fail(W2V_ERR_ARG, "K = %u outside 1..%d", K, W2V_TOPK_MAX);
+    if (N == 0 || d == 0) return fail(W2V_ERR_ARG, "N and d must be at least 1");
+    if (!queries || !cands || !out_idx || !out_score || !workspace)
+        return fail(W2V_ERR_NULL, "NULL argument");
+    if (N >= 0xFFFFFF00u || Q >= 0xFFFFFF00u) return fail(W2V_ERR_ARG, "Q and N must stay below 2^32 - 256");
+    if (!(tau == tau)) return fail(W2V_ERR_ARG, "tau is not a number");
+    if ((uintptr_t)workspace % 256) return fail(W2V_ERR_ARG, "workspace must be 256-byte aligned");
+    const uint32_t cap = topk_round_capacity(Q, N, workspace_bytes);
+    if (cap == 0)
+        return fail(W2V_ERR_ARG, "workspace of %zu bytes is too small: %zu are needed for rounds of "
+                    "128 candidates", workspace_bytes, topk_workspace_bytes(Q, N, 128));
+    launch_topk_cosine(queries, Q, cands, N, d, K, tau, out_idx, out_score, out_count, workspace, cap,
+                       (hipStream_t)stream);
     HIP_TRY(hipGetLastError());
     return W2V_OK;
 }

@@ -158,6 +158,18 @@ struct PairArgs {
 size_t pairs_scratch_u32(uint32_t n_tokens, bool interleave);
 void launch_make_pairs(const PairArgs& a, hipStream_t st);
 
+// ---- export and retrieval ----------------------------------------------------------------------------
+void launch_export_rows(const float* M, RowGeom g, uint32_t d_slice, const uint32_t* rows, uint32_t m,
+                        uint32_t V, float* dst, uint32_t d_total, uint32_t col_begin, uint32_t* err,
+                        hipStream_t st);
+// Workspace of the top-K search for rounds of `round_candidates` candidates, and the largest round a
+// given workspace allows (multiple of 128; 0: too small).
+size_t topk_workspace_bytes(uint32_t Q, uint32_t N, uint32_t round_candidates);
+uint32_t topk_round_capacity(uint32_t Q, uint32_t N, size_t workspace_bytes);
+uint32_t* launch_topk_cosine(const float* Qm, uint32_t Q, const float* Cm, uint32_t N, uint32_t d,
+                             uint32_t K, float tau, uint32_t* out_idx, float* out_score,
+                             uint32_t* out_count, void* workspace, uint32_t cap, hipStream_t st);
+
 // ---- continuous bag of words ----------------------------------------------------------------------
 // Per context entry: checked word, example number, weight 1/|C|; offsets are validated (error flag).
 void launch_cbow_entries(const uint32_t* ctx_off, const uint32_t* ctx_idx, uint32_t n, uint32_t m,

@@ -49,6 +49,10 @@ _SIGNATURES = {
     "w2v_make_cbow_examples": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_u32, c_u64,
                                               c_u32, c_vp, c_vp, c_vp, c_u64, c_u64,
                                               ctypes.POINTER(c_u64), ctypes.POINTER(c_u64), c_vp]),
+    "w2v_export_rows": (ctypes.c_int, [ctypes.POINTER(c_vp), c_u32, ctypes.c_int, c_vp, c_u32, c_vp, c_vp]),
+    "w2v_topk_cosine_workspace": (ctypes.c_size_t, [c_u32, c_u32, c_u32]),
+    "w2v_topk_cosine": (ctypes.c_int, [c_vp, c_u32, c_vp, c_u32, c_u32, c_u32, ctypes.c_float, c_vp,
+                                       c_vp, c_vp, c_vp, ctypes.c_size_t, c_vp]),
     "w2v_minibatch_seed": (c_u64, [c_u64, c_u64]),
     "w2v_shard_timing_enable": (ctypes.c_int, [c_vp, ctypes.c_int]),
     "w2v_shard_timing_read": (ctypes.c_int, [c_vp, c_vp, c_vp]),
@@ -286,3 +290,38 @@ def cbow_train_minibatch(shards, ctx_off, ctx_idx, out_idx, k, seed, alpha, loss
                                           _dev(out_idx, IDX, "out_idx"), out_idx.numel(), int(k),
                                           int(seed), float(alpha), _dev(loss, torch.float64, "loss"),
                                           _stream(stream)))
+
+
+def export_rows(shards, which, rows, out=None, stream=None):
+    """Whole vectors [m, d_total] of the listed rows, joined from the column shards
+    (w2v_export_rows)."""
+    S = len(shards)
+    arr = (c_vp * S)(*[s.h.value for s in shards])
+    m = rows.numel()
+    if out is None:
+        out = torch.empty((m, shards[0].d_total), dtype=torch.float32, device=rows.device)
+    _check(lib().w2v_export_rows(arr, S, int(which), _dev(rows, IDX, "rows"), m,
+                                 _dev(out, torch.float32, "dst"), _stream(stream)))
+    return out
+
+
+def topk_cosine(queries, cands, K, tau=-2.0, round_candidates=8192, workspace=None, stream=None):
+    """(idx int32[Q, K] (uint32 bits), score float32[Q, K], count int32[Q]) of w2v_topk_cosine.
+    ``workspace``: optional uint8 device tensor to reuse; otherwise one for rounds of
+    ``round_candidates`` candidates is allocated here."""
+    Q, d = queries.shape
+    N = cands.shape[0]
+    if cands.shape[1] != d:
+        raise ValueError("queries and candidates differ in width")
+    if workspace is None:
+        need = int(lib().w2v_topk_cosine_workspace(Q, N, int(round_candidates)))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=queries.device)
+    idx = torch.empty((Q, K), dtype=IDX, device=queries.device)
+    score = torch.empty((Q, K), dtype=torch.float32, device=queries.device)
+    count = torch.empty(Q, dtype=IDX, device=queries.device)
+    _check(lib().w2v_topk_cosine(_dev(queries, torch.float32, "queries"), Q,
+                                 _dev(cands, torch.float32, "cands"), N, d, int(K), float(tau),
+                                 _dev(idx, IDX, "out_idx"), _dev(score, torch.float32, "out_score"),
+                                 _dev(count, IDX, "out_count"), c_vp(workspace.data_ptr()),
+                                 workspace.numel(), _stream(stream)))
+    return idx, score, count

@@ -137,6 +137,30 @@ def iid_examples(wl, n, B, seed=None, cdf=None, min_ctx=1):
     return off, zipf_draw(cdf, int(off[-1]), rng), zipf_draw(cdf, n, rng)
 
 
+def embedding_like(n, d, seed, n_clusters=1000, spread=0.6, cluster_seed=0):
+    """n vectors of width d shaped like trained embeddings: a cluster direction (one of n_clusters
+    drawn from ``cluster_seed``, Zipf-popular) plus isotropic unit-variance noise times ``spread``,
+    with log-normal lengths.  Calls with the same cluster_seed share the directions, so queries
+    generated by one call have close neighbours among candidates generated by another.
+    float32 [n, d]."""
+    crng = np.random.Generator(np.random.PCG64(cluster_seed + 5000))
+    centers = crng.standard_normal((n_clusters, d)).astype(np.float32)
+    rng = np.random.Generator(np.random.PCG64(seed + 4000))
+    which = zipf_draw(zipf_cdf(n_clusters, 1.0), n, rng)
+    length = (np.exp(0.3 * rng.standard_normal(n)) / np.sqrt(d)).astype(np.float32)
+    x = np.empty((n, d), np.float32)
+    step = 1 << 16                                   # in slices: no second array of the full size
+    for a in range(0, n, step):
+        b = min(n, a + step)
+        part = rng.random((b - a, d), dtype=np.float32)
+        part -= np.float32(0.5)
+        part *= np.float32(spread * np.sqrt(12.0))
+        part += centers[which[a:b]]
+        part *= length[a:b, None]
+        x[a:b] = part
+    return x
+
+
 def uniform_coeffs(n, T, seed):
     """Harness-supplied coefficients uniform(-1, 1), float32 [n, T]."""
     rng = np.random.Generator(np.random.PCG64(seed + 2000))
