@@ -368,7 +368,7 @@ def main():
     ap.add_argument("--topk-queries", type=int, default=4096)
     ap.add_argument("--topk-candidates", type=int, default=1 << 20)
     ap.add_argument("--topk-k", type=int, default=30)
-    ap.add_argument("--topk-round", type=int, default=8192, help="candidates per round")
+    ap.add_argument("--topk-round", type=int, default=32768, help="candidates per round")
     ap.add_argument("--cbow-examples", type=int, default=1 << 17, help="examples per cbow minibatch")
     ap.add_argument("--corpus-tokens", type=int, default=0, help="tokens of the corpus slice to generate")
     ap.add_argument("--cpu-sample-pairs", type=int, default=0,

@@ -146,8 +146,10 @@ __global__ __launch_bounds__(TK_THREADS) void topk_scores_kernel(TopkArgs a) {
                 rb[i] = load_cols<VEC4>(brow[i], bok[i], kb + TK_BK + scol[i], a.d);
             }
         }
+        const int kmax = (int)min((uint32_t)TK_BK, a.d - kb);   // columns beyond d hold zeros: skipped
 #pragma unroll
         for (int kk = 0; kk < TK_BK; kk += 2) {
+            if (kk >= kmax) break;
             const float a0 = As[wm * 64 + fr][kk + fk];
             const float a1 = As[wm * 64 + 32 + fr][kk + fk];
             const float b0 = Bs[wn * 64 + fr][kk + fk];
@@ -336,9 +338,13 @@ uint32_t* launch_topk_cosine(const float* Qm, uint32_t Q, const float* Cm, uint3
     a.invq = invq; a.invc = invc; a.theta = theta; a.cnt = cnt; a.pend = pend; a.cap = cap;
     a.err = err;
     a.nq_tiles = (Q + TK_BQ - 1) / TK_BQ;
-    for (uint64_t begin = 0; begin < N; begin += cap) {
+    // The first rounds are short and grow fourfold: with a threshold from the first few hundred
+    // candidates only a small share of a full round's scores reaches the pending lists.
+    uint64_t len = TK_BC;
+    for (uint64_t begin = 0; begin < N; begin += len, len = (len * 4 < cap ? len * 4 : cap)) {
+        if (len > cap) len = cap;
         a.c_begin = (uint32_t)begin;
-        a.c_end = (uint32_t)(begin + cap < N ? begin + cap : N);
+        a.c_end = (uint32_t)(begin + len < N ? begin + len : N);
         a.nc_tiles = (a.c_end - a.c_begin + TK_BC - 1) / TK_BC;
         const uint32_t total = a.nq_tiles * a.nc_tiles;
         const dim3 grid(((total + 7u) / 8u) * 8u), block(TK_THREADS);

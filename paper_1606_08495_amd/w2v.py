@@ -305,7 +305,7 @@ def export_rows(shards, which, rows, out=None, stream=None):
     return out
 
 
-def topk_cosine(queries, cands, K, tau=-2.0, round_candidates=8192, workspace=None, stream=None):
+def topk_cosine(queries, cands, K, tau=-2.0, round_candidates=32768, workspace=None, stream=None):
     """(idx int32[Q, K] (uint32 bits), score float32[Q, K], count int32[Q]) of w2v_topk_cosine.
     ``workspace``: optional uint8 device tensor to reuse; otherwise one for rounds of
     ``round_candidates`` candidates is allocated here."""
