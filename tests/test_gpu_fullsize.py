@@ -228,3 +228,74 @@ def test_stress25_reduced_n_sampled():
 def test_search200m_reduced_n_sampled():
     """V = 200M, d_slice = 60 of 300, k = 10, Zipf(0.9): heavy tail, rows rarely reused."""
     reduced_n_step("search200m", 1 << 18, 64_000)
+
+
+@pytest.mark.parametrize("init_w", [True, False])
+def test_full300_cbow_step_sampled(init_w):
+    """The bag-of-words benchmark configuration: V = 10M, d = 300, 2^17 examples from the corpus,
+    k = 5: make_cbow_examples + cbow_train_minibatch; examples in full, updated rows on samples."""
+    wl = workloads.WORKLOADS["full300"]
+    rng = np.random.default_rng(17)
+    cdf = workloads.zipf_cdf(wl.V, wl.zipf_s)
+    counts = workloads.analytic_counts(wl.V, wl.zipf_s, wl.corpus_tokens)
+    tokens, off = workloads.corpus(wl, 400_000, cdf=cdf)
+    del cdf
+    say("full300 cbow: building shard", "W uniform" if init_w else "W zero")
+    sh = w2v.Shard(wl.V, wl.d_slice, wl.seed, init_mode=1 if init_w else 0)
+    sh.set_counts(counts, wl.subsample_t)
+    th, al = oracle.build_alias(counts)
+    kt = oracle.build_keep(counts, wl.subsample_t)
+    n_tok = tokens.size
+    co = torch.empty(n_tok + 1, dtype=torch.int32, device="cuda")
+    cx = torch.empty(n_tok * 2 * wl.window, dtype=torch.int32, device="cuda")
+    ce = torch.empty(n_tok, dtype=torch.int32, device="cuda")
+    n_ex, n_ctx = sh.make_cbow_examples(dev(tokens), torch.from_numpy(off.astype(np.int64)).cuda(), 0, 0,
+                                        wl.seed, wl.window, co, cx, ce)
+    ooff, octx, oout, ocnt, onctx = oracle.make_cbow_examples(tokens, off, 0, 0, wl.seed, wl.window, kt)
+    assert (n_ex, n_ctx) == (ocnt, onctx)
+    assert np.array_equal(w2v.index_to_numpy(co[:n_ex + 1]), ooff)
+    assert np.array_equal(w2v.index_to_numpy(cx[:n_ctx]), octx)
+    assert np.array_equal(w2v.index_to_numpy(ce[:n_ex]), oout)
+    n = 1 << 17
+    assert n_ex >= n
+    m = int(ooff[n])
+    off_n, ctx_n, out_n = ooff[:n + 1], octx[:m], oout[:n]
+    seed = w2v.minibatch_seed(wl.seed, 0)
+    alpha = workloads.alpha_schedule(wl, 0, 1000)
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    w2v.cbow_train_minibatch([sh], co[:n + 1].contiguous(), cx[:m].contiguous(), ce[:n].contiguous(),
+                             wl.k, seed, alpha, loss=loss)
+    sh.status()
+    neg = oracle.negatives(out_n, wl.k, seed, th, al)
+    rows = np.concatenate([out_n[:, None], neg], axis=1)
+    samp_u = sample_rows(ctx_n, 16, 200, rng)
+    samp_w = sample_rows(rows.ravel(), 16, 800, rng)
+    # every example that touches a sampled row, whole
+    ex_of = np.repeat(np.arange(n), np.diff(off_n.astype(np.int64)))
+    hit = np.zeros(n, bool)
+    hit[ex_of[np.isin(ctx_n, samp_u)]] = True
+    hit |= np.isin(rows, samp_w).any(axis=1)
+    sel = np.flatnonzero(hit)
+    say("   sub-minibatch of", sel.size, "examples for", samp_u.size, "+", samp_w.size, "rows")
+    lens = np.diff(off_n.astype(np.int64))[sel]
+    sub_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint32)
+    sub_ctx = np.concatenate([ctx_n[off_n[p]:off_n[p + 1]] for p in sel])
+    sub_rows = rows[sel]
+    words_u, cctx = np.unique(sub_ctx, return_inverse=True)
+    words_w, cr = np.unique(sub_rows.ravel(), return_inverse=True)
+    U = oracle.init_rows(wl.seed, wl.d_total, 0, wl.d_slice, 0, words_u.astype(np.uint32))
+    W = (oracle.init_rows(wl.seed, wl.d_total, 0, wl.d_slice, 1, words_w.astype(np.uint32)) if init_w
+         else np.zeros((words_w.size, wl.d_slice), np.float32))
+    cr = cr.reshape(sub_rows.shape).astype(np.uint32)
+    g = oracle.coeffs([oracle.cbow_dots(U, W, sub_off, cctx.astype(np.uint32), cr)])
+    oracle.cbow_adjust_rows(U, W, sub_off, cctx.astype(np.uint32), cr, g, alpha)
+    gu = sh.get_rows(0, dev(samp_u)).cpu().numpy()
+    gw = sh.get_rows(1, dev(samp_w)).cpu().numpy()
+    eu = vec_error(gu, U[np.searchsorted(words_u, samp_u)])
+    ew = vec_error(gw, W[np.searchsorted(words_w, samp_w)])
+    say("   U error", eu, "W error", ew)
+    assert eu <= TOL1 and ew <= TOL1
+    if not init_w:
+        assert abs(loss.item() - n * (wl.k + 1) * np.log(2.0)) <= 1e-6 * loss.item()
+        assert np.array_equal(gu, oracle.init_rows(wl.seed, wl.d_total, 0, wl.d_slice, 0, samp_u))
+    sh.destroy()
