@@ -109,16 +109,19 @@ void launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32
 }
 
 // ---------------------------------------------------------------------------------------------
-// Radix sort pass.  A block owns a tile of 256 x 8 consecutive elements; wave w of the block owns
+// Radix sort pass.  A block owns a tile of 256 x 16 consecutive elements; wave w of the block owns
 // the w-th quarter of the tile and walks it in order, 64 elements at a time.
 //   histogram : per-block digit counts, stored digit-major [256][blocks]
 //   digit scan: per digit, exclusive prefix of its counts over the blocks, and the digit's total
 //   (prefix of the totals + that prefix = where a block's elements of a digit start in the output)
 //   scatter   : each element's position = that start + its rank among the block's elements with
-//               the same digit, counted in tile order -> stable.
+//               the same digit, counted in tile order -> stable.  The tile is first put in that
+//               order in LDS and then written out position by position, so that the stores of
+//               neighbouring threads fall into the same digit run (coalesced pieces of about
+//               tile/256 elements) instead of single 4-byte stores all over the output.
 // ---------------------------------------------------------------------------------------------
 constexpr int SORT_THREADS = 256;
-constexpr int SORT_ITEMS = 8;
+constexpr int SORT_ITEMS = 16;
 constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
 constexpr int SORT_WAVES = SORT_THREADS / 64;
 constexpr int SORT_WAVE_SPAN = 64 * SORT_ITEMS;
@@ -145,6 +148,9 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, uint32_t n, uint32_t shift,
     uint32_t nblocks, const uint32_t* __restrict__ offsets, const uint32_t* __restrict__ digit_total) {
     __shared__ uint32_t cnt[SORT_WAVES][256];
+    __shared__ uint32_t to_global[256];
+    __shared__ uint32_t s_key[SORT_TILE];
+    __shared__ uint32_t s_val[SORT_TILE];
     __shared__ uint32_t wave_sums[4];
     __shared__ uint32_t total_all;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -183,25 +189,43 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
         if (valid && (same & below) == 0) cnt[wave][d] = before + (uint32_t)__popcll(same);
     }
     __syncthreads();
-    {   // thread t owns digit t: turn per-wave counts into per-wave starts in the output
-        uint32_t d = threadIdx.x;
-        uint32_t run = digit_base + offsets[(uint64_t)d * nblocks + blockIdx.x];
+    // Thread t owns digit t.  The tile is first put in sorted order in LDS (digit by digit, within
+    // a digit wave by wave), then copied out position by position: neighbouring threads then write
+    // neighbouring addresses inside each digit's run instead of 4-byte pieces all over the output.
+    {
+        const uint32_t d = threadIdx.x;
+        uint32_t c[SORT_WAVES], tile_count = 0;
 #pragma unroll
-        for (int w = 0; w < SORT_WAVES; ++w) {
-            uint32_t c = cnt[w][d];
-            cnt[w][d] = run;
-            run += c;
-        }
+        for (int w = 0; w < SORT_WAVES; ++w) { c[w] = cnt[w][d]; tile_count += c[w]; }
+        const uint32_t local_start = block_exclusive_scan(tile_count, wave_sums, &total_all);
+        uint32_t run = local_start;
+#pragma unroll
+        for (int w = 0; w < SORT_WAVES; ++w) { cnt[w][d] = run; run += c[w]; }
+        // output position = to_global[digit] + position in the sorted tile (mod 2^32 arithmetic)
+        to_global[d] = digit_base + offsets[(uint64_t)d * nblocks + blockIdx.x] - local_start;
     }
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < SORT_ITEMS; ++e) {
         uint64_t i = base + (uint64_t)e * 64 + lane;
         if (i < n) {
-            uint32_t d = (key[e] >> shift) & 255u;
-            uint32_t pos = cnt[wave][d] + rank[e];
-            keys_out[pos] = key[e];
-            vals_out[pos] = val[e];
+            const uint32_t d = (key[e] >> shift) & 255u;
+            const uint32_t lp = cnt[wave][d] + rank[e];
+            s_key[lp] = key[e];
+            s_val[lp] = val[e];
+        }
+    }
+    __syncthreads();
+    const uint64_t tile_base = (uint64_t)blockIdx.x * SORT_TILE;
+    const uint32_t in_tile = (uint32_t)min((uint64_t)SORT_TILE, (uint64_t)n - tile_base);
+#pragma unroll
+    for (int e = 0; e < SORT_ITEMS; ++e) {
+        const uint32_t lp = (uint32_t)e * SORT_THREADS + threadIdx.x;
+        if (lp < in_tile) {
+            const uint32_t k = s_key[lp];
+            const uint32_t pos = to_global[(k >> shift) & 255u] + lp;
+            keys_out[pos] = k;
+            vals_out[pos] = s_val[lp];
         }
     }
 }
