@@ -254,3 +254,56 @@ def test_cbow_bad_offsets_and_words_raise_the_flag_without_a_fault():
     assert e.value.code == -2
     sh.status()
     sh.destroy()
+
+
+@pytest.mark.parametrize("V,d,n,k,ctx_len", [(2, 60, 50, 3, 5), (1000, 60, 3, 64, 2000), (300, 300, 1, 5, 1),
+                                             (5000, 8, 9000, 1, 3)])
+def test_cbow_edge_shapes(V, d, n, k, ctx_len):
+    say("cbow edge", V, d, n, k, ctx_len)
+    rng = np.random.default_rng(V + n)
+    counts = zipf_counts(V)
+    th, al = oracle.build_alias(counts)
+    sh = make_shard(V, d, 6, counts)
+    U, W = oracle_state(V, d, 6)
+    lens = np.full(n, ctx_len)
+    lens[0] = 0 if n > 1 else ctx_len            # an empty context in front
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint32)
+    ctx = rng.integers(0, V, int(off[-1])).astype(np.uint32)
+    out = rng.integers(0, V, n).astype(np.uint32)
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    alpha = 0.025 if V > 2 else 1e-4
+    w2v.cbow_train_minibatch([sh], dev(off), dev(ctx), dev(out), k, 31, alpha, loss=loss)
+    ref = oracle.cbow_train_minibatch([U], [W], off, ctx, out, k, 31, th, al, alpha)
+    eu, ew = vec_error(all_rows(sh, 0), U), vec_error(all_rows(sh, 1), W)
+    say("  errors", eu, ew)
+    assert eu <= TOL1 and ew <= TOL1 and abs(loss.item() - ref) <= 1e-5 * abs(ref)
+    sh.status()
+    sh.destroy()
+
+
+def test_cbow_no_examples_and_no_text():
+    V = 50
+    sh = make_shard(V, 12, 1, np.ones(V, np.uint64))
+    before = (all_rows(sh, 0), all_rows(sh, 1))
+    empty = torch.empty(0, dtype=torch.int32, device="cuda")
+    loss = torch.ones(1, dtype=torch.float64, device="cuda")
+    w2v.cbow_train_minibatch([sh], dev(np.zeros(1, np.uint32)), empty, empty, 5, 1, 0.1, loss=loss)
+    assert loss.item() == 0.0
+    # examples whose contexts are all empty: nothing moves
+    off = dev(np.zeros(4, np.uint32))
+    w2v.cbow_train_minibatch([sh], off, empty, dev(np.array([1, 2, 3], np.uint32)), 5, 1, 0.1)
+    assert np.array_equal(all_rows(sh, 0), before[0]) and np.array_equal(all_rows(sh, 1), before[1])
+    # text of one-word sentences gives no example; so does no text at all
+    co = torch.full((11,), 7, dtype=torch.int32, device="cuda")
+    cx = torch.empty(40, dtype=torch.int32, device="cuda")
+    ce = torch.empty(10, dtype=torch.int32, device="cuda")
+    toks = dev(np.arange(10, dtype=np.uint32))
+    n_ex, n_ctx = sh.make_cbow_examples(toks, torch.arange(11, dtype=torch.int64, device="cuda"), 0, 0, 1, 3,
+                                        co, cx, ce)
+    assert (n_ex, n_ctx) == (0, 0) and co[0].item() == 0
+    co.fill_(7)
+    n_ex, n_ctx = sh.make_cbow_examples(empty, torch.zeros(1, dtype=torch.int64, device="cuda"), 0, 0, 1, 3,
+                                        co, cx, ce)
+    assert (n_ex, n_ctx) == (0, 0) and co[0].item() == 0
+    sh.status()
+    sh.destroy()
