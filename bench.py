@@ -336,7 +336,7 @@ def run_topk(args, torch, w2v, workloads):
     }
     if not args.no_cpu_baseline:
         import oracle
-        m = min(Q, args.cpu_sample_pairs or 6)
+        m = min(Q, args.cpu_sample_pairs or 48)
         t0 = time.perf_counter()
         oi, osc, oc = oracle.topk_cosine(Qm[:m], C, K)
         dtc = time.perf_counter() - t0
