@@ -71,6 +71,7 @@ struct w2v_shard {
     // into the caller's stream by an event before its result is used
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_keys = nullptr, ev_join = nullptr;
+    hipEvent_t ev_coeffs = nullptr, ev_wdone = nullptr, ev_tails = nullptr;
     bool overlap = true;
     // timing
     bool timing = false;
@@ -175,7 +176,8 @@ struct Plan {
     float* delta; uint32_t* dkey;
     float* pa_rows; uint32_t* pa_keys;     // input side, level 1 slots
     float* pb_rows; uint32_t* pb_keys;     // output side, level 1 slots
-    float* pc_rows; uint32_t* pc_keys;     // level 2 slots of either side
+    float* pc_rows; uint32_t* pc_keys;     // level 2 slots, output side
+    float* pe_rows; uint32_t* pe_keys;     // level 2 slots, input side (the two sides' tails may overlap)
     uint32_t slots_u1, slots_w1, slots_2;
     size_t bytes;
 };
@@ -208,6 +210,7 @@ Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_
         p.pa_rows = c.take<float>((size_t)p.slots_u1 * row); p.pa_keys = c.take<uint32_t>(p.slots_u1 + 1);
         p.pb_rows = c.take<float>((size_t)p.slots_w1 * row); p.pb_keys = c.take<uint32_t>(p.slots_w1 + 1);
         p.pc_rows = c.take<float>((size_t)p.slots_2 * row);  p.pc_keys = c.take<uint32_t>(p.slots_2 + 1);
+        p.pe_rows = c.take<float>((size_t)p.slots_2 * row);  p.pe_keys = c.take<uint32_t>(p.slots_2 + 1);
     }
     p.bytes = c.off + 256;
     return p;
@@ -233,6 +236,9 @@ int ensure_side_stream(w2v_shard* sh) {
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_fork, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_keys, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_join, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&sh->ev_coeffs, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&sh->ev_wdone, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&sh->ev_tails, hipEventDisableTiming));
     return W2V_OK;
 }
 
@@ -280,10 +286,17 @@ void join_output_sort(w2v_shard* sh, hipStream_t st) {
 }
 
 // The update of one shard from given coefficients (or, fused, from its own dots).
+// After the input-side kernel the coefficients exist, so the minibatch loss (if asked for, fused
+// form only) is summed on the second stream while the output side runs; after the output-side
+// kernel the two sides' remaining work is independent -- the output side's higher reduction levels
+// go to the second stream, the input side's write-back and levels stay on the caller's stream --
+// and the caller's stream finally waits for the second one.
 void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* sku,
                   const uint32_t* perm, const uint32_t* skw, const uint32_t* sidx,
                   const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
-                  hipStream_t st) {
+                  double* loss_out, hipStream_t st) {
+    const bool two = ws_owner->overlap && ws_owner->side;
+    hipStream_t side = two ? ws_owner->side : st;
     {
         Phase ph(ws_owner, W2V_PH_USIDE, st);
         USideArgs a{};
@@ -292,6 +305,14 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         a.dots_out = nullptr; a.delta = p.delta; a.dkey = p.dkey;
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
         launch_useg(a, st);
+    }
+    if (loss_out) {
+        if (two) {
+            (void)hipEventRecord(ws_owner->ev_coeffs, st);
+            (void)hipStreamWaitEvent(side, ws_owner->ev_coeffs, 0);
+        }
+        Phase ph(ws_owner, W2V_PH_COEFF, side);
+        launch_loss_from_coeffs(fused ? coeffs_out : coeffs_in, p.n, p.T, p.loss_tmp, loss_out, side);
     }
     join_output_sort(ws_owner, st);
     {
@@ -302,12 +323,21 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         w.prows = p.pb_rows; w.pkeys = p.pb_keys;
         launch_wseg(w, st);
     }
+    if (two) {
+        (void)hipEventRecord(ws_owner->ev_wdone, st);
+        (void)hipStreamWaitEvent(side, ws_owner->ev_wdone, 0);
+    }
+    {
+        Phase ph(ws_owner, W2V_PH_APPLY, side);
+        run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, side);
+    }
+    if (two) (void)hipEventRecord(ws_owner->ev_tails, side);
     {
         Phase ph(ws_owner, W2V_PH_APPLY, st);
-        run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st);
         launch_apply_delta(sh->U, sh->g, p.delta, p.dkey, p.n, alpha, st);
-        run_tails(sh, sh->U, alpha, p.pa_rows, p.pa_keys, p.slots_u1, p.pc_rows, p.pc_keys, st);
+        run_tails(sh, sh->U, alpha, p.pa_rows, p.pa_keys, p.slots_u1, p.pe_rows, p.pe_keys, st);
     }
+    if (two) (void)hipStreamWaitEvent(st, ws_owner->ev_tails, 0);
 }
 
 }  // namespace
@@ -398,6 +428,9 @@ extern "C" int w2v_shard_destroy(w2v_shard* sh) {
     if (sh->ev_fork) (void)hipEventDestroy(sh->ev_fork);
     if (sh->ev_keys) (void)hipEventDestroy(sh->ev_keys);
     if (sh->ev_join) (void)hipEventDestroy(sh->ev_join);
+    if (sh->ev_coeffs) (void)hipEventDestroy(sh->ev_coeffs);
+    if (sh->ev_wdone) (void)hipEventDestroy(sh->ev_wdone);
+    if (sh->ev_tails) (void)hipEventDestroy(sh->ev_tails);
     if (sh->side) (void)hipStreamDestroy(sh->side);
     delete sh;
     return W2V_OK;
@@ -593,7 +626,7 @@ extern "C" int w2v_adjust(w2v_shard* sh, const uint32_t* in_idx, const uint32_t*
     uint32_t *sku, *perm, *skw, *sidx;
     rc = queue_keys_and_sorts(sh, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);
     if (rc) return rc;
-    queue_adjust(sh, sh, p, sku, perm, skw, sidx, coeffs, nullptr, false, alpha, st);
+    queue_adjust(sh, sh, p, sku, perm, skw, sidx, coeffs, nullptr, false, alpha, nullptr, st);
     HIP_TRY(hipGetLastError());
     return W2V_OK;
 }
@@ -634,11 +667,7 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
     rc = queue_keys_and_sorts(s0, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);
     if (rc) return rc;
     if (fused) {
-        queue_adjust(s0, s0, p, sku, perm, skw, sidx, nullptr, p.coeffs, true, alpha, st);
-        if (loss) {
-            Phase ph(s0, W2V_PH_COEFF, st);
-            launch_loss_from_coeffs(p.coeffs, n, p.T, p.loss_tmp, loss, st);
-        }
+        queue_adjust(s0, s0, p, sku, perm, skw, sidx, nullptr, p.coeffs, true, alpha, loss, st);
     } else {
         PartialPtrs pp{};
         {
@@ -654,7 +683,7 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
             launch_coeffs(pp, S, n, p.T, p.coeffs, p.loss_tmp, loss, st);
         }
         for (uint32_t s = 0; s < S; ++s)
-            queue_adjust(s0, shards[s], p, sku, perm, skw, sidx, p.coeffs, nullptr, false, alpha, st);
+            queue_adjust(s0, shards[s], p, sku, perm, skw, sidx, p.coeffs, nullptr, false, alpha, nullptr, st);
     }
     HIP_TRY(hipGetLastError());
     return W2V_OK;

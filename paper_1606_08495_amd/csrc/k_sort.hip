@@ -109,7 +109,7 @@ void launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32
 }
 
 // ---------------------------------------------------------------------------------------------
-// Radix sort pass.  A block owns a tile of 256 x 16 consecutive elements; wave w of the block owns
+// Radix sort pass.  A block owns a tile of 256 x ITEMS consecutive elements; wave w of the block owns
 // the w-th quarter of the tile and walks it in order, 64 elements at a time.
 //   histogram : per-block digit counts, stored digit-major [256][blocks]
 //   digit scan: per digit, exclusive prefix of its counts over the blocks, and the digit's total
@@ -121,15 +121,20 @@ void launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32
 //               tile/256 elements) instead of single 4-byte stores all over the output.
 // ---------------------------------------------------------------------------------------------
 constexpr int SORT_THREADS = 256;
-constexpr int SORT_ITEMS = 16;
-constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
 constexpr int SORT_WAVES = SORT_THREADS / 64;
-constexpr int SORT_WAVE_SPAN = 64 * SORT_ITEMS;
+// Elements per thread (ITEMS): 16 for large inputs (long coalesced pieces, few blocks to scan over),
+// 4 below SORT_SMALL_N elements, where 16 would leave most of the chip without a block.
+constexpr int SORT_ITEMS_LARGE = 16;
+constexpr int SORT_ITEMS_SMALL = 4;
+constexpr uint32_t SORT_SMALL_N = 1u << 22;
+static inline int sort_items_for(uint32_t n) { return n < SORT_SMALL_N ? SORT_ITEMS_SMALL : SORT_ITEMS_LARGE; }
 
+template <int SORT_ITEMS>
 __global__ __launch_bounds__(SORT_THREADS) void sort_hist_kernel(const uint32_t* __restrict__ keys,
                                                                  uint32_t n, uint32_t shift,
                                                                  uint32_t nblocks,
                                                                  uint32_t* __restrict__ hist) {
+    constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
     __shared__ uint32_t h[256];
     h[threadIdx.x] = 0;
     __syncthreads();
@@ -143,10 +148,13 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_hist_kernel(const uint32_t*
     hist[(uint64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
 }
 
+template <int SORT_ITEMS>
 __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
     const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
     uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, uint32_t n, uint32_t shift,
     uint32_t nblocks, const uint32_t* __restrict__ offsets, const uint32_t* __restrict__ digit_total) {
+    constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
+    constexpr int SORT_WAVE_SPAN = 64 * SORT_ITEMS;
     __shared__ uint32_t cnt[SORT_WAVES][256];
     __shared__ uint32_t to_global[256];
     __shared__ uint32_t s_key[SORT_TILE];
@@ -251,7 +259,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void sort_digit_scan_kernel(uint32_t*
 }
 
 size_t sort_scratch_u32(uint32_t n) {
-    uint32_t nblocks = blocks_for(n, SORT_TILE);
+    uint32_t nblocks = blocks_for(n, SORT_THREADS * sort_items_for(n));
     uint32_t hist = 256u * (nblocks ? nblocks : 1u);
     return (size_t)hist + 256 + 8;
 }
@@ -261,7 +269,8 @@ void launch_sort_pairs(const uint32_t* keys_in, uint32_t* k0, uint32_t* v0, uint
                        uint32_t** out_vals, hipStream_t st) {
     if (bits == 0) bits = 1;
     uint32_t passes = (bits + 7) / 8;
-    uint32_t nblocks = blocks_for(n, SORT_TILE);
+    const bool small = sort_items_for(n) == SORT_ITEMS_SMALL;
+    uint32_t nblocks = blocks_for(n, SORT_THREADS * sort_items_for(n));
     uint32_t hist_len = 256u * nblocks;
     uint32_t* hist = tmp;
     uint32_t* digit_total = tmp + hist_len;
@@ -273,12 +282,20 @@ void launch_sort_pairs(const uint32_t* keys_in, uint32_t* k0, uint32_t* v0, uint
     uint32_t *kout = k0, *vout = v0;
     for (uint32_t ps = 0; ps < passes; ++ps) {
         uint32_t shift = ps * 8;
-        hipLaunchKernelGGL(sort_hist_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, st, kin, n,
-                           shift, nblocks, hist);
+        if (small)
+            hipLaunchKernelGGL(sort_hist_kernel<SORT_ITEMS_SMALL>, dim3(nblocks), dim3(SORT_THREADS), 0,
+                               st, kin, n, shift, nblocks, hist);
+        else
+            hipLaunchKernelGGL(sort_hist_kernel<SORT_ITEMS_LARGE>, dim3(nblocks), dim3(SORT_THREADS), 0,
+                               st, kin, n, shift, nblocks, hist);
         hipLaunchKernelGGL(sort_digit_scan_kernel, dim3(256), dim3(SCAN_THREADS), 0, st, hist,
                            nblocks, digit_total);
-        hipLaunchKernelGGL(sort_scatter_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, st, kin, vin,
-                           kout, vout, n, shift, nblocks, hist, digit_total);
+        if (small)
+            hipLaunchKernelGGL(sort_scatter_kernel<SORT_ITEMS_SMALL>, dim3(nblocks), dim3(SORT_THREADS),
+                               0, st, kin, vin, kout, vout, n, shift, nblocks, hist, digit_total);
+        else
+            hipLaunchKernelGGL(sort_scatter_kernel<SORT_ITEMS_LARGE>, dim3(nblocks), dim3(SORT_THREADS),
+                               0, st, kin, vin, kout, vout, n, shift, nblocks, hist, digit_total);
         *out_keys = kout;
         *out_vals = vout;
         kin = kout; vin = vout;
