@@ -757,22 +757,47 @@ int check_cbow_batch(const w2v_shard* sh, uint32_t n, uint32_t k, uint32_t m) {
 
 // Checked context entries, example numbers and weights, the destination keys, and (for adjust)
 // both sorts: destinations of the M output-side contributions, words of the m context entries.
-void queue_cbow_indices(w2v_shard* sh, CbowPlan& p, const uint32_t* ctx_off, const uint32_t* ctx_idx,
-                        const uint32_t* out_idx, uint32_t k, uint64_t seed, bool sorts,
-                        uint32_t** skw, uint32_t** sidx, uint32_t** skc, uint32_t** cidx,
-                        hipStream_t st) {
+// With the second stream, the keys and the sorts are queued there (they depend on the indices
+// only) while the caller's stream forms the hidden vectors; cbow_wait_keys / join_output_sort make
+// the caller's stream wait for them where they are first needed.
+int queue_cbow_indices(w2v_shard* sh, CbowPlan& p, const uint32_t* ctx_off, const uint32_t* ctx_idx,
+                       const uint32_t* out_idx, uint32_t k, uint64_t seed, bool sorts,
+                       uint32_t** skw, uint32_t** sidx, uint32_t** skc, uint32_t** cidx,
+                       hipStream_t st) {
     {
         Phase ph(sh, W2V_PH_NEG, st);
         launch_cbow_entries(ctx_off, ctx_idx, p.n, p.m, sh->V, p.ctx_safe, p.ex_of, p.weight,
                             sh->err, st);
         launch_iota(p.iota, p.n, st);
-        launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, p.n, k, seed, p.keys, sh->err, st);
     }
-    if (!sorts) return;
-    Phase ph(sh, W2V_PH_SORT, st);
-    const uint32_t bits = key_bits(sh->V);
-    launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp_w, skw, sidx, st);
-    launch_sort_pairs(p.ctx_safe, p.ck0, p.cv0, p.ck1, p.cv1, p.m, bits, p.sort_tmp_c, skc, cidx, st);
+    hipStream_t wst = st;
+    const bool two = sorts && sh->overlap;
+    if (two) {
+        int rc = ensure_side_stream(sh);
+        if (rc) return rc;
+        HIP_TRY(hipEventRecord(sh->ev_fork, st));
+        HIP_TRY(hipStreamWaitEvent(sh->side, sh->ev_fork, 0));
+        wst = sh->side;
+    }
+    {
+        Phase ph(sh, W2V_PH_NEG, wst);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, p.n, k, seed, p.keys, sh->err, wst);
+    }
+    if (two) HIP_TRY(hipEventRecord(sh->ev_keys, wst));
+    if (!sorts) return W2V_OK;
+    {
+        Phase ph(sh, W2V_PH_SORT, wst);
+        const uint32_t bits = key_bits(sh->V);
+        launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp_w, skw, sidx, wst);
+        launch_sort_pairs(p.ctx_safe, p.ck0, p.cv0, p.ck1, p.cv1, p.m, bits, p.sort_tmp_c, skc, cidx, wst);
+    }
+    if (two) HIP_TRY(hipEventRecord(sh->ev_join, wst));
+    return W2V_OK;
+}
+
+// The caller's stream needs the keys from here on (only after a queue_cbow_indices with sorts).
+void cbow_wait_keys(w2v_shard* sh, hipStream_t st) {
+    if (sh->overlap && sh->side) (void)hipStreamWaitEvent(st, sh->ev_keys, 0);
 }
 
 void queue_cbow_hidden(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint32_t* ctx_off,
@@ -800,6 +825,7 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
         launch_useg(a, st);
     }
+    join_output_sort(owner, st);
     {
         Phase ph(owner, W2V_PH_WSIDE, st);
         WSideArgs w{};
@@ -844,8 +870,9 @@ extern "C" int w2v_cbow_dotprod(w2v_shard* sh, const uint32_t* ctx_off, const ui
     rc = ensure_ws(sh, sz.bytes);
     if (rc) return rc;
     CbowPlan p = make_cbow_plan(sh->ws, n, k, m, sh->g.stride4, 0, false, false);
-    queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, false, nullptr, nullptr, nullptr,
-                       nullptr, st);
+    rc = queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, false, nullptr, nullptr,
+                            nullptr, nullptr, st);
+    if (rc) return rc;
     queue_cbow_hidden(sh, sh, p, ctx_off, st);
     {
         Phase ph(sh, W2V_PH_DOT, st);
@@ -870,8 +897,10 @@ extern "C" int w2v_cbow_adjust(w2v_shard* sh, const uint32_t* ctx_off, const uin
     if (rc) return rc;
     CbowPlan p = make_cbow_plan(sh->ws, n, k, m, sh->g.stride4, 0, true, false);
     uint32_t *skw, *sidx, *skc, *cidx;
-    queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, true, &skw, &sidx, &skc, &cidx, st);
+    rc = queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, true, &skw, &sidx, &skc, &cidx, st);
+    if (rc) return rc;
     queue_cbow_hidden(sh, sh, p, ctx_off, st);
+    cbow_wait_keys(sh, st);
     queue_cbow_adjust(sh, sh, p, skw, sidx, skc, cidx, coeffs, nullptr, false, alpha, st);
     HIP_TRY(hipGetLastError());
     return W2V_OK;
@@ -909,9 +938,11 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
     if (rc) return rc;
     CbowPlan p = make_cbow_plan(s0->ws, n, k, m, stride_max, fused ? 0 : S, true, true);
     uint32_t *skw, *sidx, *skc, *cidx;
-    queue_cbow_indices(s0, p, ctx_off, ctx_idx, out_idx, k, seed, true, &skw, &sidx, &skc, &cidx, st);
+    rc = queue_cbow_indices(s0, p, ctx_off, ctx_idx, out_idx, k, seed, true, &skw, &sidx, &skc, &cidx, st);
+    if (rc) return rc;
     if (fused) {
         queue_cbow_hidden(s0, s0, p, ctx_off, st);
+        cbow_wait_keys(s0, st);
         queue_cbow_adjust(s0, s0, p, skw, sidx, skc, cidx, nullptr, p.coeffs, true, alpha, st);
         if (loss) {
             Phase ph(s0, W2V_PH_COEFF, st);
@@ -924,6 +955,7 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
         for (uint32_t s = 0; s < S; ++s) {
             float* d = p.dots + (size_t)s * p.M;
             queue_cbow_hidden(s0, shards[s], p, ctx_off, st);
+            cbow_wait_keys(s0, st);
             Phase ph(s0, W2V_PH_DOT, st);
             launch_dots(p.H, shards[s]->W, shards[s]->g, p.iota, p.keys, n, p.T, d, st);
             pp.p[s] = d;
