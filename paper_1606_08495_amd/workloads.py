@@ -125,18 +125,6 @@ def iid_pairs(wl, n=None, seed=None, cdf=None):
     return zipf_draw(cdf, n, rng), zipf_draw(cdf, n, rng)
 
 
-def iid_examples(wl, n, B, seed=None, cdf=None, min_ctx=1):
-    """Bag-of-words examples with the shape text gives: a center word and 2b context words,
-    b uniform on 1..B (edge clipping ignored), every word iid from the workload's Zipf law.
-    Returns (ctx_off uint32[n+1], ctx_idx uint32[m], out_idx uint32[n])."""
-    rng = np.random.Generator(np.random.PCG64((wl.seed if seed is None else seed) + 3000))
-    if cdf is None:
-        cdf = zipf_cdf(wl.V, wl.zipf_s)
-    lens = np.maximum(min_ctx, 2 * rng.integers(1, B + 1, n))
-    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint32)
-    return off, zipf_draw(cdf, int(off[-1]), rng), zipf_draw(cdf, n, rng)
-
-
 def embedding_like(n, d, seed, n_clusters=1000, spread=0.6, cluster_seed=0):
     """n vectors of width d shaped like trained embeddings: a cluster direction (one of n_clusters
     drawn from ``cluster_seed``, Zipf-popular) plus isotropic unit-variance noise times ``spread``,
