@@ -16,12 +16,11 @@ static inline unsigned blocks_for(uint64_t items, unsigned per_block) {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int TK_BQ = 128;          // queries per block tile
-constexpr int TK_BC = 128;          // candidates per block tile
+constexpr int TK_BQ = 128;          // queries per block tile (2 x 2 wavefronts x 2 x 2 tiles of 32)
+constexpr int TK_BC = 128;          // candidates per block tile; granularity of a round
 constexpr int TK_BK = 32;           // columns staged per step (16 and 64 measured slower)
 constexpr int TK_LD = TK_BK + 1;    // LDS row pitch (odd: conflict-free column reads)
-constexpr int TK_THREADS = 256;     // four wavefronts, each owns a 64 x 64 sub-tile
-constexpr int TK_MOVES = TK_BQ * TK_BK / 4 / TK_THREADS;   // float4 per thread and panel
+constexpr int TK_THREADS = 256;     // four wavefronts
 constexpr int TK_RPM = TK_THREADS / (TK_BK / 4);            // rows covered by one move of the block
 constexpr int TK_LIST = 64;         // slots of a query's best list (K <= 64)
 constexpr uint32_t TK_NONE = 0xFFFFFFFFu;
@@ -86,113 +85,129 @@ __device__ __forceinline__ float4 load_cols(const float* __restrict__ row, bool 
     return r;
 }
 
-// Four wavefronts per SIMD (128 registers each, accumulators included) measured 3 % faster than
-// the three the compiler settles on by itself.
-template <bool VEC4>
-__global__ __launch_bounds__(TK_THREADS, 4) void topk_scores_kernel(TopkArgs a) {
-    __shared__ float As[TK_BQ][TK_LD];
-    __shared__ float Bs[TK_BC][TK_LD];
-    __shared__ float s_invq[TK_BQ];
-    __shared__ float s_theta[TK_BQ];
+// The block is 2 x 2 wavefronts; a wavefront owns TM x TN matrix-core tiles of 32 x 32, so the
+// block tile is (64 TM) queries x (64 TN) candidates.  WPE = wavefronts per SIMD the register
+// budget is set for.
+template <int TM, int TN, int WPE, bool VEC4>
+__global__ __launch_bounds__(TK_THREADS, WPE) void topk_scores_kernel(TopkArgs a) {
+    constexpr int BQ = 64 * TM, BC = 64 * TN;
+    constexpr int MOVES_A = BQ * TK_BK / 4 / TK_THREADS, MOVES_B = BC * TK_BK / 4 / TK_THREADS;
+    __shared__ float As[BQ][TK_LD];
+    __shared__ float Bs[BC][TK_LD];
+    __shared__ float s_invq[BQ];
+    __shared__ float s_theta[BQ];
 
     const uint32_t total = a.nq_tiles * a.nc_tiles;
     const uint32_t per_xcd = (total + 7u) / 8u;
     const uint32_t logical = (blockIdx.x % 8u) * per_xcd + blockIdx.x / 8u;
     if (logical >= total) return;                            // uniform per block, before any barrier
-    const uint32_t q0 = (logical % a.nq_tiles) * TK_BQ;
-    const uint32_t c0 = a.c_begin + (logical / a.nq_tiles) * TK_BC;
+    const uint32_t q0 = (logical % a.nq_tiles) * BQ;
+    const uint32_t c0 = a.c_begin + (logical / a.nq_tiles) * BC;
 
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int wm = wave / 2, wn = wave % 2;
-    if (tid < TK_BQ) {
-        const uint32_t q = q0 + tid;
-        s_invq[tid] = q < a.Q ? a.invq[q] : 0.f;
-        s_theta[tid] = q < a.Q ? a.theta[q] : INFINITY;
+    for (int i = tid; i < BQ; i += TK_THREADS) {
+        const uint32_t q = q0 + i;
+        s_invq[i] = q < a.Q ? a.invq[q] : 0.f;
+        s_theta[i] = q < a.Q ? a.theta[q] : INFINITY;
     }
 
-    // staging: thread t moves float4 number t, t+256, ... of each 128 x TK_BK panel, i.e. the same
-    // four columns of rows srow0, srow0 + TK_RPM, ...
+    // staging: thread t moves float4 number t, t+256, ... of each panel of TK_BK columns, i.e. the
+    // same four columns of rows srow0, srow0 + TK_RPM, ...
     const int srow0 = tid / (TK_BK / 4), scol = (tid % (TK_BK / 4)) * 4;
     const float* arow0 = a.Qm + (uint64_t)(q0 + srow0) * a.d;      // not dereferenced past Q / c_end
     const float* brow0 = a.Cm + (uint64_t)(c0 + srow0) * a.d;
     const uint64_t row_step = (uint64_t)TK_RPM * a.d;
-    float4 ra[TK_MOVES], rb[TK_MOVES];
+    float4 ra[MOVES_A], rb[MOVES_B];
 #pragma unroll
-    for (int i = 0; i < TK_MOVES; ++i) {
+    for (int i = 0; i < MOVES_A; ++i)
         ra[i] = load_cols<VEC4>(arow0 + i * row_step, q0 + srow0 + i * TK_RPM < a.Q, scol, a.d);
+#pragma unroll
+    for (int i = 0; i < MOVES_B; ++i)
         rb[i] = load_cols<VEC4>(brow0 + i * row_step, c0 + srow0 + i * TK_RPM < a.c_end, scol, a.d);
-    }
 
-    v16f acc00 = {0}, acc01 = {0}, acc10 = {0}, acc11 = {0};
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     const int fr = lane & 31, fk = lane >> 5;
     for (uint32_t kb = 0; kb < a.d; kb += TK_BK) {
         __syncthreads();                                     // the previous panel has been consumed
 #pragma unroll
-        for (int i = 0; i < TK_MOVES; ++i) {
+        for (int i = 0; i < MOVES_A; ++i) {
             float* pa = &As[srow0 + i * TK_RPM][scol];
             pa[0] = ra[i].x; pa[1] = ra[i].y; pa[2] = ra[i].z; pa[3] = ra[i].w;
+        }
+#pragma unroll
+        for (int i = 0; i < MOVES_B; ++i) {
             float* pb = &Bs[srow0 + i * TK_RPM][scol];
             pb[0] = rb[i].x; pb[1] = rb[i].y; pb[2] = rb[i].z; pb[3] = rb[i].w;
         }
         __syncthreads();
         if (kb + TK_BK < a.d) {                              // next panel on its way during the math
 #pragma unroll
-            for (int i = 0; i < TK_MOVES; ++i) {
+            for (int i = 0; i < MOVES_A; ++i)
                 ra[i] = load_cols<VEC4>(arow0 + i * row_step, q0 + srow0 + i * TK_RPM < a.Q,
                                         kb + TK_BK + scol, a.d);
+#pragma unroll
+            for (int i = 0; i < MOVES_B; ++i)
                 rb[i] = load_cols<VEC4>(brow0 + i * row_step, c0 + srow0 + i * TK_RPM < a.c_end,
                                         kb + TK_BK + scol, a.d);
-            }
         }
         const int kmax = (int)min((uint32_t)TK_BK, a.d - kb);   // columns beyond d hold zeros: skipped
 #pragma unroll
         for (int kk = 0; kk < TK_BK; kk += 2) {
             if (kk >= kmax) break;
-            const float a0 = As[wm * 64 + fr][kk + fk];
-            const float a1 = As[wm * 64 + 32 + fr][kk + fk];
-            const float b0 = Bs[wn * 64 + fr][kk + fk];
-            const float b1 = Bs[wn * 64 + 32 + fr][kk + fk];
-            acc00 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc00, 0, 0, 0);
-            acc01 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc01, 0, 0, 0);
-            acc10 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc10, 0, 0, 0);
-            acc11 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc11, 0, 0, 0);
+            float av[TM], bv[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) av[i] = As[wm * 32 * TM + i * 32 + fr][kk + fk];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bv[j] = Bs[wn * 32 * TN + j * 32 + fr][kk + fk];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
     }
 
     // filter: a score at or above the query's threshold joins the query's pending list.  For a
     // given accumulator register the 32 lanes of a half-wavefront hold 32 candidates of one query,
     // so each half reserves its slots with a single atomic.
-    auto filter = [&](const v16f& acc, int ti, int tj) {
-        const uint32_t c = c0 + wn * 64 + tj * 32 + fr;
-        const bool c_ok = c < a.c_end;
-        const float ic = c_ok ? a.invc[c] : 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int ql = wm * 64 + ti * 32 + 8 * (v / 4) + 4 * fk + (v % 4);
-            const float s = acc[v] * s_invq[ql] * ic;
-            const bool pass = c_ok && s >= s_theta[ql];      // padded queries carry +inf: never
-            const uint64_t both = __ballot(pass);
-            const uint32_t half = fk ? (uint32_t)(both >> 32) : (uint32_t)both;
-            if (half) {
-                const uint32_t q = q0 + ql;
-                const int leader = __ffs(half) - 1 + 32 * fk;
-                uint32_t base = 0;
-                if (lane == leader) base = atomicAdd(&a.cnt[q], (uint32_t)__popc(half));
-                base = __shfl(base, leader, 64);
-                if (pass) {
-                    const uint32_t slot = base + (uint32_t)__popc(half & ((1u << fr) - 1u));
-                    if (slot < a.cap)
-                        a.pend[(uint64_t)q * a.cap + slot] = make_uint2(__float_as_uint(s), c);
-                    else
-                        atomicOr(a.err, 1u);
+    for (int ti = 0; ti < TM; ++ti) {
+#pragma unroll
+        for (int tj = 0; tj < TN; ++tj) {
+            const uint32_t c = c0 + wn * 32 * TN + tj * 32 + fr;
+            const bool c_ok = c < a.c_end;
+            const float ic = c_ok ? a.invc[c] : 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int ql = wm * 32 * TM + ti * 32 + 8 * (v / 4) + 4 * fk + (v % 4);
+                const float s = acc[ti][tj][v] * s_invq[ql] * ic;
+                const bool pass = c_ok && s >= s_theta[ql];  // padded queries carry +inf: never
+                const uint64_t both = __ballot(pass);
+                const uint32_t half = fk ? (uint32_t)(both >> 32) : (uint32_t)both;
+                if (half) {
+                    const uint32_t q = q0 + ql;
+                    const int leader = __ffs(half) - 1 + 32 * fk;
+                    uint32_t base = 0;
+                    if (lane == leader) base = atomicAdd(&a.cnt[q], (uint32_t)__popc(half));
+                    base = __shfl(base, leader, 64);
+                    if (pass) {
+                        const uint32_t slot = base + (uint32_t)__popc(half & ((1u << fr) - 1u));
+                        if (slot < a.cap)
+                            a.pend[(uint64_t)q * a.cap + slot] = make_uint2(__float_as_uint(s), c);
+                        else
+                            atomicOr(a.err, 1u);
+                    }
                 }
             }
         }
-    };
-    filter(acc00, 0, 0);
-    filter(acc01, 0, 1);
-    filter(acc10, 1, 0);
-    filter(acc11, 1, 1);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -335,7 +350,12 @@ uint32_t* launch_topk_cosine(const float* Qm, uint32_t Q, const float* Cm, uint3
     a.Qm = Qm; a.Cm = Cm; a.Q = Q; a.N = N; a.d = d;
     a.invq = invq; a.invc = invc; a.theta = theta; a.cnt = cnt; a.pend = pend; a.cap = cap;
     a.err = err;
-    a.nq_tiles = (Q + TK_BQ - 1) / TK_BQ;
+    // 2 x 2 tiles per wavefront at four wavefronts per SIMD (128 registers, accumulators included)
+    // measured best: 2 x 4 and 4 x 2 tiles (two wavefronts per SIMD) ran 9 % slower, 4 x 4 (one) 2.3
+    // times slower -- this kernel lives on having other wavefronts to switch to at its barriers.
+    constexpr int TK_TM = 2, TK_TN = 2, TK_WPE = 4;
+    constexpr int BQ = 64 * TK_TM, BC = 64 * TK_TN;
+    a.nq_tiles = (Q + BQ - 1) / BQ;
     // The first rounds are short and grow fourfold: with a threshold from the first few hundred
     // candidates only a small share of a full round's scores reaches the pending lists.
     uint64_t len = TK_BC;
@@ -343,13 +363,13 @@ uint32_t* launch_topk_cosine(const float* Qm, uint32_t Q, const float* Cm, uint3
         if (len > cap) len = cap;
         a.c_begin = (uint32_t)begin;
         a.c_end = (uint32_t)(begin + len < N ? begin + len : N);
-        a.nc_tiles = (a.c_end - a.c_begin + TK_BC - 1) / TK_BC;
+        a.nc_tiles = (a.c_end - a.c_begin + BC - 1) / BC;
         const uint32_t total = a.nq_tiles * a.nc_tiles;
         const dim3 grid(((total + 7u) / 8u) * 8u), block(TK_THREADS);
         if (d % 4 == 0 && ((uintptr_t)Qm % 16 == 0) && ((uintptr_t)Cm % 16 == 0))
-            hipLaunchKernelGGL((topk_scores_kernel<true>), grid, block, 0, st, a);
+            hipLaunchKernelGGL((topk_scores_kernel<TK_TM, TK_TN, TK_WPE, true>), grid, block, 0, st, a);
         else
-            hipLaunchKernelGGL((topk_scores_kernel<false>), grid, block, 0, st, a);
+            hipLaunchKernelGGL((topk_scores_kernel<TK_TM, TK_TN, TK_WPE, false>), grid, block, 0, st, a);
         hipLaunchKernelGGL(topk_select_kernel, dim3(Q), dim3(64), 0, st, Q, K, cap, cnt, pend, best,
                            best_cnt, theta);
     }
