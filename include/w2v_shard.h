@@ -19,7 +19,9 @@
  *     one shard share that shard's scratch memory and must be stream-ordered with one another (same
  *     stream, or the caller orders them).  Scratch grows to the largest request seen and is then
  *     reused, so a steady-state training loop allocates nothing (cf. Section 6.1.3: the paper's
- *     shards also create no objects in steady state).
+ *     shards also create no objects in steady state).  Part of a call's work may run on a second
+ *     stream the shard owns, forked from `stream` and joined back into it by events before the call
+ *     returns: for the caller everything is ordered on `stream`.
  *   - index arrays are uint32 word indices < V.  An index >= V never causes an out-of-range access:
  *     the kernel substitutes word 0 and raises a sticky flag that w2v_shard_status() reports.
  *   - layouts are row-major and dense: partial_dots / coeffs are [n][k+1] with the positive output
