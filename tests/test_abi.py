@@ -67,3 +67,12 @@ def test_workload_generators_are_seeded_and_shaped():
     assert counts.min() >= 1 and counts[0] > counts[1] > counts[10]
     assert workloads.alpha_schedule(workloads.WORKLOADS["full300"], 0, 100) == np.float32(0.025)
     assert abs(workloads.alpha_schedule(workloads.WORKLOADS["full300"], 100, 100) - 1e-4) < 1e-9
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
