@@ -64,5 +64,21 @@ def _build(verbose, jobs, extra_flags):
     return LIB
 
 
+C_CLIENT_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_client", "abi_client.c")
+C_CLIENT = os.path.join(os.path.dirname(HERE), "tests", "c_client", "abi_client")
+
+
+def build_c_client():
+    """The plain C (C99, gcc) client of the ABI that the GPU tests run: shows that the header and
+    the library are usable without Python or torch."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    _run(["gcc", "-std=c99", "-Wall", "-Werror", "-O1", "-D__HIP_PLATFORM_AMD__=1",
+          "-I" + os.path.join(rocm, "include"), C_CLIENT_SRC, "-o", C_CLIENT,
+          "-L" + HERE, "-lw2v_shard", "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+          "-Wl,-rpath,$ORIGIN/../../paper_1606_08495_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")])
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))
+    print(build_c_client())

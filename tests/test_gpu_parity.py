@@ -468,3 +468,53 @@ def test_out_of_range_index_raises_the_sticky_flag_without_a_fault():
     with pytest.raises(w2v.W2VError):
         sh.status()
     sh.destroy()
+
+
+# --- the C ABI from plain C ----------------------------------------------------------------------------
+
+def test_plain_c_client_gets_the_same_bits_as_the_binding(tmp_path):
+    """tests/c_client/abi_client.c (C99, gcc, no Python or torch) runs dotprod / coeffs / adjust /
+    train_minibatch through the header; the binding must return the same bits for the same inputs."""
+    import os
+    import subprocess
+    from paper_1606_08495_amd import build as hip_build
+    if not os.path.exists(hip_build.C_CLIENT):
+        hip_build.build_c_client()                       # a sub-second gcc compile
+    out = tmp_path / "client.bin"
+    r = subprocess.run([hip_build.C_CLIENT, str(out)], capture_output=True, text=True, timeout=300)
+    say(r.stdout.strip(), r.stderr.strip())
+    assert r.returncode == 0
+    V, D, N, K = 1000, 64, 3000, 5
+    T = K + 1
+    raw = np.fromfile(out, dtype=np.uint8)
+    pos = 0
+
+    def take(dtype, count):
+        nonlocal pos
+        a = raw[pos:pos + np.dtype(dtype).itemsize * count].view(dtype)
+        pos += a.nbytes
+        return a
+    in_idx, out_idx = take(np.uint32, N), take(np.uint32, N)
+    c_dots, c_coeffs = take(np.float32, N * T).reshape(N, T), take(np.float32, N * T).reshape(N, T)
+    c_loss = take(np.float64, 2)
+    c_U, c_W = take(np.float32, V * D).reshape(V, D), take(np.float32, V * D).reshape(V, D)
+    assert pos == raw.size
+    counts = (1000000 // (np.arange(V, dtype=np.uint64) + 1) + 1).astype(np.uint64)
+    sh = make_shard(V, D, 77, counts, 0.0, init_mode=1)
+    a, b = dev(in_idx), dev(out_idx)
+    seed = w2v.minibatch_seed(99, 0)
+    dots = sh.dotprod(a, b, K, seed)
+    g, loss0 = sh.coeffs([dots], K, want_loss=True)
+    sh.adjust(a, b, K, seed, g, 0.05)
+    loss1 = torch.zeros(1, dtype=torch.float64, device="cuda")
+    w2v.train_minibatch([sh], a, b, K, w2v.minibatch_seed(99, 1), 0.05, loss=loss1)
+    assert np.array_equal(dots.cpu().numpy(), c_dots) and np.array_equal(g.cpu().numpy(), c_coeffs)
+    assert loss0.item() == c_loss[0] and loss1.item() == c_loss[1]
+    assert np.array_equal(all_rows(sh, 0), c_U) and np.array_equal(all_rows(sh, 1), c_W)
+    # and both agree with the oracle
+    U, W = oracle_state(V, D, 77)
+    th, al = oracle.build_alias(counts)
+    oracle.train_minibatch([U], [W], in_idx, out_idx, K, seed, th, al, 0.05)
+    oracle.train_minibatch([U], [W], in_idx, out_idx, K, w2v.minibatch_seed(99, 1), th, al, 0.05)
+    assert vec_error(c_U, U) <= 2 * TOL1 and vec_error(c_W, W) <= 2 * TOL1
+    sh.destroy()
