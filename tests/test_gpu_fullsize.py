@@ -219,6 +219,84 @@ def reduced_n_step(name, n, n_tokens):
     sh.destroy()
 
 
+def full_n_step(name, n_tokens):
+    """The benchmark's own launch configuration (full vocabulary, dimension, k and n): pairs and
+    negatives compared in full; updated rows compared on sampled rows that collect few
+    contributions (for those the oracle can be given every pair that touches them); the whole step
+    repeated on a fresh shard must give the same bits, hottest rows included."""
+    wl = workloads.WORKLOADS[name]
+    n = wl.n_pairs
+    rng = np.random.default_rng(23)
+    say(name, "full n =", n, ": tables")
+    cdf = workloads.zipf_cdf(wl.V, wl.zipf_s)
+    counts = workloads.analytic_counts(wl.V, wl.zipf_s, wl.corpus_tokens)
+    tokens, off = workloads.corpus(wl, n_tokens, cdf=cdf)
+    del cdf
+    th, al = oracle.build_alias(counts)
+
+    def fresh():
+        sh = w2v.Shard(wl.V, wl.d_slice, wl.seed, d_total=wl.d_total, col_begin=wl.col_begin, init_mode=1)
+        sh.set_counts(counts, wl.subsample_t)
+        return sh
+    sh = fresh()
+    cap = n_tokens * 2 * wl.window
+    gi = torch.empty(cap, dtype=torch.int32, device="cuda")
+    go = torch.empty(cap, dtype=torch.int32, device="cuda")
+    cnt = sh.make_pairs(dev(tokens), torch.from_numpy(off.astype(np.int64)).cuda(), 0, 0, wl.seed,
+                        wl.window, gi, go)
+    oi, oo, ocnt = oracle.make_pairs(tokens, off, 0, 0, wl.seed, wl.window, None)
+    assert cnt == ocnt and cnt >= n
+    assert np.array_equal(w2v.index_to_numpy(gi[:cnt]), oi) and np.array_equal(w2v.index_to_numpy(go[:cnt]), oo)
+    in_idx, out_idx = oi[:n], oo[:n]
+    a, b = gi[:n].contiguous(), go[:n].contiguous()
+    del gi, go
+    seed = w2v.minibatch_seed(wl.seed, 0)
+    say("   negatives, all", n * wl.k)
+    neg = oracle.negatives(out_idx, wl.k, seed, th, al)
+    assert np.array_equal(w2v.index_to_numpy(sh.negatives(b, wl.k, seed)), neg)
+    rows = np.concatenate([out_idx[:, None], neg], axis=1)
+    del neg
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    w2v.train_minibatch([sh], a, b, wl.k, seed, wl.alpha, loss=loss)
+    sh.status()
+    # rows with at most four contributions, found from a random sample of slots
+    cand_w = np.unique(rows.ravel()[rng.integers(0, rows.size, 3000)])
+    hits = rows.ravel()[np.isin(rows.ravel(), cand_w)]
+    vals, c = np.unique(hits, return_counts=True)
+    samp_w = vals[c <= 4][:600].astype(np.uint32)
+    vals, c = np.unique(in_idx, return_counts=True)
+    few = vals[c <= 4]
+    samp_u = rng.choice(few, size=min(150, few.size), replace=False).astype(np.uint32)
+    assert samp_w.size >= 100 and samp_u.size >= 50
+    eu, ew = check_sampled_update(sh, wl, in_idx, rows, None, wl.alpha, True, samp_u, samp_w)
+    say("   U error", eu, "W error", ew)
+    assert eu <= TOL1 and ew <= TOL1
+    hot_u = sample_rows(in_idx, 8, 100, rng)
+    hot_w = sample_rows(out_idx, 8, 300, rng)
+    keep = [sh.get_rows(0, dev(x)).cpu().numpy() for x in (samp_u, hot_u)] + \
+           [sh.get_rows(1, dev(x)).cpu().numpy() for x in (samp_w, hot_w)] + [loss.item()]
+    sh.destroy()
+    del sh
+    say("   the same step on a fresh shard")
+    sh = fresh()
+    w2v.train_minibatch([sh], a, b, wl.k, seed, wl.alpha, loss=loss)
+    again = [sh.get_rows(0, dev(x)).cpu().numpy() for x in (samp_u, hot_u)] + \
+            [sh.get_rows(1, dev(x)).cpu().numpy() for x in (samp_w, hot_w)] + [loss.item()]
+    for x, y in zip(keep[:4], again[:4]):
+        assert np.array_equal(x, y)
+    assert keep[4] == again[4]
+    sh.status()
+    sh.destroy()
+
+
+def test_stress25_full_n_properties():
+    full_n_step("stress25", 700_000)
+
+
+def test_search200m_full_n_properties():
+    full_n_step("search200m", 520_000)
+
+
 def test_stress25_reduced_n_sampled():
     """V = 50M, d = 200, k = 25, Zipf(1.2): the most frequent word is the input of ~18% of the pairs,
     so its row collects hundreds of thousands of contributions through several reduction levels."""
