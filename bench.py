@@ -23,6 +23,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# the row kernel that makes up a timed phase (names as rocprofv3 lists them)
+KERNEL_OF_PHASE = {"wside": "wown_kernel", "uside": "useg_multi_kernel / useg_kernel", "dot": "dots_kernel",
+                   "apply": "wown_kernel (input side)"}
 
 
 def log(*a):
@@ -261,7 +264,9 @@ def run_cbow(args, torch, w2v, workloads):
                    "path": "make_cbow_examples+cbow_train_minibatch",
                    "distinct_input_rows": du, "distinct_output_rows": dw},
         "context_words_per_s": ctx_total / dt,
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "cbow_hidden_kernel" if dom == "dot" else
+                     KERNEL_OF_PHASE.get(dom, dom), "phase": dom, "achieved": achieved,
+                     "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": algo[dom], "ms_per_launch": dom_ms},
         "phases": per_phase,
@@ -549,7 +554,8 @@ def main():
                    "subsample_t": wl.subsample_t,
                    "path": "make_pairs+train_minibatch" if fused else "dotprod+adjust",
                    "distinct_input_rows": du, "distinct_output_rows": dw},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": KERNEL_OF_PHASE.get(dom, dom), "phase": dom,
+                     "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": algo[dom], "ms_per_launch": dom_ms},
         "step_logical_GBps": step_algo / (ms_per_step * 1e-3) / 1e9,
