@@ -518,3 +518,48 @@ def test_plain_c_client_gets_the_same_bits_as_the_binding(tmp_path):
     oracle.train_minibatch([U], [W], in_idx, out_idx, K, w2v.minibatch_seed(99, 1), th, al, 0.05)
     assert vec_error(c_U, U) <= 2 * TOL1 and vec_error(c_W, W) <= 2 * TOL1
     sh.destroy()
+
+
+# --- random shapes ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_shapes_skipgram_and_bag_of_words(case):
+    """Shapes, skews and shard splits drawn at random inside the documented limits: one skip-gram
+    step and one bag-of-words step per case against the oracle."""
+    rng = np.random.default_rng(9000 + case)
+    V = int(rng.choice([2, 3, 17, 100, 1000, 3000]))
+    S = int(rng.choice([1, 1, 2, 3]))
+    widths = [int(rng.integers(1, 120)) if S > 1 else int(rng.choice([1, 7, 60, 64, 65, 100, 128, 200, 257, 330]))
+              for _ in range(S)]
+    n = int(rng.choice([1, 2, 15, 16, 17, 300, 2047, 4097, 9000]))
+    k = int(rng.choice([0, 1, 5, 5, 12, 31]))
+    skew = float(rng.choice([0.0, 1.0, 2.5]))
+    say("random case", case, "V", V, "widths", widths, "n", n, "k", k, "skew", skew)
+    counts = np.maximum(1, 1e9 / np.arange(1, V + 1) ** skew).astype(np.uint64)
+    th, al = oracle.build_alias(counts)
+    dt = sum(widths)
+    begins = np.concatenate([[0], np.cumsum(widths)[:-1]])
+    cdf = workloads.zipf_cdf(V, skew)
+    alpha = 0.02 if V >= 100 else 1e-4
+    for variant in ("sgns", "cbow"):
+        shards = [make_shard(V, w, 31, counts, d_total=dt, col_begin=int(b)) for w, b in zip(widths, begins)]
+        st = [oracle_state(V, w, 31, dt, int(b)) for w, b in zip(widths, begins)]
+        Us, Ws = [a for a, _ in st], [b for _, b in st]
+        out = workloads.zipf_draw(cdf, n, rng)
+        loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+        if variant == "sgns":
+            inn = workloads.zipf_draw(cdf, n, rng)
+            w2v.train_minibatch(shards, dev(inn), dev(out), k, 4242, alpha, loss=loss)
+            ref = oracle.train_minibatch(Us, Ws, inn, out, k, 4242, th, al, alpha)
+        else:
+            lens = rng.integers(0, 9, n)
+            off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint32)
+            ctx = workloads.zipf_draw(cdf, int(off[-1]), rng)
+            w2v.cbow_train_minibatch(shards, dev(off), dev(ctx), dev(out), k, 4242, alpha, loss=loss)
+            ref = oracle.cbow_train_minibatch(Us, Ws, off, ctx, out, k, 4242, th, al, alpha)
+        assert abs(loss.item() - ref) <= 1e-5 * abs(ref) + 1e-12
+        for s in range(S):
+            eu, ew = vec_error(all_rows(shards[s], 0), Us[s]), vec_error(all_rows(shards[s], 1), Ws[s])
+            assert eu <= TOL1 and ew <= TOL1, (variant, s, eu, ew)
+            shards[s].status()
+            shards[s].destroy()
