@@ -563,3 +563,41 @@ def test_random_shapes_skipgram_and_bag_of_words(case):
             assert eu <= TOL1 and ew <= TOL1, (variant, s, eu, ew)
             shards[s].status()
             shards[s].destroy()
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_text_blocks_pairs_interleaved_pairs_and_examples(case):
+    rng = np.random.default_rng(7000 + case)
+    V = int(rng.choice([2, 50, 5000]))
+    n_tok = int(rng.choice([1, 2, 63, 4096, 4097, 30_000]))
+    B = int(rng.choice([1, 2, 5, 10, 15]))
+    t = float(rng.choice([0.0, 1e-4, 1e-2, 1e6]))
+    max_len = int(rng.choice([1, 2, 8, 60, 1000]))
+    say("text case", case, "V", V, "tokens", n_tok, "B", B, "t", t, "max sentence", max_len)
+    tokens = workloads.zipf_draw(workloads.zipf_cdf(V, 1.0), n_tok, rng)
+    counts = np.maximum(1, workloads.counted(tokens, V))
+    lens = rng.integers(0, max_len + 1, n_tok + 1)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    off = np.append(off[off < n_tok], n_tok).astype(np.uint64)
+    sh = make_shard(V, 4, 1, counts, t)
+    kt = oracle.build_keep(counts, t) if t > 0 else None
+    base, epoch, seed = int(rng.integers(0, 1 << 40)), int(rng.integers(0, 5)), int(rng.integers(0, 1 << 62))
+    doff = torch.from_numpy(off.astype(np.int64)).cuda()
+    cap = max(1, n_tok * 2 * B)
+    gi = torch.empty(cap, dtype=torch.int32, device="cuda")
+    go = torch.empty(cap, dtype=torch.int32, device="cuda")
+    for inter in (False, True):
+        cnt = sh.make_pairs(dev(tokens), doff, base, epoch, seed, B, gi, go, interleaved=inter)
+        oi, oo, ocnt = oracle.make_pairs(tokens, off, base, epoch, seed, B, kt, interleaved=inter)
+        assert cnt == ocnt
+        assert np.array_equal(w2v.index_to_numpy(gi[:cnt]), oi) and np.array_equal(w2v.index_to_numpy(go[:cnt]), oo)
+    co = torch.empty(n_tok + 1, dtype=torch.int32, device="cuda")
+    ce = torch.empty(n_tok, dtype=torch.int32, device="cuda")
+    n_ex, n_ctx = sh.make_cbow_examples(dev(tokens), doff, base, epoch, seed, B, co, go, ce)
+    ooff, octx, oout, ocnt, onctx = oracle.make_cbow_examples(tokens, off, base, epoch, seed, B, kt)
+    assert (n_ex, n_ctx) == (ocnt, onctx)
+    assert np.array_equal(w2v.index_to_numpy(co[:n_ex + 1]), ooff)
+    assert np.array_equal(w2v.index_to_numpy(go[:n_ctx]), octx)
+    assert np.array_equal(w2v.index_to_numpy(ce[:n_ex]), oout)
+    sh.status()
+    sh.destroy()
