@@ -352,6 +352,46 @@ def run_topk(args, torch, w2v, workloads):
     print(json.dumps(res), flush=True)
 
 
+def run_gather_probe(args, torch, w2v, workloads):
+    """What random row gathers reach on this part: w2v_dotprod alone on the chosen workload's shard
+    with uniformly random input and output words (no frequent words, so no cache help beyond what
+    the row size gives): (k+2) row reads per pair and 4(k+1) bytes written.  A measured ceiling for
+    the access pattern of the training kernels, next to the 8 TB/s data-sheet figure."""
+    wl = workloads.WORKLOADS[args.workload]
+    n, k, R = wl.n_pairs, wl.k, 4 * wl.d_slice
+    sh = w2v.Shard(wl.V, wl.d_slice, wl.seed, d_total=wl.d_total, col_begin=wl.col_begin, init_mode=1)
+    sh.set_counts(np.ones(wl.V, np.uint64), 0.0)          # uniform noise distribution
+    g = torch.Generator(device="cuda").manual_seed(5)
+    a = torch.randint(0, wl.V, (n,), generator=g, device="cuda", dtype=torch.int32)
+    b = torch.randint(0, wl.V, (n,), generator=g, device="cuda", dtype=torch.int32)
+    dots = torch.empty((n, k + 1), dtype=torch.float32, device="cuda")
+    for h in range(max(args.warmup, 1)):
+        sh.dotprod(a, b, k, h, out=dots)
+    sh.timing_enable(True)
+    sh.timing_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for h in range(args.steps):
+        sh.dotprod(a, b, k, 100 + h, out=dots)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms, cnt = sh.timing_read()["dot"]
+    sh.status()
+    sh.destroy()
+    algo = n * (k + 2) * R + 8 * n * (k + 1)
+    achieved = algo / (ms / cnt * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "random row gather (dots_kernel alone, uniform words) on 1 MI355X",
+        "value": achieved, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 1),
+        "ms_per_step": dt * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name + "/gather-probe", "V": wl.V, "d_slice": wl.d_slice,
+                   "row_bytes": R, "pairs": n, "k": k},
+        "roofline": {"bound": "hbm", "kernel": "dots_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": algo, "ms_per_launch": ms / cnt}}), flush=True)
+
+
 def distinct_rows(torch, shard, in_idx, out_idx, k, seed):
     """Distinct input rows and distinct output/negative rows of one minibatch (for byte counts)."""
     neg = shard.negatives(out_idx, k, seed)
@@ -367,9 +407,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="full300",
                     choices=["full300", "slice60", "tiny", "search200m", "stress25"])
-    ap.add_argument("--variant", default="sgns", choices=["sgns", "cbow", "topk"],
+    ap.add_argument("--variant", default="sgns", choices=["sgns", "cbow", "topk", "gather"],
                     help="cbow: the bag-of-words variant on the same text workload; "
-                         "topk: cosine retrieval over exported vectors")
+                         "topk: cosine retrieval over exported vectors; gather: the rate plain "
+                         "random row gathers reach (dotprod alone, uniform words)")
     ap.add_argument("--topk-queries", type=int, default=4096)
     ap.add_argument("--topk-candidates", type=int, default=1 << 20)
     ap.add_argument("--topk-k", type=int, default=30)
@@ -399,6 +440,8 @@ def main():
         return run_cbow(args, torch, w2v, workloads)
     if args.variant == "topk":
         return run_topk(args, torch, w2v, workloads)
+    if args.variant == "gather":
+        return run_gather_probe(args, torch, w2v, workloads)
     wl = workloads.WORKLOADS[args.workload]
     K, Wm = args.steps, args.warmup
     if not args.cpu_sample_pairs:
