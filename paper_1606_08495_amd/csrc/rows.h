@@ -27,6 +27,38 @@ __device__ __forceinline__ void load_row_if(bool on, const float4* __restrict__ 
     }
 }
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// The same with the non-temporal hint: rows that are touched once per minibatch and should not
+// push reusable rows out of the caches.
+template <int G, int NV>
+__device__ __forceinline__ void load_row_nt_if(bool on, const float4* __restrict__ row, uint32_t d4,
+                                               int l, float4 (&r)[NV]) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        uint32_t i = (uint32_t)l + (uint32_t)(G * v);
+        if (on && i < d4) {
+            const v4f x = __builtin_nontemporal_load((const v4f*)row + i);
+            r[v] = make_float4(x.x, x.y, x.z, x.w);
+        } else {
+            r[v] = f4zero();
+        }
+    }
+}
+
+template <int G, int NV>
+__device__ __forceinline__ void store_row_nt(float4* __restrict__ row, uint32_t d4, int l,
+                                             const float4 (&r)[NV]) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        uint32_t i = (uint32_t)l + (uint32_t)(G * v);
+        if (i < d4) {
+            v4f x = {r[v].x, r[v].y, r[v].z, r[v].w};
+            __builtin_nontemporal_store(x, (v4f*)row + i);
+        }
+    }
+}
+
 template <int G, int NV>
 __device__ __forceinline__ void store_row(float4* __restrict__ row, uint32_t d4, int l,
                                           const float4 (&r)[NV]) {
