@@ -73,6 +73,7 @@ struct w2v_shard {
     hipEvent_t ev_fork = nullptr, ev_keys = nullptr, ev_join = nullptr;
     hipEvent_t ev_coeffs = nullptr, ev_wdone = nullptr, ev_tails = nullptr;
     bool overlap = true;
+    bool own_rows = true;           // fused step: singly named output rows updated by the input side
     // timing
     bool timing = false;
     std::vector<TimedSpan> spans;
@@ -169,6 +170,7 @@ uint32_t slots_after(uint32_t entries, uint32_t per_chunk) {
 struct Plan {
     uint32_t n, T, M;
     uint32_t* keys; uint32_t* in_safe;
+    bool own_rows;                         // fused step: singly named output rows go to the input side
     uint32_t *uk0, *uv0, *uk1, *uv1;       // sort buffers, input side (n)
     uint32_t *wk0, *wv0, *wk1, *wv1;       // sort buffers, output side (M)
     uint32_t* sort_tmp; uint32_t* sort_tmp_u;
@@ -183,12 +185,13 @@ struct Plan {
 };
 
 Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_t S_dots,
-               bool want_adjust, bool want_coeffs) {
+               bool want_adjust, bool want_coeffs, uint32_t V_own_rows = 0) {
     Plan p{};
     p.n = n; p.T = k + 1; p.M = n * p.T;
     Carver c(base);
     p.keys = c.take<uint32_t>(p.M);
     p.in_safe = c.take<uint32_t>(n);
+    p.own_rows = V_own_rows != 0;
     if (want_coeffs) p.coeffs = c.take<float>(p.M);
     if (S_dots) p.dots = c.take<float>((size_t)S_dots * p.M);
     p.loss_tmp = c.take<double>(coeffs_loss_scratch_doubles(n, p.T));
@@ -253,6 +256,7 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
                          uint32_t k, uint64_t seed, uint32_t** sku, uint32_t** perm, uint32_t** skw,
                          uint32_t** sidx, hipStream_t st) {
     const uint32_t bits = key_bits(sh->V);
+
     const NoiseTable nt{sh->bins, sh->V};
     hipStream_t wst = st;
     if (sh->overlap) {
@@ -270,6 +274,9 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
     {
         Phase ph(sh, W2V_PH_SORT, wst);
         launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp, skw, sidx, wst);
+        // fused single-shard step: output rows named by one slot only are updated by the
+        // input-side kernel (which then has to wait for this sort) and skipped by the output side
+        if (p.own_rows) launch_mark_alone(*skw, *sidx, p.M, p.keys, wst);
     }
     if (sh->overlap) HIP_TRY(hipEventRecord(sh->ev_join, sh->side));
     {
@@ -277,7 +284,7 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
         launch_check_inputs(in_idx, p.n, sh->V, p.in_safe, sh->err, st);
         launch_sort_pairs(p.in_safe, p.uk0, p.uv0, p.uk1, p.uv1, p.n, bits, p.sort_tmp_u, sku, perm, st);
     }
-    if (sh->overlap) HIP_TRY(hipStreamWaitEvent(st, sh->ev_keys, 0));
+    if (sh->overlap) HIP_TRY(hipStreamWaitEvent(st, p.own_rows ? sh->ev_join : sh->ev_keys, 0));
     return W2V_OK;
 }
 
@@ -304,6 +311,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
         a.dots_out = nullptr; a.delta = p.delta; a.dkey = p.dkey;
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
+        if (fused && p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
         launch_useg(a, st);
     }
     if (loss_out) {
@@ -321,6 +329,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         w.U = sh->U; w.W = sh->W; w.g = sh->g; w.skey = skw; w.sidx = sidx; w.M = p.M; w.T = p.T;
         w.in_idx = p.in_safe; w.coeffs = fused ? coeffs_out : coeffs_in; w.alpha = alpha;
         w.prows = p.pb_rows; w.pkeys = p.pb_keys;
+        w.skip_alone = fused && p.own_rows;
         launch_wseg(w, st);
     }
     if (two) {
@@ -379,6 +388,7 @@ extern "C" int w2v_shard_create_ex(uint32_t V, uint32_t d_total, uint32_t col_be
     }
     sh->g.stride4 = ((sh->g.d4 + align4 - 1) / align4) * align4;
     if (const char* env = getenv("W2V_NO_OVERLAP")) sh->overlap = (atoi(env) == 0);
+    if (const char* env = getenv("W2V_NO_OWN_ROWS")) sh->own_rows = (atoi(env) == 0);
 
     size_t bytes = (size_t)V * sh->g.stride4 * 16;
     hipError_t e = hipMalloc((void**)&sh->U, bytes);
@@ -659,10 +669,11 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
         return W2V_OK;
     }
     const bool fused = (S == 1);
-    Plan sz = make_plan(nullptr, n, k, stride_max, fused ? 0 : S, true, true);
+    const uint32_t own = (fused && s0->own_rows) ? s0->V : 0u;
+    Plan sz = make_plan(nullptr, n, k, stride_max, fused ? 0 : S, true, true, own);
     rc = ensure_ws(s0, sz.bytes);
     if (rc) return rc;
-    Plan p = make_plan(s0->ws, n, k, stride_max, fused ? 0 : S, true, true);
+    Plan p = make_plan(s0->ws, n, k, stride_max, fused ? 0 : S, true, true, own);
     uint32_t *sku, *perm, *skw, *sidx;
     rc = queue_keys_and_sorts(s0, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);
     if (rc) return rc;

@@ -47,6 +47,7 @@ struct RowGeom {
 constexpr uint32_t KEY_NONE = 0xFFFFFFFFu;   // "no destination" in partial-sum key arrays
 constexpr uint32_t KEY_ZERO = 0x80000000u;   // flag: slot belongs to the row but holds no data
 constexpr uint32_t KEY_MASK = 0x7FFFFFFFu;
+constexpr uint32_t KEY_ALONE = 0x80000000u;  // slot-ordered keys: no other slot names this row
 
 // ---- launch wrappers (defined in the .hip files) -------------------------------------------------
 struct NoiseTable { const uint2* bins; uint32_t V; };   // {keep threshold, alias} per word
@@ -63,6 +64,9 @@ void launch_scatter_rows(float* M, RowGeom g, uint32_t d_slice, const uint32_t* 
 // later kernel uses.
 void launch_dest_keys(NoiseTable nt, const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed,
                       uint32_t* keys, uint32_t* err, hipStream_t st);
+// keys[sidx[i]] |= KEY_ALONE for every sorted entry i whose neighbours carry other keys.
+void launch_mark_alone(const uint32_t* skey, const uint32_t* sidx, uint32_t M, uint32_t* keys,
+                       hipStream_t st);
 void launch_check_inputs(const uint32_t* in_idx, uint32_t n, uint32_t V, uint32_t* in_safe,
                          uint32_t* err, hipStream_t st);
 void launch_copy_negatives(const uint32_t* keys, uint32_t n, uint32_t k, uint32_t* neg,
@@ -110,6 +114,10 @@ struct USideArgs {
     float* delta; uint32_t* dkey;
     float* prows; uint32_t* pkeys;
     bool fused;
+    // fused only, optional (W_update != null): keys carrying KEY_ALONE name rows that no other slot
+    // of the minibatch names; the kernel then writes W[row] += alpha * g * u itself (nobody else
+    // reads or writes that row in this minibatch) and the output side must leave those slots out.
+    float* W_update; float alpha;
 };
 void launch_useg(const USideArgs& a, hipStream_t st);
 // Minibatch loss from the coefficients alone: a slot with coefficient g contributes
@@ -124,6 +132,7 @@ void launch_loss_from_coeffs(const float* coeffs, uint32_t n, uint32_t T, double
 struct WSideArgs {
     const float* U; float* W; RowGeom g;
     const uint32_t* skey; const uint32_t* sidx; uint32_t M; uint32_t T;
+    bool skip_alone;             // entries whose neighbours carry other keys are handled elsewhere
     const uint32_t* in_idx; const float* coeffs; float alpha;
     float* prows; uint32_t* pkeys;
 };

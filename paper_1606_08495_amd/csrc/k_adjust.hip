@@ -21,6 +21,7 @@ constexpr int ADJ_THREADS = 256;
 constexpr int TAIL_C = 16;     // entries per chunk, higher levels (even, so a border's two slots
                                // fall into one chunk)
 constexpr uint32_t NOKEY = 0xFFFFFFFFu;   // compares unequal to every masked key
+constexpr uint32_t ALONE = KEY_ALONE;
 
 uint32_t tail_entries_per_chunk() { return TAIL_C; }
 uint32_t useg_pairs_per_chunk(uint32_t T) {     // about 48 entries, 2..16 pairs, <= 136 entries
@@ -48,6 +49,7 @@ struct SegArgs {
     uint32_t entries, T;
     float alpha;
     float4* prows; uint32_t* pkeys;    // this level's partial slots
+    bool skip_alone;                   // wown_kernel: runs of length one are handled elsewhere
 };
 
 template <int G, int NV, int C, int D, int SRC>
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
     for (int i = l; i < WOWN_E; i += G) {
         const uint32_t k = K(i), kn = K(i + 1);
         uint32_t act = ACT_SKIP;
-        if (active && k != NOKEY) {
+        if (active && k != NOKEY && !(a.skip_alone && kn != k && K(i - 1) != k)) {
             if (i < C) {
                 if (head_exists && k == k0) {            // a run that came in from the left
                     if (own_head) act = (kn != k) ? ACT_HEAD : ACT_ADD;
@@ -274,7 +276,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
         store_row_nt<G, NV>(a.dst + (uint64_t)row * s4, d4, l, out);
     };
     auto fetch = [&](int i, float4 (&sv)[NV], float4 (&dv)[NV]) {
-        const bool on = i < hi;
+        const bool on = i < hi && s_act[grp][i] != ACT_SKIP;
         const uint32_t sr = on ? s_srow[grp][i] : 0u;
         const bool cm = on && s_act[grp][i] == ACT_COMPLETE;
         const uint32_t dk = cm ? K(i) : 0u;
@@ -290,7 +292,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
 #pragma unroll
         for (int t = 0; t < D; ++t) {
             const int i = b + t;
-            if (i < hi) {
+            if (i < hi && s_act[grp][i] != ACT_SKIP) {
                 const uint32_t act = s_act[grp][i];
                 axpy<NV>(s_coef[grp][i], srcv[t], acc);
                 if (act == ACT_COMPLETE) {
@@ -368,6 +370,7 @@ void launch_wseg(const WSideArgs& w, hipStream_t st) {
     a.src = (const float4*)w.U; a.dst = (float4*)w.W; a.g = w.g; a.skey = w.skey; a.sidx = w.sidx;
     a.in_idx = w.in_idx; a.coeffs = w.coeffs; a.entries = w.M; a.T = w.T;
     a.alpha = w.alpha; a.prows = (float4*)w.prows; a.pkeys = w.pkeys;
+    a.skip_alone = w.skip_alone;
     // border slots of the cells: only pieces of long runs write them
     uint32_t ncells = (w.M + WOWN_L - 1) / WOWN_L;
     uint32_t slots = 2 * (ncells - 1);
@@ -388,6 +391,7 @@ void launch_tail(const TailArgs& t, hipStream_t st) {
     SegArgs a;
     a.src = (const float4*)t.src_rows; a.dst = (float4*)t.M; a.g = t.g; a.skey = t.src_keys;
     a.sidx = nullptr; a.in_idx = nullptr; a.coeffs = nullptr; a.entries = t.entries; a.T = 1;
+    a.skip_alone = false;
     a.alpha = t.alpha; a.prows = (float4*)t.prows; a.pkeys = t.pkeys;
     uint32_t nchunks = (t.entries + TAIL_C - 1) / TAIL_C;
 #define CALL(G, NV)                                                                              \
@@ -441,7 +445,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
     for (uint32_t i = l; i < cnt * T; i += G) {
         uint32_t pi = i / T, j = i - pi * T;
         uint32_t q = s_pair[grp][pi] * T + j;
-        s_key[grp][i] = a.keys[q];
+        s_key[grp][i] = a.keys[q];                 // may carry ALONE (fused, own rows)
         if (!FUSED) s_cf[grp][i] = a.coeffs_in[q];
     }
     __syncthreads();
@@ -466,7 +470,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
 #pragma unroll
     for (int t = 0; t < TB; ++t) {
         bool on = (uint32_t)t < T;
-        uint32_t r = on ? s_key[grp][t] : 0u;
+        uint32_t r = on ? (s_key[grp][t] & ~ALONE) : 0u;
         load_row_if<G, NV>(on, W4p + (uint64_t)r * s4, d4, l, w[t]);
     }
     if (FUSED) load_row<G, NV>(U4p + (uint64_t)key * s4, d4, l, u);
@@ -509,11 +513,27 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
             }
 #pragma unroll
             for (int t = 0; t < TB; ++t) {
-                if (jb + t < T) axpy<NV>(gco[t], w[t], acc);
+                if (jb + t < T) {
+                    axpy<NV>(gco[t], w[t], acc);
+                    // an output row that no other slot names gets its whole update here (see the
+                    // fixed-T kernel below)
+                    const uint32_t rr = (FUSED && a.W_update) ? s_key[grp][pi * T + jb + t] : 0u;
+                    if (FUSED && (rr & ALONE)) {
+                        float4 out[NV];
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            out[v].x = fmaf(a.alpha, fmaf(gco[t], u[v].x, 0.f), w[t][v].x);
+                            out[v].y = fmaf(a.alpha, fmaf(gco[t], u[v].y, 0.f), w[t][v].y);
+                            out[v].z = fmaf(a.alpha, fmaf(gco[t], u[v].z, 0.f), w[t][v].z);
+                            out[v].w = fmaf(a.alpha, fmaf(gco[t], u[v].w, 0.f), w[t][v].w);
+                        }
+                        store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(rr & ~ALONE) * s4, d4, l, out);
+                    }
+                }
                 // this register set is free again: fetch the matching row of the following batch
                 uint32_t nj = njb + t;
                 bool on = npi < cnt && nj < T;
-                uint32_t r = on ? s_key[grp][npi * T + nj] : 0u;
+                uint32_t r = on ? (s_key[grp][npi * T + nj] & ~ALONE) : 0u;
                 load_row_if<G, NV>(on, W4p + (uint64_t)r * s4, d4, l, w[t]);
             }
         }
@@ -584,7 +604,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_multi_kernel(USideArgs a, ui
     for (uint32_t i = l; i < cnt * T; i += G) {
         uint32_t pi = i / T, j = i - pi * T;
         uint32_t q = s_pair[grp][pi] * T + j;
-        s_key[grp][i] = a.keys[q];
+        s_key[grp][i] = a.keys[q];                 // may carry ALONE (fused, own rows)
         if (!FUSED) s_cf[grp][i] = a.coeffs_in[q];
     }
     __syncthreads();
@@ -617,7 +637,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_multi_kernel(USideArgs a, ui
             }
 #pragma unroll
             for (int j = 0; j < T; ++j) {
-                const uint32_t r = live ? s_key[grp][pi * T + j] : 0u;
+                const uint32_t r = live ? (s_key[grp][pi * T + j] & ~ALONE) : 0u;
                 load_row_if<G, NV>(live, W4p + (uint64_t)r * s4, d4, l, w[b][j]);
             }
         }
@@ -643,6 +663,27 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_multi_kernel(USideArgs a, ui
                         if (l == j % G) {
                             a.coeffs_out[p * T + j] = gco[j];
                             if (a.dots_out) a.dots_out[p * T + j] = f;
+                        }
+                    }
+                    // An output row that no other slot names gets its whole update here, from the
+                    // registers, with the same two roundings as the output-side kernel
+                    // (fl(g u), then one fma with alpha); that kernel never sees the slot.
+                    if (a.W_update) {
+#pragma unroll
+                        for (int j = 0; j < T; ++j) {
+                            const uint32_t r = s_key[grp][pi * T + j];
+                            if (r & ALONE) {
+                                float4 out[NV];
+#pragma unroll
+                                for (int v = 0; v < NV; ++v) {
+                                    out[v].x = fmaf(a.alpha, fmaf(gco[j], u[b][v].x, 0.f), w[b][j][v].x);
+                                    out[v].y = fmaf(a.alpha, fmaf(gco[j], u[b][v].y, 0.f), w[b][j][v].y);
+                                    out[v].z = fmaf(a.alpha, fmaf(gco[j], u[b][v].z, 0.f), w[b][j][v].z);
+                                    out[v].w = fmaf(a.alpha, fmaf(gco[j], u[b][v].w, 0.f), w[b][j][v].w);
+                                }
+                                store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(r & ~ALONE) * s4, d4,
+                                                    l, out);
+                            }
                         }
                     }
                 } else {

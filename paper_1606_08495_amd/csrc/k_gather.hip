@@ -133,6 +133,21 @@ __global__ __launch_bounds__(256) void dest_keys_kernel(const uint2* __restrict_
     keys[i] = key;
 }
 
+// After the sort of the destination keys: an entry whose two neighbours carry other keys is the
+// only slot of the minibatch that names its row.  Such slots get KEY_ALONE set in the slot-ordered
+// key array (each slot is written by at most one thread), so that the input-side kernel, which
+// holds everything the row's update needs, can write it, and the output side can leave it out.
+__global__ __launch_bounds__(256) void mark_alone_kernel(const uint32_t* __restrict__ skey,
+                                                         const uint32_t* __restrict__ sidx,
+                                                         uint32_t M, uint32_t* __restrict__ keys) {
+    uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= M) return;
+    const uint32_t k = skey[i];
+    const bool left = i > 0 && skey[i - 1] == k;
+    const bool right = i + 1 < M && skey[i + 1] == k;
+    if (!left && !right) keys[sidx[i]] = k | KEY_ALONE;
+}
+
 void launch_dest_keys(NoiseTable nt, const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed,
                       uint32_t* keys, uint32_t* err, hipStream_t st) {
     if (n == 0) return;
@@ -140,6 +155,13 @@ void launch_dest_keys(NoiseTable nt, const uint32_t* out_idx, uint32_t n, uint32
     hipLaunchKernelGGL(dest_keys_kernel, dim3(blocks_for((uint64_t)n * T, 256)), dim3(256), 0, st,
                        nt.bins, nt.V, out_idx, n, T, (uint32_t)seed, (uint32_t)(seed >> 32), keys,
                        err);
+}
+
+void launch_mark_alone(const uint32_t* skey, const uint32_t* sidx, uint32_t M, uint32_t* keys,
+                       hipStream_t st) {
+    if (M == 0) return;
+    hipLaunchKernelGGL(mark_alone_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, st, skey, sidx, M,
+                       keys);
 }
 
 // Range-checked copy of the input words: an index >= V raises *err and is replaced by word 0, so no

@@ -142,7 +142,17 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_hist_kernel(const uint32_t*
 #pragma unroll
     for (int e = 0; e < SORT_ITEMS; ++e) {
         uint64_t i = base + (uint64_t)e * SORT_THREADS + threadIdx.x;
-        if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+        const bool valid = i < n;
+        const uint32_t d = valid ? (keys[i] >> shift) & 255u : 0u;
+        // long stretches of one key (a very frequent word, or the sentinel of slots that are left
+        // out) would serialise 64 atomics on one counter: one lane adds for the whole wavefront
+        const uint64_t live = __ballot(valid);
+        const uint32_t d0 = __shfl(d, live ? __ffsll((long long)live) - 1 : 0, 64);
+        if (live && __ballot(valid && d == d0) == live) {
+            if ((threadIdx.x & 63) == __ffsll((long long)live) - 1) atomicAdd(&h[d0], (uint32_t)__popcll(live));
+        } else if (valid) {
+            atomicAdd(&h[d], 1u);
+        }
     }
     __syncthreads();
     hist[(uint64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
