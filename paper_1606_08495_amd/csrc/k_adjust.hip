@@ -204,6 +204,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
     __shared__ uint32_t s_srow[GROUPS][WOWN_E];
     __shared__ float s_coef[GROUPS][WOWN_E];
     __shared__ uint32_t s_act[GROUPS][WOWN_E];
+    __shared__ uint32_t s_list[GROUPS][WOWN_E];
     const int l = threadIdx.x % G, grp = threadIdx.x / G;
     const uint32_t c = blockIdx.x * (uint32_t)GROUPS + grp;
     const uint32_t nchunks = (a.entries + C - 1) / C;
@@ -223,9 +224,14 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
     const bool ext_ok = klast != NOKEY && !last_in_head && k2C != klast;
     // does the run through the chunk's last entry go on, as a long piece that this group owns?
     const bool cont = active && klast != NOKEY && kC == klast && (last_in_head ? own_head : k2C == klast);
-    int my_lo = WOWN_E, my_hi = 0;
-    for (int i = l; i < WOWN_E; i += G) {
-        const uint32_t k = K(i), kn = K(i + 1);
+    // The positions this group sums are listed densely in s_list (positions that are skipped --
+    // another group's, or rows handled elsewhere -- take no place in the load pipeline below).
+    int count = 0;
+    const int group_lane0 = ((int)(threadIdx.x & 63) / G) * G;
+    for (int i0 = 0; i0 < WOWN_E; i0 += G) {
+        const int i = i0 + l;
+        const bool inside = i < WOWN_E;
+        const uint32_t k = inside ? K(i) : NOKEY, kn = inside ? K(i + 1) : NOKEY;
         uint32_t act = ACT_SKIP;
         if (active && k != NOKEY && !(a.skip_alone && kn != k && K(i - 1) != k)) {
             if (i < C) {
@@ -240,23 +246,20 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
                 act = (kn != k) ? ACT_COMPLETE : ACT_ADD;
             }
         }
-        s_act[grp][i] = act;
-        if (act != ACT_SKIP) {
+        if (inside) s_act[grp][i] = act;
+        const bool use = act != ACT_SKIP;
+        const uint64_t wave_mask = __ballot(use);
+        const uint64_t mine = (G == 64) ? wave_mask : ((wave_mask >> group_lane0) & ((1ull << G) - 1ull));
+        if (use) {
             const uint32_t q = a.sidx[base + i];
             s_srow[grp][i] = a.in_idx[q / a.T];          // range-checked copy
             s_coef[grp][i] = a.coeffs[q];
-            my_lo = min(my_lo, i);
-            my_hi = max(my_hi, i + 1);
+            s_list[grp][count + __popcll(mine & ((1ull << l) - 1ull))] = (uint32_t)i;
         }
-    }
-#pragma unroll
-    for (int m = G / 2; m >= 1; m >>= 1) {                // the active positions form one range
-        my_lo = min(my_lo, __shfl_xor(my_lo, m, 64));
-        my_hi = max(my_hi, __shfl_xor(my_hi, m, 64));
+        count += __popcll(mine);
     }
     __syncthreads();
-    if (!active || my_lo >= my_hi) return;
-    const int lo = my_lo, hi = my_hi;
+    if (!active || count == 0) return;
     const uint32_t d4 = a.g.d4;
     const uint64_t s4 = a.g.stride4;
     const uint32_t cell = (uint32_t)(base / L);
@@ -275,8 +278,9 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
         }
         store_row_nt<G, NV>(a.dst + (uint64_t)row * s4, d4, l, out);
     };
-    auto fetch = [&](int i, float4 (&sv)[NV], float4 (&dv)[NV]) {
-        const bool on = i < hi && s_act[grp][i] != ACT_SKIP;
+    auto fetch = [&](int idx, float4 (&sv)[NV], float4 (&dv)[NV]) {
+        const bool on = idx < count;
+        const int i = on ? (int)s_list[grp][idx] : 0;
         const uint32_t sr = on ? s_srow[grp][i] : 0u;
         const bool cm = on && s_act[grp][i] == ACT_COMPLETE;
         const uint32_t dk = cm ? K(i) : 0u;
@@ -287,12 +291,13 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
         load_row_nt_if<G, NV>(cm, a.dst + (uint64_t)dk * s4, d4, l, dv);
     };
 #pragma unroll
-    for (int t = 0; t < D; ++t) fetch(lo + t, srcv[t], dstv[t]);
-    for (int b = lo; b < hi; b += D) {
+    for (int t = 0; t < D; ++t) fetch(t, srcv[t], dstv[t]);
+    for (int b = 0; b < count; b += D) {
 #pragma unroll
         for (int t = 0; t < D; ++t) {
-            const int i = b + t;
-            if (i < hi && s_act[grp][i] != ACT_SKIP) {
+            const int idx = b + t;
+            if (idx < count) {
+                const int i = (int)s_list[grp][idx];
                 const uint32_t act = s_act[grp][i];
                 axpy<NV>(s_coef[grp][i], srcv[t], acc);
                 if (act == ACT_COMPLETE) {
@@ -304,7 +309,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
                     clear<NV>(acc);
                 }
             }
-            fetch(i + D, srcv[t], dstv[t]);
+            fetch(idx + D, srcv[t], dstv[t]);
         }
     }
     if (!cont) return;
@@ -312,7 +317,6 @@ __global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
     // ---- the long piece goes on past the chunk: stream through the rest of the cell ----
     const uint32_t key = klast;
     const int64_t limit = min((int64_t)(cell + 1) * L, (int64_t)a.entries);
-    const int group_lane0 = ((int)(threadIdx.x & 63) / G) * G;
     bool ended = false;
     for (int64_t x0 = base + C; x0 < limit; x0 += 16) {
         const int nblk = (int)min((int64_t)16, limit - x0);
