@@ -33,30 +33,27 @@ def log(*a):
 
 
 class PairStream:
-    """Feeds minibatches of n pairs cut from the pair stream of a token corpus (device side)."""
+    """Feeds minibatches of n pairs cut from the pair stream of a token corpus (device side).  Pairs
+    are formed block by block into one pair of buffers sized for the whole run and never moved, so
+    that the minibatch after the current one can be announced to the shard ahead of time."""
 
-    def __init__(self, shard, wl, tokens, sent_off, block_tokens, torch):
+    def __init__(self, shard, wl, tokens, sent_off, block_tokens, torch, minibatches):
         self.torch = torch
         self.sh, self.wl = shard, wl
         self.tok = torch.from_numpy(tokens.view(np.int32)).cuda()
         self.off_host = sent_off.astype(np.int64)
         self.block_tokens = block_tokens
-        cap = wl.n_pairs + block_tokens * 2 * wl.window
+        cap = (minibatches + 2) * wl.n_pairs + block_tokens * 2 * wl.window
         self.a = torch.empty(cap, dtype=torch.int32, device="cuda")
         self.b = torch.empty(cap, dtype=torch.int32, device="cuda")
-        self.have = 0           # valid pairs at the front of the buffers
-        self.pos = 0            # consumed pairs
+        self.have = 0           # pairs formed so far
+        self.pos = 0            # pairs handed out
         self.sent = 0           # next sentence
         self.epoch = 0
         self.tokens_used = 0
 
-    def _refill(self):
+    def _more(self):
         torch = self.torch
-        rest = self.have - self.pos
-        if rest > 0 and self.pos > 0:
-            self.a[:rest] = self.a[self.pos:self.have].clone()
-            self.b[:rest] = self.b[self.pos:self.have].clone()
-        self.have, self.pos = rest, 0
         off = self.off_host
         if self.sent >= off.size - 1:
             self.sent, self.epoch = 0, self.epoch + 1
@@ -69,19 +66,25 @@ class PairStream:
         rel = torch.from_numpy(off[s0:s1 + 1] - t0).cuda()
         cnt = self.sh.make_pairs(self.tok[t0:t1], rel, t0, self.epoch, self.wl.seed, self.wl.window,
                                  self.a[self.have:], self.b[self.have:])
-        assert cnt <= self.a.numel() - self.have
+        assert cnt <= self.a.numel() - self.have, "pair buffers too small for this run"
         self.have += cnt
         self.sent = s1
         self.tokens_used += t1 - t0
 
     def next(self):
+        """The current minibatch; the one after it is formed as well (see peek)."""
         n = self.wl.n_pairs
-        while self.have - self.pos < n:
-            self._refill()
+        while self.have - self.pos < 2 * n:
+            self._more()
         a = self.a[self.pos:self.pos + n]
         b = self.b[self.pos:self.pos + n]
         self.pos += n
         return a, b
+
+    def peek(self):
+        """The minibatch the following next() will return (same device addresses)."""
+        n = self.wl.n_pairs
+        return self.a[self.pos:self.pos + n], self.b[self.pos:self.pos + n]
 
 
 def cpu_baseline_full(wl, counts, in_idx, out_idx, seed, sample_pairs):
@@ -393,11 +396,12 @@ def run_gather_probe(args, torch, w2v, workloads):
 
 
 def distinct_rows(torch, shard, in_idx, out_idx, k, seed):
-    """Distinct input rows and distinct output/negative rows of one minibatch (for byte counts)."""
+    """Distinct input rows, distinct output/negative rows, and output rows named by one slot only,
+    of one minibatch (for byte counts)."""
     neg = shard.negatives(out_idx, k, seed)
     du = int(torch.unique(in_idx).numel())
-    dw = int(torch.unique(torch.cat([out_idx, neg.reshape(-1)])).numel())
-    return du, dw
+    _, c = torch.unique(torch.cat([out_idx, neg.reshape(-1)]), return_counts=True)
+    return du, int(c.numel()), int((c == 1).sum().item())
 
 
 def main():
@@ -421,6 +425,8 @@ def main():
                     help="pairs the CPU oracle is timed on (default: about 10-30 s of one core)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loss", action="store_true", help="do not request the minibatch loss")
+    ap.add_argument("--no-prefetch", action="store_true",
+                    help="do not announce the next minibatch to the shard (w2v_prefetch_minibatch)")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates HBM counters)")
     args = ap.parse_args()
@@ -477,11 +483,15 @@ def main():
                                            "stress25": 700_000 * (K + Wm + 2)}[wl.name]
             tokens, off = workloads.corpus(wl, n_tok, cdf=cdf)
         del cdf
-        stream = PairStream(sh, wl, tokens, off, block_tokens=min(tokens.size, 1 << 21), torch=torch)
+        stream = PairStream(sh, wl, tokens, off, block_tokens=min(tokens.size, 1 << 21), torch=torch,
+                            minibatches=total_steps + 1)
         H = max(1, wl.corpus_tokens * 4 // wl.n_pairs)     # minibatches in the nominal corpus
 
         def step(h):
             a, b = stream.next()
+            if not args.no_prefetch:                       # the next minibatch's index work, ahead
+                na, nb = stream.peek()
+                sh.prefetch_minibatch(na, nb, wl.k, w2v.minibatch_seed(wl.seed, h + 1))
             w2v.train_minibatch([sh], a, b, wl.k, w2v.minibatch_seed(wl.seed, h),
                                 workloads.alpha_schedule(wl, h, H), loss=loss)
             return a, b
@@ -508,7 +518,10 @@ def main():
         phases = sh.timing_read()
         sh.timing_enable(False)
         sh.status()
-        du, dw = distinct_rows(torch, sh, last[0], last[1], wl.k, w2v.minibatch_seed(wl.seed, total_steps - 1))
+        du, dw, single = distinct_rows(torch, sh, last[0], last[1], wl.k,
+                                       w2v.minibatch_seed(wl.seed, total_steps - 1))
+        if os.environ.get("W2V_NO_OWN_ROWS", "0") not in ("", "0"):
+            single = 0
         result_extra["tokens_per_minibatch"] = stream.tokens_used / max(1, total_steps)
         if not args.no_cpu_baseline:
             cpu = cpu_baseline_full(wl, counts, first[0], first[1], w2v.minibatch_seed(wl.seed, 0),
@@ -541,7 +554,8 @@ def main():
         phases = sh.timing_read()
         sh.timing_enable(False)
         sh.status()
-        du, dw = distinct_rows(torch, sh, a, b, wl.k, w2v.minibatch_seed(wl.seed, total_steps - 1))
+        du, dw, _ = distinct_rows(torch, sh, a, b, wl.k, w2v.minibatch_seed(wl.seed, total_steps - 1))
+        single = 0                      # the two-call form sums every output row on the output side
         if not args.no_cpu_baseline:
             cpu = cpu_baseline_slice(wl, counts, ii, oo, g, w2v.minibatch_seed(wl.seed, 0),
                                      args.cpu_sample_pairs)
@@ -555,13 +569,15 @@ def main():
     #   dot      : (k+2) rows per pair + keys + dots written
     #   uside    : T output rows per pair (+ the input row when fused) + keys/coefficients/sort data
     #              + one delta row written per distinct input row
+    #              + (fused) one row written per output row that a single slot names
     #   wside    : one input row per contribution + 12 B of key/slot/coefficient
     #              + one read and one write of every distinct destination row
+    #              (fused: without the slots and rows that the input side has taken over)
     fused = wl.pairs_from_corpus
     algo = {
         "dot": n * (wl.k + 2) * R + 8 * M,
-        "uside": n * (T + (1 if fused else 0)) * R + 8 * M + 8 * n + du * R,
-        "wside": M * R + 12 * M + 2 * dw * R,
+        "uside": n * (T + (1 if fused else 0)) * R + 8 * M + 8 * n + du * R + single * R,
+        "wside": (M - single) * R + 12 * M + 2 * (dw - single) * R,
     }
     per_phase = {}
     for name, (ms, cnt) in phases.items():
@@ -578,7 +594,7 @@ def main():
             parts = line.split()
             if len(parts) == 3 and parts[0] == "traffic" and parts[1] == dom:
                 traffic = float(parts[2])
-    step_algo = 3 * (wl.k + 2) * R * n
+    step_algo = 3 * (wl.k + 2) * R * n      # the paper-style logical figure: 3 (k+2) rows per pair
     out = {
         "metric": "SGNS training pairs/s (k negatives incl.) on 1 MI355X",
         "value": pairs_per_s,
@@ -596,7 +612,9 @@ def main():
                    "pairs_per_minibatch": n, "k": wl.k, "zipf_s": wl.zipf_s, "window": wl.window,
                    "subsample_t": wl.subsample_t,
                    "path": "make_pairs+train_minibatch" if fused else "dotprod+adjust",
-                   "distinct_input_rows": du, "distinct_output_rows": dw},
+                   "distinct_input_rows": du, "distinct_output_rows": dw,
+                   "output_rows_named_once": single,
+                   "prefetch": bool(fused and not args.no_prefetch)},
         "roofline": {"bound": "hbm", "kernel": KERNEL_OF_PHASE.get(dom, dom), "phase": dom,
                      "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

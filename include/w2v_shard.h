@@ -146,6 +146,20 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
                    uint64_t corpus_seed, uint32_t B, uint32_t* in_idx_dev, uint32_t* out_idx_dev,
                    uint64_t capacity, uint64_t* n_pairs_host, void* stream);
 
+/* Optional look-ahead for a training loop on one shard.  Everything w2v_train_minibatch derives from
+ * the indices alone -- the negatives, and the grouping of the minibatch's input and output rows that
+ * makes the update deterministic -- depends on neither the vectors nor earlier minibatches.  This call
+ * queues that work for a LATER minibatch on the shard's second stream, ordered after the work queued
+ * on `stream` so far, so that it runs beside the training call that is queued next:
+ *     prefetch(h+1); train(h); prefetch(h+2); train(h+1); ...
+ * A w2v_train_minibatch on this shard alone (S = 1) with the same in_idx_dev, out_idx_dev (same
+ * pointers, contents unchanged in between), n, k and seed uses the prepared work; otherwise it
+ * computes everything itself as if this call had not been made.  Results are identical either way.
+ * Two minibatches can be held ahead (a third look-ahead replaces the older one); each keeps its own
+ * device buffers (about 20 (k+2) n bytes, allocated on first use and reused). */
+int w2v_prefetch_minibatch(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
+                           uint32_t n, uint32_t k, uint64_t seed, void* stream);
+
 /* ---- interleaved minibatch formation (Section 5.1, last paragraph) -------------------------------
  * Same arguments and the same set of pairs as w2v_make_pairs, in another order: the centers are
  * visited round-robin over the sentences of the block -- every sentence's first surviving token (in

@@ -51,6 +51,25 @@ extern "C" const char* w2v_last_error(void) { return g_last_error.c_str(); }
 // ---------------------------------------------------------------------------------------------
 struct TimedSpan { int phase; hipEvent_t a, b; };
 
+// Index work of one minibatch computed ahead of its training call (w2v_prefetch_minibatch): the
+// checked input words and their sort, the destination keys and their sort.  Two sets alternate, so
+// that the one a running step reads is never the one being filled.
+struct IndexSet {
+    char* base = nullptr; size_t cap = 0;
+    uint32_t *keys = nullptr, *in_safe = nullptr;
+    uint32_t *uk0 = nullptr, *uv0 = nullptr, *uk1 = nullptr, *uv1 = nullptr;
+    uint32_t *wk0 = nullptr, *wv0 = nullptr, *wk1 = nullptr, *wv1 = nullptr;
+    uint32_t *sort_tmp = nullptr, *sort_tmp_u = nullptr;
+    uint32_t *sku = nullptr, *perm = nullptr, *skw = nullptr, *sidx = nullptr;   // sorted results
+    hipEvent_t ready = nullptr;
+};
+
+struct Prepared {
+    bool valid = false; int set = 0; bool own_rows = false;
+    const uint32_t* in_idx = nullptr; const uint32_t* out_idx = nullptr;
+    uint32_t n = 0, k = 0; uint64_t seed = 0;
+};
+
 struct w2v_shard {
     int device = 0;
     uint32_t V = 0, d_total = 0, col_begin = 0, d_slice = 0;
@@ -74,6 +93,10 @@ struct w2v_shard {
     hipEvent_t ev_coeffs = nullptr, ev_wdone = nullptr, ev_tails = nullptr;
     bool overlap = true;
     bool own_rows = true;           // fused step: singly named output rows updated by the input side
+    IndexSet sets[2];
+    Prepared prep[2];               // what sets[i] holds
+    int next_set = 0;
+    hipEvent_t ev_pfork = nullptr;
     // timing
     bool timing = false;
     std::vector<TimedSpan> spans;
@@ -242,6 +265,40 @@ int ensure_side_stream(w2v_shard* sh) {
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_coeffs, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_wdone, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_tails, hipEventDisableTiming));
+    return W2V_OK;
+}
+
+// Buffers of one prefetched minibatch, carved from the set's own allocation (grown on demand).
+int ensure_set(w2v_shard* sh, IndexSet& x, uint32_t n, uint32_t M) {
+    for (int pass = 0; pass < 2; ++pass) {
+        Carver c(pass ? x.base : nullptr);
+        uint32_t* keys = c.take<uint32_t>(M);
+        uint32_t* in_safe = c.take<uint32_t>(n);
+        uint32_t* uk0 = c.take<uint32_t>(n); uint32_t* uv0 = c.take<uint32_t>(n);
+        uint32_t* uk1 = c.take<uint32_t>(n); uint32_t* uv1 = c.take<uint32_t>(n);
+        uint32_t* wk0 = c.take<uint32_t>(M); uint32_t* wv0 = c.take<uint32_t>(M);
+        uint32_t* wk1 = c.take<uint32_t>(M); uint32_t* wv1 = c.take<uint32_t>(M);
+        uint32_t* tw = c.take<uint32_t>(sort_scratch_u32(M ? M : 1));
+        uint32_t* tu = c.take<uint32_t>(sort_scratch_u32(n ? n : 1));
+        const size_t need = c.off + 256;
+        if (pass == 0) {
+            if (need > x.cap) {
+                if (x.base) { HIP_TRY(hipDeviceSynchronize()); HIP_TRY(hipFree(x.base)); x.base = nullptr; x.cap = 0; }
+                hipError_t e = hipMalloc((void**)&x.base, need);
+                if (e != hipSuccess) {
+                    (void)hipGetLastError();
+                    return fail(W2V_ERR_ALLOC, "allocation of %zu bytes for a prefetched minibatch failed: %s",
+                                need, hipGetErrorString(e));
+                }
+                x.cap = need;
+            }
+        } else {
+            x.keys = keys; x.in_safe = in_safe; x.uk0 = uk0; x.uv0 = uv0; x.uk1 = uk1; x.uv1 = uv1;
+            x.wk0 = wk0; x.wv0 = wv0; x.wk1 = wk1; x.wv1 = wv1; x.sort_tmp = tw; x.sort_tmp_u = tu;
+        }
+    }
+    if (!x.ready) HIP_TRY(hipEventCreateWithFlags(&x.ready, hipEventDisableTiming));
+    if (!sh->ev_pfork) HIP_TRY(hipEventCreateWithFlags(&sh->ev_pfork, hipEventDisableTiming));
     return W2V_OK;
 }
 
@@ -441,6 +498,11 @@ extern "C" int w2v_shard_destroy(w2v_shard* sh) {
     if (sh->ev_coeffs) (void)hipEventDestroy(sh->ev_coeffs);
     if (sh->ev_wdone) (void)hipEventDestroy(sh->ev_wdone);
     if (sh->ev_tails) (void)hipEventDestroy(sh->ev_tails);
+    if (sh->ev_pfork) (void)hipEventDestroy(sh->ev_pfork);
+    for (auto& x : sh->sets) {
+        if (x.ready) (void)hipEventDestroy(x.ready);
+        if (x.base) (void)hipFree(x.base);
+    }
     if (sh->side) (void)hipStreamDestroy(sh->side);
     delete sh;
     return W2V_OK;
@@ -675,8 +737,23 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
     if (rc) return rc;
     Plan p = make_plan(s0->ws, n, k, stride_max, fused ? 0 : S, true, true, own);
     uint32_t *sku, *perm, *skw, *sidx;
-    rc = queue_keys_and_sorts(s0, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);
-    if (rc) return rc;
+    int ahead = -1;                                      // a set computed by w2v_prefetch_minibatch?
+    for (int i = 0; i < 2 && fused; ++i) {
+        const Prepared& pr = s0->prep[i];
+        if (pr.valid && pr.in_idx == in_idx && pr.out_idx == out_idx && pr.n == n && pr.k == k &&
+            pr.seed == seed && pr.own_rows == p.own_rows)
+            ahead = i;
+    }
+    if (ahead >= 0) {
+        IndexSet& x = s0->sets[ahead];
+        s0->prep[ahead].valid = false;                   // a set is used once
+        HIP_TRY(hipStreamWaitEvent(st, x.ready, 0));
+        p.keys = x.keys; p.in_safe = x.in_safe;
+        sku = x.sku; perm = x.perm; skw = x.skw; sidx = x.sidx;
+    } else {
+        rc = queue_keys_and_sorts(s0, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);
+        if (rc) return rc;
+    }
     if (fused) {
         queue_adjust(s0, s0, p, sku, perm, skw, sidx, nullptr, p.coeffs, true, alpha, loss, st);
     } else {
@@ -697,6 +774,46 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
             queue_adjust(s0, shards[s], p, sku, perm, skw, sidx, p.coeffs, nullptr, false, alpha, nullptr, st);
     }
     HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+extern "C" int w2v_prefetch_minibatch(w2v_shard* sh, const uint32_t* in_idx, const uint32_t* out_idx,
+                                      uint32_t n, uint32_t k, uint64_t seed, void* stream) {
+    if (!sh || (n && (!in_idx || !out_idx))) return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_device(sh);
+    if (!rc) rc = check_batch(sh, n, k, true);
+    if (rc) return rc;
+    if (n == 0 || !sh->overlap) return W2V_OK;            // nothing to gain without the second stream
+    hipStream_t st = (hipStream_t)stream;
+    rc = ensure_side_stream(sh);
+    if (rc) return rc;
+    const int which = sh->next_set;
+    IndexSet& x = sh->sets[which];
+    sh->prep[which].valid = false;
+    const uint32_t M = n * (k + 1);
+    rc = ensure_set(sh, x, n, M);
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(sh->ev_pfork, st));
+    HIP_TRY(hipStreamWaitEvent(sh->side, sh->ev_pfork, 0));
+    hipStream_t side = sh->side;
+    const uint32_t bits = key_bits(sh->V);
+    {
+        Phase ph(sh, W2V_PH_NEG, side);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, n, k, seed, x.keys, sh->err, side);
+    }
+    {
+        Phase ph(sh, W2V_PH_SORT, side);
+        launch_sort_pairs(x.keys, x.wk0, x.wv0, x.wk1, x.wv1, M, bits, x.sort_tmp, &x.skw, &x.sidx, side);
+        if (sh->own_rows) launch_mark_alone(x.skw, x.sidx, M, x.keys, side);
+        launch_check_inputs(in_idx, n, sh->V, x.in_safe, sh->err, side);
+        launch_sort_pairs(x.in_safe, x.uk0, x.uv0, x.uk1, x.uv1, n, bits, x.sort_tmp_u, &x.sku, &x.perm, side);
+    }
+    HIP_TRY(hipEventRecord(x.ready, side));
+    HIP_TRY(hipGetLastError());
+    Prepared& pr = sh->prep[which];
+    pr.valid = true; pr.set = which; pr.own_rows = sh->own_rows;
+    pr.in_idx = in_idx; pr.out_idx = out_idx; pr.n = n; pr.k = k; pr.seed = seed;
+    sh->next_set = which ^ 1;
     return W2V_OK;
 }
 

@@ -36,6 +36,7 @@ _SIGNATURES = {
     "w2v_adjust": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp, ctypes.c_float, c_vp]),
     "w2v_train_minibatch": (ctypes.c_int, [ctypes.POINTER(c_vp), c_u32, c_vp, c_vp, c_u32, c_u32,
                                            c_u64, ctypes.c_float, c_vp, c_vp]),
+    "w2v_prefetch_minibatch": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp]),
     "w2v_make_pairs": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_u32, c_u64, c_u32,
                                       c_vp, c_vp, c_u64, ctypes.POINTER(c_u64), c_vp]),
     "w2v_make_pairs_interleaved": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_u32, c_u64,
@@ -209,6 +210,12 @@ class Shard:
         _check(lib().w2v_adjust(self.h, _dev(in_idx, IDX, "in_idx"), _dev(out_idx, IDX, "out_idx"),
                                 n, int(k), int(seed), _dev(coeffs, torch.float32, "coeffs"),
                                 float(alpha), _stream(stream)))
+
+    def prefetch_minibatch(self, in_idx, out_idx, k, seed, stream=None):
+        """Index work of the next minibatch, queued beside the current one (w2v_prefetch_minibatch)."""
+        _check(lib().w2v_prefetch_minibatch(self.h, _dev(in_idx, IDX, "in_idx"),
+                                            _dev(out_idx, IDX, "out_idx"), in_idx.numel(), int(k),
+                                            int(seed), _stream(stream)))
 
     def make_pairs(self, tokens, sent_off, token_base, epoch, corpus_seed, B, in_idx, out_idx,
                    stream=None, interleaved=False):

@@ -601,3 +601,41 @@ def test_random_text_blocks_pairs_interleaved_pairs_and_examples(case):
     assert np.array_equal(w2v.index_to_numpy(ce[:n_ex]), oout)
     sh.status()
     sh.destroy()
+
+
+# --- look-ahead ------------------------------------------------------------------------------------------
+
+def test_prefetch_gives_the_same_bits_and_a_mismatch_is_harmless():
+    V, d, n, k, steps = 3000, 300, 4099, 5, 6
+    rng = np.random.default_rng(77)
+    counts = zipf_counts(V)
+    cdf = workloads.zipf_cdf(V, 1.0)
+    ins = [dev(workloads.zipf_draw(cdf, n, rng)) for _ in range(steps + 1)]
+    outs = [dev(workloads.zipf_draw(cdf, n, rng)) for _ in range(steps + 1)]
+    seeds = [w2v.minibatch_seed(3, h) for h in range(steps + 1)]
+    plain, ahead, mixed = (make_shard(V, d, 5, counts) for _ in range(3))
+    la, lb = (torch.zeros(1, dtype=torch.float64, device="cuda") for _ in range(2))
+    for h in range(steps):
+        w2v.train_minibatch([plain], ins[h], outs[h], k, seeds[h], 0.05, loss=la)
+        ahead.prefetch_minibatch(ins[h + 1], outs[h + 1], k, seeds[h + 1])      # next one, before this one
+        w2v.train_minibatch([ahead], ins[h], outs[h], k, seeds[h], 0.05, loss=lb)
+        assert la.item() == lb.item()
+        # announcements that do not match what is trained next: other seed, other arrays, other k
+        mixed.prefetch_minibatch(ins[h], outs[h], k, seeds[h] + 1)
+        mixed.prefetch_minibatch(outs[h], ins[h], k, seeds[h])
+        w2v.train_minibatch([mixed], ins[h], outs[h], k, seeds[h], 0.05)
+        mixed.prefetch_minibatch(ins[h], outs[h], k + 1, seeds[h])
+    for which in (0, 1):
+        ref = all_rows(plain, which)
+        assert np.array_equal(all_rows(ahead, which), ref)
+        assert np.array_equal(all_rows(mixed, which), ref)
+    # and the oracle agrees
+    U, W = oracle_state(V, d, 5)
+    th, al = oracle.build_alias(counts)
+    for h in range(steps):
+        oracle.train_minibatch([U], [W], w2v.index_to_numpy(ins[h]), w2v.index_to_numpy(outs[h]), k,
+                               seeds[h], th, al, 0.05)
+    assert vec_error(all_rows(ahead, 0), U) <= 6 * TOL1 and vec_error(all_rows(ahead, 1), W) <= 6 * TOL1
+    for sh in (plain, ahead, mixed):
+        sh.status()
+        sh.destroy()
