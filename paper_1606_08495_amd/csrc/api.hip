@@ -95,6 +95,7 @@ struct w2v_shard {
     bool own_rows = true;           // fused step: singly named output rows updated by the input side
     IndexSet sets[2];
     Prepared prep[2];               // what sets[i] holds
+    Prepared deferred;              // announced by w2v_prefetch_minibatch, not yet queued
     int next_set = 0;
     hipEvent_t ev_pfork = nullptr;
     // timing
@@ -345,6 +346,39 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
     return W2V_OK;
 }
 
+// The index work of a minibatch announced by w2v_prefetch_minibatch, queued on the second stream
+// behind everything queued on `st` so far.
+int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
+    const int which = sh->next_set;
+    IndexSet& x = sh->sets[which];
+    sh->prep[which].valid = false;
+    const uint32_t n = want.n, k = want.k, M = n * (k + 1);
+    int rc = ensure_set(sh, x, n, M);
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(sh->ev_pfork, st));
+    HIP_TRY(hipStreamWaitEvent(sh->side, sh->ev_pfork, 0));
+    hipStream_t side = sh->side;
+    const uint32_t bits = key_bits(sh->V);
+    {
+        Phase ph(sh, W2V_PH_NEG, side);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, want.out_idx, n, k, want.seed, x.keys, sh->err, side);
+    }
+    {
+        Phase ph(sh, W2V_PH_SORT, side);
+        launch_sort_pairs(x.keys, x.wk0, x.wv0, x.wk1, x.wv1, M, bits, x.sort_tmp, &x.skw, &x.sidx, side);
+        if (sh->own_rows) launch_mark_alone(x.skw, x.sidx, M, x.keys, side);
+        launch_check_inputs(want.in_idx, n, sh->V, x.in_safe, sh->err, side);
+        launch_sort_pairs(x.in_safe, x.uk0, x.uv0, x.uk1, x.uv1, n, bits, x.sort_tmp_u, &x.sku, &x.perm, side);
+    }
+    HIP_TRY(hipEventRecord(x.ready, side));
+    HIP_TRY(hipGetLastError());
+    Prepared& pr = sh->prep[which];
+    pr = want;
+    pr.valid = true; pr.set = which; pr.own_rows = sh->own_rows;
+    sh->next_set = which ^ 1;
+    return W2V_OK;
+}
+
 void join_output_sort(w2v_shard* sh, hipStream_t st) {
     if (sh->overlap && sh->side) (void)hipStreamWaitEvent(st, sh->ev_join, 0);
 }
@@ -370,6 +404,11 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
         if (fused && p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
         launch_useg(a, st);
+    }
+    if (ws_owner->deferred.valid) {
+        const Prepared want = ws_owner->deferred;
+        ws_owner->deferred.valid = false;
+        (void)run_prefetch_chain(ws_owner, want, st);
     }
     if (loss_out) {
         if (two) {
@@ -787,33 +826,14 @@ extern "C" int w2v_prefetch_minibatch(w2v_shard* sh, const uint32_t* in_idx, con
     hipStream_t st = (hipStream_t)stream;
     rc = ensure_side_stream(sh);
     if (rc) return rc;
-    const int which = sh->next_set;
-    IndexSet& x = sh->sets[which];
-    sh->prep[which].valid = false;
-    const uint32_t M = n * (k + 1);
-    rc = ensure_set(sh, x, n, M);
-    if (rc) return rc;
-    HIP_TRY(hipEventRecord(sh->ev_pfork, st));
-    HIP_TRY(hipStreamWaitEvent(sh->side, sh->ev_pfork, 0));
-    hipStream_t side = sh->side;
-    const uint32_t bits = key_bits(sh->V);
-    {
-        Phase ph(sh, W2V_PH_NEG, side);
-        launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, n, k, seed, x.keys, sh->err, side);
-    }
-    {
-        Phase ph(sh, W2V_PH_SORT, side);
-        launch_sort_pairs(x.keys, x.wk0, x.wv0, x.wk1, x.wv1, M, bits, x.sort_tmp, &x.skw, &x.sidx, side);
-        if (sh->own_rows) launch_mark_alone(x.skw, x.sidx, M, x.keys, side);
-        launch_check_inputs(in_idx, n, sh->V, x.in_safe, sh->err, side);
-        launch_sort_pairs(x.in_safe, x.uk0, x.uv0, x.uk1, x.uv1, n, bits, x.sort_tmp_u, &x.sku, &x.perm, side);
-    }
-    HIP_TRY(hipEventRecord(x.ready, side));
-    HIP_TRY(hipGetLastError());
-    Prepared& pr = sh->prep[which];
-    pr.valid = true; pr.set = which; pr.own_rows = sh->own_rows;
-    pr.in_idx = in_idx; pr.out_idx = out_idx; pr.n = n; pr.k = k; pr.seed = seed;
-    sh->next_set = which ^ 1;
+    Prepared want;
+    want.in_idx = in_idx; want.out_idx = out_idx; want.n = n; want.k = k; want.seed = seed;
+    // Queued by the next call that updates this shard, right behind its input-side kernel: the
+    // look-ahead work then runs beside the (shorter) output-side kernel and the write-backs.  Run
+    // beside the input-side kernel instead it costs that kernel as much as it saves.
+    (void)st;
+    sh->deferred = want;
+    sh->deferred.valid = true;
     return W2V_OK;
 }
 
