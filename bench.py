@@ -229,17 +229,22 @@ def run_cbow(args, torch, w2v, workloads):
     m = ctx_total / K
     neg = sh.negatives(last[2], wl.k, w2v.minibatch_seed(wl.seed, Wm + K - 1))
     du = int(torch.unique(last[1]).numel())
-    dw = int(torch.unique(torch.cat([last[2], neg.reshape(-1)])).numel())
+    _, c = torch.unique(torch.cat([last[2], neg.reshape(-1)]), return_counts=True)
+    dw, single = int(c.numel()), int((c == 1).sum().item())    # single: output rows named by one slot
+    if os.environ.get("W2V_NO_OWN_ROWS", "0") not in ("", "0"):
+        single = 0
     M = n * T
     # algorithmic bytes per launch (= per minibatch):
     #   dot   (hidden vectors)      : m input rows read + n rows written + 4 B per entry
-    #   uside (per-example pass)    : T output rows + the hidden row per example, one row written
+    #   uside (per-example pass)    : T output rows + the hidden row per example, one row written,
+    #                                 + one row written per output row that a single slot names
     #   wside (output-side update)  : one hidden row per contribution + 12 B + RMW of distinct rows
+    #                                 (without the slots and rows the per-example pass has taken over)
     #   apply (input-side update)   : one summed row per context entry + 12 B + RMW of distinct rows
     algo = {
         "dot": (m + n) * R + 4 * m,
-        "uside": n * (T + 2) * R + 8 * M,
-        "wside": M * R + 12 * M + 2 * dw * R,
+        "uside": n * (T + 2) * R + 8 * M + single * R,
+        "wside": (M - single) * R + 12 * M + 2 * (dw - single) * R,
         "apply": m * R + 12 * m + 2 * du * R,
     }
     per_phase = {name: {"ms_per_launch": ms / cnt, "launches": cnt}
@@ -265,7 +270,8 @@ def run_cbow(args, torch, w2v, workloads):
                    "examples_per_minibatch": n, "context_words_per_minibatch": m, "k": wl.k,
                    "zipf_s": wl.zipf_s, "window": wl.window, "subsample_t": wl.subsample_t,
                    "path": "make_cbow_examples+cbow_train_minibatch",
-                   "distinct_input_rows": du, "distinct_output_rows": dw},
+                   "distinct_input_rows": du, "distinct_output_rows": dw,
+                   "output_rows_named_once": single},
         "context_words_per_s": ctx_total / dt,
         "roofline": {"bound": "hbm", "kernel": "cbow_hidden_kernel" if dom == "dot" else
                      KERNEL_OF_PHASE.get(dom, dom), "phase": dom, "achieved": achieved,

@@ -845,6 +845,7 @@ namespace {
 // Scratch of one bag-of-words minibatch: n examples, M = n(k+1) dot slots, m context entries.
 struct CbowPlan {
     uint32_t n, T, M, m;
+    bool own_rows;                                   // fused step: rows named once go to the per-example pass
     uint32_t* keys;                                  // [M] center word + negatives per example
     uint32_t* ctx_safe; uint32_t* ex_of; float* weight;   // [m]
     uint32_t* iota;                                  // [n] 0, 1, 2, ...
@@ -931,12 +932,16 @@ int queue_cbow_indices(w2v_shard* sh, CbowPlan& p, const uint32_t* ctx_off, cons
         Phase ph(sh, W2V_PH_NEG, wst);
         launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, p.n, k, seed, p.keys, sh->err, wst);
     }
-    if (two) HIP_TRY(hipEventRecord(sh->ev_keys, wst));
+    if (two && !p.own_rows) HIP_TRY(hipEventRecord(sh->ev_keys, wst));
     if (!sorts) return W2V_OK;
     {
         Phase ph(sh, W2V_PH_SORT, wst);
         const uint32_t bits = key_bits(sh->V);
         launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp_w, skw, sidx, wst);
+        if (p.own_rows) {           // the per-example pass needs the marks: "keys ready" moves here
+            launch_mark_alone(*skw, *sidx, p.M, p.keys, wst);
+            if (two) HIP_TRY(hipEventRecord(sh->ev_keys, wst));
+        }
         launch_sort_pairs(p.ctx_safe, p.ck0, p.cv0, p.ck1, p.cv1, p.m, bits, p.sort_tmp_c, skc, cidx, wst);
     }
     if (two) HIP_TRY(hipEventRecord(sh->ev_join, wst));
@@ -971,6 +976,7 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
         a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
         a.dots_out = nullptr; a.delta = p.E; a.dkey = p.dkey;
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
+        if (fused && p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }   // source: the hidden vector
         launch_useg(a, st);
     }
     join_output_sort(owner, st);
@@ -980,6 +986,7 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
         w.U = p.H; w.W = sh->W; w.g = sh->g; w.skey = skw; w.sidx = sidx; w.M = p.M; w.T = p.T;
         w.in_idx = p.iota; w.coeffs = fused ? coeffs_out : coeffs_in; w.alpha = alpha;
         w.prows = p.pb_rows; w.pkeys = p.pb_keys;
+        w.skip_alone = fused && p.own_rows;
         launch_wseg(w, st);
         run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st);
     }
@@ -1085,6 +1092,7 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
     rc = ensure_ws(s0, sz.bytes);
     if (rc) return rc;
     CbowPlan p = make_cbow_plan(s0->ws, n, k, m, stride_max, fused ? 0 : S, true, true);
+    p.own_rows = fused && s0->own_rows;
     uint32_t *skw, *sidx, *skc, *cidx;
     rc = queue_cbow_indices(s0, p, ctx_off, ctx_idx, out_idx, k, seed, true, &skw, &sidx, &skc, &cidx, st);
     if (rc) return rc;
