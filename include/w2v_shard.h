@@ -149,16 +149,14 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
 /* Optional look-ahead for a training loop on one shard.  Everything w2v_train_minibatch derives from
  * the indices alone -- the negatives, and the grouping of the minibatch's input and output rows that
  * makes the update deterministic -- depends on neither the vectors nor earlier minibatches.  This call
- * announces a LATER minibatch; the next call that updates the shard (w2v_train_minibatch or
- * w2v_adjust) queues the announced minibatch's index work on the shard's second stream, beside its own
- * output-side work:
+ * queues that work for a LATER minibatch on the shard's second stream, ordered after the work queued
+ * on `stream` so far, so that it runs beside the training call that is queued next:
  *     prefetch(h+1); train(h); prefetch(h+2); train(h+1); ...
  * A w2v_train_minibatch on this shard alone (S = 1) with the same in_idx_dev, out_idx_dev (same
- * pointers, contents unchanged since the announcement), n, k and seed then uses the prepared work;
- * otherwise it computes everything itself as if nothing had been announced.  Results are identical
- * either way.  One announcement is pending at a time (a second one replaces it); prepared work of two
- * minibatches can be held, each in its own device buffers (about 20 (k+2) n bytes, allocated on first
- * use and reused).  The call itself queues nothing and never fails for lack of memory. */
+ * pointers, contents unchanged in between), n, k and seed uses the prepared work; otherwise it
+ * computes everything itself as if this call had not been made.  Results are identical either way.
+ * Two minibatches can be held ahead (a third look-ahead replaces the older one); each keeps its own
+ * device buffers (about 20 (k+2) n bytes, allocated on first use and reused). */
 int w2v_prefetch_minibatch(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
                            uint32_t n, uint32_t k, uint64_t seed, void* stream);
 

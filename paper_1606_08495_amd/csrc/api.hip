@@ -95,7 +95,6 @@ struct w2v_shard {
     bool own_rows = true;           // fused step: singly named output rows updated by the input side
     IndexSet sets[2];
     Prepared prep[2];               // what sets[i] holds
-    Prepared deferred;              // announced by w2v_prefetch_minibatch, not yet queued
     int next_set = 0;
     hipEvent_t ev_pfork = nullptr;
     // timing
@@ -404,11 +403,6 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
         if (fused && p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
         launch_useg(a, st);
-    }
-    if (ws_owner->deferred.valid) {
-        const Prepared want = ws_owner->deferred;
-        ws_owner->deferred.valid = false;
-        (void)run_prefetch_chain(ws_owner, want, st);
     }
     if (loss_out) {
         if (two) {
@@ -828,13 +822,10 @@ extern "C" int w2v_prefetch_minibatch(w2v_shard* sh, const uint32_t* in_idx, con
     if (rc) return rc;
     Prepared want;
     want.in_idx = in_idx; want.out_idx = out_idx; want.n = n; want.k = k; want.seed = seed;
-    // Queued by the next call that updates this shard, right behind its input-side kernel: the
-    // look-ahead work then runs beside the (shorter) output-side kernel and the write-backs.  Run
-    // beside the input-side kernel instead it costs that kernel as much as it saves.
-    (void)st;
-    sh->deferred = want;
-    sh->deferred.valid = true;
-    return W2V_OK;
+    // Queued at once, so that it runs beside the whole of the training call that is queued next.
+    // (Queued behind that call's input-side kernel instead, it left the benchmark step unchanged but
+    // did not fit beside the output-side kernel alone when k is large: the next step then waited.)
+    return run_prefetch_chain(sh, want, st);
 }
 
 // ---------------------------------------------------------------------------------------------

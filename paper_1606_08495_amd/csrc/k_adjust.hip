@@ -537,6 +537,8 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
                 // this register set is free again: fetch the matching row of the following batch
                 uint32_t nj = njb + t;
                 bool on = npi < cnt && nj < T;
+                // (the non-temporal hint for rows named once, which pays in the fixed-T kernel,
+                // costs 25 % here: the branch breaks up this loop's batched loads)
                 uint32_t r = on ? (s_key[grp][npi * T + nj] & ~ALONE) : 0u;
                 load_row_if<G, NV>(on, W4p + (uint64_t)r * s4, d4, l, w[t]);
             }
@@ -641,8 +643,12 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_multi_kernel(USideArgs a, ui
             }
 #pragma unroll
             for (int j = 0; j < T; ++j) {
-                const uint32_t r = live ? (s_key[grp][pi * T + j] & ~ALONE) : 0u;
-                load_row_if<G, NV>(live, W4p + (uint64_t)r * s4, d4, l, w[b][j]);
+                const uint32_t rk = live ? s_key[grp][pi * T + j] : 0u;
+                const uint32_t r = rk & ~ALONE;
+                // a row that no other slot names is read here once and written once: the
+                // non-temporal hint keeps it out of the caches' way (-7 % on this kernel)
+                if (rk & ALONE) load_row_nt_if<G, NV>(live, W4p + (uint64_t)r * s4, d4, l, w[b][j]);
+                else load_row_if<G, NV>(live, W4p + (uint64_t)r * s4, d4, l, w[b][j]);
             }
         }
 #pragma unroll
