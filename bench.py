@@ -5,7 +5,10 @@ One step = one pass of the whole hot path over one minibatch: pair formation fro
 (amortised over the minibatches a token block yields), negatives, dot products, coefficients and
 the deterministic adjust -- i.e. w2v_make_pairs + w2v_train_minibatch (workload "full300", the
 10M-word d=300 configuration the bandwidth target is stated on), or w2v_dotprod + w2v_adjust with
-harness coefficients (workload "slice60", one of five column shards).
+harness coefficients (workload "slice60", one of five column shards).  In the text workloads the
+next minibatch is announced to the shard (w2v_prefetch_minibatch) before the current one is
+trained, so its index work runs beside the current step; every minibatch's index work is still done
+exactly once inside the timed region (--no-prefetch turns the announcement off).
 
 Prints one JSON line: pairs/s (k negatives included), ms per step, the roofline entry of the
 dominant kernel (algorithmic bytes / its measured HIP-event time, against 8 TB/s) and the CPU oracle
