@@ -546,8 +546,13 @@ def main():
 
         def step(h):
             seed = w2v.minibatch_seed(wl.seed, h)
+            if not args.no_prefetch:          # the next minibatch's index work, beside this one's rows
+                sh.prefetch_minibatch(a, b, wl.k, w2v.minibatch_seed(wl.seed, h + 1))
             sh.dotprod(a, b, wl.k, seed, out=dots)
             sh.adjust(a, b, wl.k, seed, gd, wl.alpha)
+
+        if not args.no_prefetch:
+            sh.prefetch_minibatch(a, b, wl.k, w2v.minibatch_seed(wl.seed, 0))
 
         for h in range(Wm):
             step(h)
@@ -623,7 +628,7 @@ def main():
                    "path": "make_pairs+train_minibatch" if fused else "dotprod+adjust",
                    "distinct_input_rows": du, "distinct_output_rows": dw,
                    "output_rows_named_once": single,
-                   "prefetch": bool(fused and not args.no_prefetch)},
+                   "prefetch": not args.no_prefetch},
         "roofline": {"bound": "hbm", "kernel": KERNEL_OF_PHASE.get(dom, dom), "phase": dom,
                      "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

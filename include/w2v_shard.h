@@ -152,9 +152,13 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
  * queues that work for a LATER minibatch on the shard's second stream, ordered after the work queued
  * on `stream` so far, so that it runs beside the training call that is queued next:
  *     prefetch(h+1); train(h); prefetch(h+2); train(h+1); ...
- * A w2v_train_minibatch on this shard alone (S = 1) with the same in_idx_dev, out_idx_dev (same
- * pointers, contents unchanged in between), n, k and seed uses the prepared work; otherwise it
- * computes everything itself as if this call had not been made.  Results are identical either way.
+ * or, on a column shard that serves the two calls of Section 5.1,
+ *     prefetch(h+1); dotprod(h); adjust(h); prefetch(h+2); dotprod(h+1); adjust(h+1); ...
+ * A w2v_train_minibatch whose first shard is this one, a w2v_dotprod or a w2v_adjust on this shard
+ * with the same in_idx_dev, out_idx_dev (same pointers, contents unchanged in between), n, k and
+ * seed uses the prepared work (w2v_dotprod leaves it in place for the w2v_adjust of the same
+ * minibatch; an update consumes it); otherwise the call computes everything itself as if this call
+ * had not been made.  Results are identical either way.
  * Two minibatches can be held ahead (a third look-ahead replaces the older one); each keeps its own
  * device buffers (about 20 (k+2) n bytes, allocated on first use and reused). */
 int w2v_prefetch_minibatch(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,

@@ -378,6 +378,18 @@ int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
     return W2V_OK;
 }
 
+// The set that w2v_prefetch_minibatch filled for exactly this minibatch, or -1.
+int find_prepared(const w2v_shard* sh, const uint32_t* in_idx, const uint32_t* out_idx, uint32_t n,
+                  uint32_t k, uint64_t seed) {
+    for (int i = 0; i < 2; ++i) {
+        const Prepared& pr = sh->prep[i];
+        if (pr.valid && pr.in_idx == in_idx && pr.out_idx == out_idx && pr.n == n && pr.k == k &&
+            pr.seed == seed)
+            return i;
+    }
+    return -1;
+}
+
 void join_output_sort(w2v_shard* sh, hipStream_t st) {
     if (sh->overlap && sh->side) (void)hipStreamWaitEvent(st, sh->ev_join, 0);
 }
@@ -401,7 +413,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
         a.dots_out = nullptr; a.delta = p.delta; a.dkey = p.dkey;
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
-        if (fused && p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
+        if (p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
         launch_useg(a, st);
     }
     if (loss_out) {
@@ -419,7 +431,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         w.U = sh->U; w.W = sh->W; w.g = sh->g; w.skey = skw; w.sidx = sidx; w.M = p.M; w.T = p.T;
         w.in_idx = p.in_safe; w.coeffs = fused ? coeffs_out : coeffs_in; w.alpha = alpha;
         w.prows = p.pb_rows; w.pkeys = p.pb_keys;
-        w.skip_alone = fused && p.own_rows;
+        w.skip_alone = p.own_rows;
         launch_wseg(w, st);
     }
     if (two) {
@@ -675,7 +687,12 @@ extern "C" int w2v_dotprod(w2v_shard* sh, const uint32_t* in_idx, const uint32_t
     rc = ensure_ws(sh, sz.bytes);
     if (rc) return rc;
     Plan p = make_plan(sh->ws, n, k, sh->g.stride4, 0, false, false);
-    {
+    const int ahead = find_prepared(sh, in_idx, out_idx, n, k, seed);
+    if (ahead >= 0) {                 // announced: the checked words and the keys exist already; the
+        IndexSet& x = sh->sets[ahead];                   // set stays valid for the adjust call
+        HIP_TRY(hipStreamWaitEvent(st, x.ready, 0));
+        p.keys = x.keys; p.in_safe = x.in_safe;
+    } else {
         Phase ph(sh, W2V_PH_NEG, st);
         launch_check_inputs(in_idx, n, sh->V, p.in_safe, sh->err, st);
         launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, n, k, seed, p.keys, sh->err, st);
@@ -729,8 +746,19 @@ extern "C" int w2v_adjust(w2v_shard* sh, const uint32_t* in_idx, const uint32_t*
     if (rc) return rc;
     Plan p = make_plan(sh->ws, n, k, sh->g.stride4, 0, true, false);
     uint32_t *sku, *perm, *skw, *sidx;
-    rc = queue_keys_and_sorts(sh, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);
-    if (rc) return rc;
+    const int ahead = find_prepared(sh, in_idx, out_idx, n, k, seed);
+    if (ahead >= 0) {
+        IndexSet& x = sh->sets[ahead];
+        sh->prep[ahead].valid = false;                   // a set serves one update
+        HIP_TRY(hipStreamWaitEvent(st, x.ready, 0));
+        // (the keys may carry the marks of rows named once; the two-call form does not use them:
+        // its input-side kernel would have to read the input rows for that, which costs more)
+        p.keys = x.keys; p.in_safe = x.in_safe;
+        sku = x.sku; perm = x.perm; skw = x.skw; sidx = x.sidx;
+    } else {
+        rc = queue_keys_and_sorts(sh, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);
+        if (rc) return rc;
+    }
     queue_adjust(sh, sh, p, sku, perm, skw, sidx, coeffs, nullptr, false, alpha, nullptr, st);
     HIP_TRY(hipGetLastError());
     return W2V_OK;
@@ -770,18 +798,13 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
     if (rc) return rc;
     Plan p = make_plan(s0->ws, n, k, stride_max, fused ? 0 : S, true, true, own);
     uint32_t *sku, *perm, *skw, *sidx;
-    int ahead = -1;                                      // a set computed by w2v_prefetch_minibatch?
-    for (int i = 0; i < 2 && fused; ++i) {
-        const Prepared& pr = s0->prep[i];
-        if (pr.valid && pr.in_idx == in_idx && pr.out_idx == out_idx && pr.n == n && pr.k == k &&
-            pr.seed == seed && pr.own_rows == p.own_rows)
-            ahead = i;
-    }
+    // a set computed by w2v_prefetch_minibatch on shard 0 (every shard holds the same noise table)
+    const int ahead = find_prepared(s0, in_idx, out_idx, n, k, seed);
     if (ahead >= 0) {
         IndexSet& x = s0->sets[ahead];
-        s0->prep[ahead].valid = false;                   // a set is used once
+        s0->prep[ahead].valid = false;                   // a set serves one update
         HIP_TRY(hipStreamWaitEvent(st, x.ready, 0));
-        p.keys = x.keys; p.in_safe = x.in_safe;
+        p.keys = x.keys; p.in_safe = x.in_safe; p.own_rows = fused && s0->prep[ahead].own_rows;
         sku = x.sku; perm = x.perm; skw = x.skw; sidx = x.sidx;
     } else {
         rc = queue_keys_and_sorts(s0, p, in_idx, out_idx, k, seed, &sku, &perm, &skw, &sidx, st);

@@ -421,8 +421,9 @@ __device__ __forceinline__ float sigmoid_of_minus(float x) { return 1.0f / (1.0f
 constexpr int USEG_MAXP = 16;     // pairs per chunk, at most
 constexpr int USEG_MAXE = 136;    // entries (pairs x slots) per chunk, at most
 
-template <int G, int NV, int TB, bool FUSED>
+template <int G, int NV, int TB, bool FUSED, bool OWN>
 __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t CP) {
+    constexpr bool NEED_U = FUSED || OWN;      // the pair's input row: for the dots, for own rows
     constexpr int GROUPS = ADJ_THREADS / G;
     // The chunk's indices are staged in LDS first (two dependent gathers for the whole chunk), so
     // that the row loads of the main loop depend on nothing but LDS reads.
@@ -477,14 +478,14 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
         uint32_t r = on ? (s_key[grp][t] & ~ALONE) : 0u;
         load_row_if<G, NV>(on, W4p + (uint64_t)r * s4, d4, l, w[t]);
     }
-    if (FUSED) load_row<G, NV>(U4p + (uint64_t)key * s4, d4, l, u);
+    if (NEED_U) load_row<G, NV>(U4p + (uint64_t)key * s4, d4, l, u);
 
     for (uint32_t pi = 0; pi < cnt; ++pi) {
         const uint32_t ps = ps0 + pi;
         const uint32_t p = s_pair[grp][pi];
         const uint32_t next = s_skey[grp][pi + 2];
         if (l == 0) a.dkey[ps] = KEY_NONE;
-        if (FUSED) {                                   // the next pair's input row, ahead of need
+        if (NEED_U) {                                  // the next pair's input row, ahead of need
             bool more = pi + 1 < cnt;
             load_row_if<G, NV>(more, U4p + (uint64_t)(more ? next : 0u) * s4, d4, l, un);
         }
@@ -521,8 +522,8 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
                     axpy<NV>(gco[t], w[t], acc);
                     // an output row that no other slot names gets its whole update here (see the
                     // fixed-T kernel below)
-                    const uint32_t rr = (FUSED && a.W_update) ? s_key[grp][pi * T + jb + t] : 0u;
-                    if (FUSED && (rr & ALONE)) {
+                    const uint32_t rr = OWN ? s_key[grp][pi * T + jb + t] : 0u;
+                    if (OWN && (rr & ALONE)) {
                         float4 out[NV];
 #pragma unroll
                         for (int v = 0; v < NV; ++v) {
@@ -554,7 +555,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
             clear<NV>(acc);
             run_start = ps + 1;
         }
-        if (FUSED) {
+        if (NEED_U) {
 #pragma unroll
             for (int v = 0; v < NV; ++v) u[v] = un[v];
         }
@@ -584,8 +585,9 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
 // latency-bound (rows in flight per SIMD x row size / memory latency), and registers spent on
 // rows in flight buy more than registers spent on extra resident waves.
 // ---------------------------------------------------------------------------------------------
-template <int G, int NV, int T, int PB, bool FUSED>
+template <int G, int NV, int T, int PB, bool FUSED, bool OWN>
 __global__ __launch_bounds__(ADJ_THREADS) void useg_multi_kernel(USideArgs a, uint32_t CP) {
+    constexpr bool NEED_U = FUSED || OWN;
     constexpr int GROUPS = ADJ_THREADS / G;
     constexpr int MAXP = 16, MAXE = MAXP * T;
     __shared__ uint32_t s_key[GROUPS][MAXE];
@@ -637,7 +639,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_multi_kernel(USideArgs a, ui
         for (int b = 0; b < PB; ++b) {
             const uint32_t pi = pb + b;
             const bool live = pi < cnt;
-            if (FUSED) {
+            if (NEED_U) {
                 const uint32_t k_in = live ? s_skey[grp][pi + 1] : 0u;
                 load_row_if<G, NV>(live, U4p + (uint64_t)k_in * s4, d4, l, u[b]);
             }
@@ -675,30 +677,30 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_multi_kernel(USideArgs a, ui
                             if (a.dots_out) a.dots_out[p * T + j] = f;
                         }
                     }
-                    // An output row that no other slot names gets its whole update here, from the
-                    // registers, with the same two roundings as the output-side kernel
-                    // (fl(g u), then one fma with alpha); that kernel never sees the slot.
-                    if (a.W_update) {
-#pragma unroll
-                        for (int j = 0; j < T; ++j) {
-                            const uint32_t r = s_key[grp][pi * T + j];
-                            if (r & ALONE) {
-                                float4 out[NV];
-#pragma unroll
-                                for (int v = 0; v < NV; ++v) {
-                                    out[v].x = fmaf(a.alpha, fmaf(gco[j], u[b][v].x, 0.f), w[b][j][v].x);
-                                    out[v].y = fmaf(a.alpha, fmaf(gco[j], u[b][v].y, 0.f), w[b][j][v].y);
-                                    out[v].z = fmaf(a.alpha, fmaf(gco[j], u[b][v].z, 0.f), w[b][j][v].z);
-                                    out[v].w = fmaf(a.alpha, fmaf(gco[j], u[b][v].w, 0.f), w[b][j][v].w);
-                                }
-                                store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(r & ~ALONE) * s4, d4,
-                                                    l, out);
-                            }
-                        }
-                    }
                 } else {
 #pragma unroll
                     for (int j = 0; j < T; ++j) gco[j] = s_cf[grp][pi * T + j];
+                }
+                // An output row that no other slot names gets its whole update here, from the
+                // registers, with the same two roundings as the output-side kernel
+                // (fl(g u), then one fma with alpha); that kernel never sees the slot.
+                if (OWN) {
+#pragma unroll
+                    for (int j = 0; j < T; ++j) {
+                        const uint32_t r = s_key[grp][pi * T + j];
+                        if (r & ALONE) {
+                            float4 out[NV];
+#pragma unroll
+                            for (int v = 0; v < NV; ++v) {
+                                out[v].x = fmaf(a.alpha, fmaf(gco[j], u[b][v].x, 0.f), w[b][j][v].x);
+                                out[v].y = fmaf(a.alpha, fmaf(gco[j], u[b][v].y, 0.f), w[b][j][v].y);
+                                out[v].z = fmaf(a.alpha, fmaf(gco[j], u[b][v].z, 0.f), w[b][j][v].z);
+                                out[v].w = fmaf(a.alpha, fmaf(gco[j], u[b][v].w, 0.f), w[b][j][v].w);
+                            }
+                            store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(r & ~ALONE) * s4, d4,
+                                                l, out);
+                        }
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < T; ++j) axpy<NV>(gco[j], w[b][j], acc);
@@ -741,10 +743,13 @@ constexpr int USEG_PB = 1;     // pairs per batch of the fixed-T kernel (1 measu
 
 template <int G, int NV, int T>
 static void launch_useg_fixed(const USideArgs& a, uint32_t CP, dim3 grid, dim3 block, hipStream_t st) {
-    if (a.fused)
-        hipLaunchKernelGGL((useg_multi_kernel<G, NV, T, USEG_PB, true>), grid, block, 0, st, a, CP);
+    const bool own = a.W_update != nullptr;      // (only the fused form takes rows over)
+    if (a.fused && own)
+        hipLaunchKernelGGL((useg_multi_kernel<G, NV, T, USEG_PB, true, true>), grid, block, 0, st, a, CP);
+    else if (a.fused)
+        hipLaunchKernelGGL((useg_multi_kernel<G, NV, T, USEG_PB, true, false>), grid, block, 0, st, a, CP);
     else
-        hipLaunchKernelGGL((useg_multi_kernel<G, NV, T, USEG_PB, false>), grid, block, 0, st, a, CP);
+        hipLaunchKernelGGL((useg_multi_kernel<G, NV, T, USEG_PB, false, false>), grid, block, 0, st, a, CP);
 }
 
 template <int G, int NV>
@@ -756,10 +761,13 @@ static void launch_useg_shape(const USideArgs& a, hipStream_t st) {
         if (a.T == 6) return launch_useg_fixed<G, NV, 6>(a, CP, grid, block, st);
     }
     constexpr int TB = NV == 1 ? 9 : (NV == 2 ? 6 : 4);     // rows requested per batch
-    if (a.fused)
-        hipLaunchKernelGGL((useg_kernel<G, NV, TB, true>), grid, block, 0, st, a, CP);
+    const bool own = a.W_update != nullptr;      // (only the fused form takes rows over)
+    if (a.fused && own)
+        hipLaunchKernelGGL((useg_kernel<G, NV, TB, true, true>), grid, block, 0, st, a, CP);
+    else if (a.fused)
+        hipLaunchKernelGGL((useg_kernel<G, NV, TB, true, false>), grid, block, 0, st, a, CP);
     else
-        hipLaunchKernelGGL((useg_kernel<G, NV, TB, false>), grid, block, 0, st, a, CP);
+        hipLaunchKernelGGL((useg_kernel<G, NV, TB, false, false>), grid, block, 0, st, a, CP);
 }
 
 void launch_useg(const USideArgs& a, hipStream_t st) {

@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256) void dots_kernel(const float4* __restrict__ U,
         for (int t = 0; t < TB; ++t) {
             uint32_t j = jb + t;
             bool on = j < T;
-            uint32_t r = on ? keys[p * T + j] : 0u;
+            uint32_t r = on ? (keys[p * T + j] & ~KEY_ALONE) : 0u;   // (a prepared set may carry the mark)
             load_row_if<G, NV>(on, W + (uint64_t)r * g.stride4, g.d4, l, w[t]);
         }
         float s[TB];

@@ -639,3 +639,73 @@ def test_prefetch_gives_the_same_bits_and_a_mismatch_is_harmless():
     for sh in (plain, ahead, mixed):
         sh.status()
         sh.destroy()
+
+
+@pytest.mark.parametrize("V,d,k,d_total,col", [(3000, 60, 5, 300, 120), (2500, 300, 5, 300, 0),
+                                               (1500, 100, 10, 100, 0), (40, 64, 5, 64, 0),
+                                               (5000, 1000, 2, 1000, 0)])
+def test_announced_dotprod_and_adjust_give_the_same_bits(V, d, k, d_total, col):
+    # a column shard serving the two calls, with each minibatch announced one step ahead: dots and
+    # vectors must equal, bit for bit, those of a shard that was told nothing -- and match the oracle
+    say("announced two-call form", V, d, k)
+    n, steps = 4099, 4
+    rng = np.random.default_rng(V + k)
+    counts = zipf_counts(V)
+    cdf = workloads.zipf_cdf(V, 1.0)
+    ins = [dev(workloads.zipf_draw(cdf, n, rng)) for _ in range(steps + 1)]
+    outs = [dev(workloads.zipf_draw(cdf, n, rng)) for _ in range(steps + 1)]
+    seeds = [w2v.minibatch_seed(9, h) for h in range(steps + 1)]
+    gs = [torch.from_numpy(workloads.uniform_coeffs(n, k + 1, 100 + h)).cuda() for h in range(steps)]
+    plain = make_shard(V, d, 5, counts, d_total=d_total, col_begin=col)
+    ahead = make_shard(V, d, 5, counts, d_total=d_total, col_begin=col)
+    U, W = oracle_state(V, d, 5, d_total=d_total, col_begin=col)
+    th, al = oracle.build_alias(counts)
+    ahead.prefetch_minibatch(ins[0], outs[0], k, seeds[0])
+    for h in range(steps):
+        ahead.prefetch_minibatch(ins[h + 1], outs[h + 1], k, seeds[h + 1])
+        da = ahead.dotprod(ins[h], outs[h], k, seeds[h]).cpu().numpy()
+        dp = plain.dotprod(ins[h], outs[h], k, seeds[h]).cpu().numpy()
+        assert np.array_equal(da, dp)
+        ahead.adjust(ins[h], outs[h], k, seeds[h], gs[h], 0.05)
+        plain.adjust(ins[h], outs[h], k, seeds[h], gs[h], 0.05)
+        oracle.adjust(U, W, w2v.index_to_numpy(ins[h]), w2v.index_to_numpy(outs[h]), k, seeds[h], th,
+                      al, gs[h].cpu().numpy(), 0.05)
+    for which, ref in ((0, U), (1, W)):
+        assert np.array_equal(all_rows(ahead, which), all_rows(plain, which))
+        assert vec_error(all_rows(ahead, which), ref) <= steps * TOL1
+    # an adjust without the dotprod before it, and a second adjust of the same minibatch (the set
+    # is spent: it recomputes), are the same updates as on the shard that was told nothing
+    ahead.adjust(ins[steps], outs[steps], k, seeds[steps], gs[0], 0.05)
+    ahead.adjust(ins[steps], outs[steps], k, seeds[steps], gs[0], 0.05)
+    plain.adjust(ins[steps], outs[steps], k, seeds[steps], gs[0], 0.05)
+    plain.adjust(ins[steps], outs[steps], k, seeds[steps], gs[0], 0.05)
+    for which in (0, 1):
+        assert np.array_equal(all_rows(ahead, which), all_rows(plain, which))
+    for sh in (plain, ahead):
+        sh.status()
+        sh.destroy()
+
+
+def test_announced_step_over_column_shards_gives_the_same_bits():
+    rng = np.random.default_rng(58)
+    V, n, k, steps = 1200, 3000, 5, 3
+    counts = zipf_counts(V)
+    cuts = [(0, 60), (60, 100), (160, 140)]
+    told = [make_shard(V, w, 3, counts, d_total=300, col_begin=b) for b, w in cuts]
+    plain = [make_shard(V, w, 3, counts, d_total=300, col_begin=b) for b, w in cuts]
+    ins = [dev(rng.integers(0, V, n)) for _ in range(steps + 1)]
+    outs = [dev(rng.integers(0, V, n)) for _ in range(steps + 1)]
+    la, lb = (torch.zeros(1, dtype=torch.float64, device="cuda") for _ in range(2))
+    for h in range(steps):
+        told[0].prefetch_minibatch(ins[h + 1], outs[h + 1], k, 40 + h + 1)
+        if h == 0:
+            told[0].prefetch_minibatch(ins[0], outs[0], k, 40)
+        w2v.train_minibatch(told, ins[h], outs[h], k, 40 + h, 0.05, loss=la)
+        w2v.train_minibatch(plain, ins[h], outs[h], k, 40 + h, 0.05, loss=lb)
+        assert la.item() == lb.item()
+    for a, b in zip(told, plain):
+        for which in (0, 1):
+            assert np.array_equal(all_rows(a, which), all_rows(b, which))
+    for s in told + plain:
+        s.status()
+        s.destroy()
