@@ -158,7 +158,8 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
  * with the same in_idx_dev, out_idx_dev (same pointers, contents unchanged in between), n, k and
  * seed uses the prepared work (w2v_dotprod leaves it in place for the w2v_adjust of the same
  * minibatch; an update consumes it); otherwise the call computes everything itself as if this call
- * had not been made.  Results are identical either way.
+ * had not been made.  Results are identical either way.  w2v_shard_set_counts voids what was
+ * announced before it (the negatives came from the old table).
  * Two minibatches can be held ahead (a third look-ahead replaces the older one); each keeps its own
  * device buffers (about 20 (k+2) n bytes, allocated on first use and reused). */
 int w2v_prefetch_minibatch(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,

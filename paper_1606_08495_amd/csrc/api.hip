@@ -585,6 +585,7 @@ extern "C" int w2v_shard_set_counts(w2v_shard* sh, const uint64_t* counts, doubl
     HIP_TRY(hipMemcpy(sh->keep, keep.data(), sizeof(uint64_t) * (size_t)V, hipMemcpyHostToDevice));
     sh->has_tables = true;
     sh->table_tag = tag;
+    sh->prep[0].valid = sh->prep[1].valid = false;   // negatives drawn from the old table are void
     return W2V_OK;
 }
 

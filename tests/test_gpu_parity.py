@@ -709,3 +709,23 @@ def test_announced_step_over_column_shards_gives_the_same_bits():
     for s in told + plain:
         s.status()
         s.destroy()
+
+
+def test_new_counts_void_an_announced_minibatch():
+    # the announced negatives came from the old noise table: after w2v_shard_set_counts the step
+    # must draw them again
+    V, d, n, k = 900, 60, 2000, 5
+    rng = np.random.default_rng(4)
+    a, b = dev(rng.integers(0, V, n)), dev(rng.integers(0, V, n))
+    old, new = zipf_counts(V), zipf_counts(V)[::-1].copy()
+    told = make_shard(V, d, 2, old)
+    plain = make_shard(V, d, 2, new)
+    told.prefetch_minibatch(a, b, k, 11)
+    told.set_counts(new)
+    w2v.train_minibatch([told], a, b, k, 11, 0.05)
+    w2v.train_minibatch([plain], a, b, k, 11, 0.05)
+    for which in (0, 1):
+        assert np.array_equal(all_rows(told, which), all_rows(plain, which))
+    for sh in (told, plain):
+        sh.status()
+        sh.destroy()
