@@ -93,6 +93,8 @@ struct w2v_shard {
     hipEvent_t ev_coeffs = nullptr, ev_wdone = nullptr, ev_tails = nullptr;
     bool overlap = true;
     bool own_rows = true;           // fused step: singly named output rows updated by the input side
+    bool last_update_fused = true;  // what the last update on this shard was: an announced minibatch
+                                    // gets its rows-named-once marks only if the fused step is likely
     IndexSet sets[2];
     Prepared prep[2];               // what sets[i] holds
     int next_set = 0;
@@ -358,6 +360,7 @@ int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
     HIP_TRY(hipStreamWaitEvent(sh->side, sh->ev_pfork, 0));
     hipStream_t side = sh->side;
     const uint32_t bits = key_bits(sh->V);
+    const bool marks = sh->own_rows && sh->last_update_fused;
     {
         Phase ph(sh, W2V_PH_NEG, side);
         launch_dest_keys(NoiseTable{sh->bins, sh->V}, want.out_idx, n, k, want.seed, x.keys, sh->err, side);
@@ -365,7 +368,7 @@ int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
     {
         Phase ph(sh, W2V_PH_SORT, side);
         launch_sort_pairs(x.keys, x.wk0, x.wv0, x.wk1, x.wv1, M, bits, x.sort_tmp, &x.skw, &x.sidx, side);
-        if (sh->own_rows) launch_mark_alone(x.skw, x.sidx, M, x.keys, side);
+        if (marks) launch_mark_alone(x.skw, x.sidx, M, x.keys, side);
         launch_check_inputs(want.in_idx, n, sh->V, x.in_safe, sh->err, side);
         launch_sort_pairs(x.in_safe, x.uk0, x.uv0, x.uk1, x.uv1, n, bits, x.sort_tmp_u, &x.sku, &x.perm, side);
     }
@@ -373,7 +376,7 @@ int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
     HIP_TRY(hipGetLastError());
     Prepared& pr = sh->prep[which];
     pr = want;
-    pr.valid = true; pr.set = which; pr.own_rows = sh->own_rows;
+    pr.valid = true; pr.set = which; pr.own_rows = marks;
     sh->next_set = which ^ 1;
     return W2V_OK;
 }
@@ -747,6 +750,7 @@ extern "C" int w2v_adjust(w2v_shard* sh, const uint32_t* in_idx, const uint32_t*
     if (rc) return rc;
     Plan p = make_plan(sh->ws, n, k, sh->g.stride4, 0, true, false);
     uint32_t *sku, *perm, *skw, *sidx;
+    sh->last_update_fused = false;
     const int ahead = find_prepared(sh, in_idx, out_idx, n, k, seed);
     if (ahead >= 0) {
         IndexSet& x = sh->sets[ahead];
@@ -800,6 +804,7 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
     Plan p = make_plan(s0->ws, n, k, stride_max, fused ? 0 : S, true, true, own);
     uint32_t *sku, *perm, *skw, *sidx;
     // a set computed by w2v_prefetch_minibatch on shard 0 (every shard holds the same noise table)
+    s0->last_update_fused = fused;
     const int ahead = find_prepared(s0, in_idx, out_idx, n, k, seed);
     if (ahead >= 0) {
         IndexSet& x = s0->sets[ahead];
