@@ -38,13 +38,18 @@ def log(*a):
 class PairStream:
     """Feeds minibatches of n pairs cut from the pair stream of a token corpus (device side).  Pairs
     are formed block by block into one pair of buffers sized for the whole run and never moved, so
-    that the minibatch after the current one can be announced to the shard ahead of time."""
+    that the minibatch after the current one can be announced to the shard ahead of time.  Pair
+    formation runs on a stream of its own (it keeps its own scratch in the shard), so a block is
+    formed while the training calls queued before it are still running; the call returns the pair
+    count, i.e. waits for that stream only."""
 
-    def __init__(self, shard, wl, tokens, sent_off, block_tokens, torch, minibatches):
+    def __init__(self, shard, wl, tokens, sent_off, block_tokens, torch, minibatches, own_stream=True):
         self.torch = torch
         self.sh, self.wl = shard, wl
         self.tok = torch.from_numpy(tokens.view(np.int32)).cuda()
         self.off_host = sent_off.astype(np.int64)
+        self.off_dev = torch.from_numpy(self.off_host).cuda()
+        self.side = torch.cuda.Stream() if own_stream else torch.cuda.current_stream()
         self.block_tokens = block_tokens
         cap = (minibatches + 2) * wl.n_pairs + block_tokens * 2 * wl.window
         self.a = torch.empty(cap, dtype=torch.int32, device="cuda")
@@ -66,9 +71,10 @@ class PairStream:
         s1 = max(s1, s0 + 1)
         s1 = min(s1, off.size - 1)
         t1 = int(off[s1])
-        rel = torch.from_numpy(off[s0:s1 + 1] - t0).cuda()
-        cnt = self.sh.make_pairs(self.tok[t0:t1], rel, t0, self.epoch, self.wl.seed, self.wl.window,
-                                 self.a[self.have:], self.b[self.have:])
+        with torch.cuda.stream(self.side):
+            rel = self.off_dev[s0:s1 + 1] - t0
+            cnt = self.sh.make_pairs(self.tok[t0:t1], rel, t0, self.epoch, self.wl.seed,
+                                     self.wl.window, self.a[self.have:], self.b[self.have:])
         assert cnt <= self.a.numel() - self.have, "pair buffers too small for this run"
         self.have += cnt
         self.sent = s1
@@ -434,6 +440,8 @@ def main():
                     help="pairs the CPU oracle is timed on (default: about 10-30 s of one core)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loss", action="store_true", help="do not request the minibatch loss")
+    ap.add_argument("--pairs-on-main-stream", action="store_true",
+                    help="form the pairs on the training stream instead of a stream of their own")
     ap.add_argument("--no-prefetch", action="store_true",
                     help="do not announce the next minibatch to the shard (w2v_prefetch_minibatch)")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
@@ -493,7 +501,7 @@ def main():
             tokens, off = workloads.corpus(wl, n_tok, cdf=cdf)
         del cdf
         stream = PairStream(sh, wl, tokens, off, block_tokens=min(tokens.size, 1 << 21), torch=torch,
-                            minibatches=total_steps + 1)
+                            minibatches=total_steps + 1, own_stream=not args.pairs_on_main_stream)
         H = max(1, wl.corpus_tokens * 4 // wl.n_pairs)     # minibatches in the nominal corpus
 
         def step(h):

@@ -140,6 +140,9 @@ int w2v_train_minibatch(w2v_shard* const* shards_host, uint32_t S, const uint32_
  * survivors within b positions, centers in corpus order, contexts by increasing position.  All draws
  * are functions of (corpus_seed, token position, epoch).  Writes at most `capacity` pairs to
  * in_idx_dev/out_idx_dev and the full count to *n_pairs_host.  Synchronises `stream`.
+ * The formation calls keep scratch of their own in the shard and read only its subsample table:
+ * on a stream of their own they may run beside a training call on the same shard (one formation
+ * call at a time per shard).
  * Requires n_tokens * 2B < 2^32. */
 int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t* sent_off_dev,
                    uint32_t n_sent, uint32_t n_tokens, uint64_t token_base, uint32_t epoch,

@@ -86,6 +86,9 @@ struct w2v_shard {
     // scratch: one region, carved per call
     char* ws = nullptr;
     size_t ws_cap = 0;
+    // scratch of the pair formation, apart from the training calls' so that the two may overlap
+    char* pairs_ws = nullptr;
+    size_t pairs_ws_cap = 0;
     // second stream for work that only depends on the keys (the output-side sort), joined back
     // into the caller's stream by an event before its result is used
     hipStream_t side = nullptr;
@@ -120,24 +123,27 @@ struct Carver {
     }
 };
 
-int ensure_ws(w2v_shard* sh, size_t bytes) {
-    if (bytes <= sh->ws_cap) return W2V_OK;
-    if (sh->ws) { HIP_TRY(hipDeviceSynchronize()); HIP_TRY(hipFree(sh->ws)); sh->ws = nullptr; sh->ws_cap = 0; }
+// Grow a scratch region to at least `bytes` (it is never shrunk; growing waits for the device).
+int ensure_region(char*& region, size_t& cap, size_t bytes) {
+    if (bytes <= cap) return W2V_OK;
+    if (region) { HIP_TRY(hipDeviceSynchronize()); HIP_TRY(hipFree(region)); region = nullptr; cap = 0; }
     size_t want = bytes + bytes / 8 + 4096;
-    hipError_t e = hipMalloc((void**)&sh->ws, want);
+    hipError_t e = hipMalloc((void**)&region, want);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         want = bytes;
-        e = hipMalloc((void**)&sh->ws, want);
+        e = hipMalloc((void**)&region, want);
     }
     if (e != hipSuccess) {
         (void)hipGetLastError();
         return fail(W2V_ERR_ALLOC, "scratch allocation of %zu bytes failed: %s", want,
                     hipGetErrorString(e));
     }
-    sh->ws_cap = want;
+    cap = want;
     return W2V_OK;
 }
+
+int ensure_ws(w2v_shard* sh, size_t bytes) { return ensure_region(sh->ws, sh->ws_cap, bytes); }
 
 struct Phase {
     w2v_shard* sh; int phase; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
@@ -540,6 +546,7 @@ extern "C" int w2v_shard_destroy(w2v_shard* sh) {
     if (sh->keep) (void)hipFree(sh->keep);
     if (sh->err) (void)hipFree(sh->err);
     if (sh->ws) (void)hipFree(sh->ws);
+    if (sh->pairs_ws) (void)hipFree(sh->pairs_ws);
     if (sh->ev_fork) (void)hipEventDestroy(sh->ev_fork);
     if (sh->ev_keys) (void)hipEventDestroy(sh->ev_keys);
     if (sh->ev_join) (void)hipEventDestroy(sh->ev_join);
@@ -1248,19 +1255,19 @@ static int make_pairs_impl(w2v_shard* sh, const uint32_t* tokens, const uint64_t
         return W2V_OK;
     }
     size_t need = sizeof(uint32_t) * (pairs_scratch_u32(n_tokens, interleave) + 64) + 512;
-    rc = ensure_ws(sh, need);
+    rc = ensure_region(sh->pairs_ws, sh->pairs_ws_cap, need);
     if (rc) return rc;
     PairArgs a{};
     a.tokens = tokens; a.sent_off = sent_off; a.n_sent = n_sent; a.n_tokens = n_tokens;
     a.token_base = token_base; a.epoch = epoch; a.seed = corpus_seed; a.B = B;
     a.keep = sh->has_tables ? sh->keep : nullptr; a.V = sh->V;
     a.in_idx = in_idx; a.out_idx = out_idx; a.capacity = capacity; a.interleave = interleave;
-    a.total_pairs = (uint32_t*)sh->ws;
+    a.total_pairs = (uint32_t*)sh->pairs_ws;
     if (cbow) {
         a.ctx_off = cbow->ctx_off; a.centers = cbow->centers; a.cap_examples = cbow->cap_examples;
-        a.total_examples = (uint32_t*)sh->ws + 1;
+        a.total_examples = (uint32_t*)sh->pairs_ws + 1;
     }
-    a.scratch = (uint32_t*)sh->ws + 64;
+    a.scratch = (uint32_t*)sh->pairs_ws + 64;
     a.err = sh->err;
     {
         Phase ph(sh, W2V_PH_PAIRS, st);
