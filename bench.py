@@ -148,16 +148,22 @@ def copy_probe(torch, mb):
 class ExampleStream:
     """Feeds minibatches of n bag-of-words examples formed from a token corpus (device side).  A
     token block gives a run of examples; whole minibatches are cut from it and the block's last,
-    incomplete minibatch is dropped (its formation cost still counts)."""
+    incomplete minibatch is dropped (its formation cost still counts).  Blocks alternate between
+    two sets of buffers and are formed on a stream of their own, beside the training calls queued
+    before; a set is refilled only after the training calls that read it have finished (event)."""
 
     def __init__(self, shard, wl, tokens, sent_off, block_tokens, n, torch):
         self.torch, self.sh, self.wl, self.n = torch, shard, wl, n
         self.tok = torch.from_numpy(tokens.view(np.int32)).cuda()
         self.off_host = sent_off.astype(np.int64)
+        self.off_dev = torch.from_numpy(self.off_host).cuda()
         self.block_tokens = block_tokens
-        self.co = torch.empty(block_tokens + 64, dtype=torch.int32, device="cuda")
-        self.ce = torch.empty(block_tokens + 63, dtype=torch.int32, device="cuda")
-        self.cx = torch.empty((block_tokens + 63) * 2 * wl.window, dtype=torch.int32, device="cuda")
+        self.sets = [(torch.empty(block_tokens + 64, dtype=torch.int32, device="cuda"),
+                      torch.empty((block_tokens + 63) * 2 * wl.window, dtype=torch.int32, device="cuda"),
+                      torch.empty(block_tokens + 63, dtype=torch.int32, device="cuda")) for _ in range(2)]
+        self.done = [None, None]        # event: the training calls that read set i have been queued
+        self.which = 1
+        self.side = torch.cuda.Stream()
         self.have = self.pos = self.sent = self.epoch = 0
         self.tokens_used = 0
 
@@ -170,12 +176,20 @@ class ExampleStream:
         s1 = int(np.searchsorted(off, t0 + self.block_tokens, side="right")) - 1
         s1 = min(max(s1, s0 + 1), off.size - 1)
         t1 = int(off[s1])
-        rel = torch.from_numpy(off[s0:s1 + 1] - t0).cuda()
-        n_ex, n_ctx = self.sh.make_cbow_examples(self.tok[t0:t1], rel, t0, self.epoch, self.wl.seed,
-                                                 self.wl.window, self.co, self.cx, self.ce)
-        assert n_ex <= self.ce.numel() and n_ctx <= self.cx.numel()
+        ev = torch.cuda.Event()                      # everything queued so far reads the current set
+        ev.record(torch.cuda.current_stream())
+        self.done[self.which] = ev
+        self.which ^= 1
+        self.co, self.cx, self.ce = self.sets[self.which]
+        with torch.cuda.stream(self.side):
+            if self.done[self.which] is not None:
+                self.side.wait_event(self.done[self.which])
+            rel = self.off_dev[s0:s1 + 1] - t0
+            n_ex, n_ctx = self.sh.make_cbow_examples(self.tok[t0:t1], rel, t0, self.epoch, self.wl.seed,
+                                                     self.wl.window, self.co, self.cx, self.ce)
+            assert n_ex <= self.ce.numel() and n_ctx <= self.cx.numel()
+            self.co_host = self.co[:n_ex + 1].cpu().numpy()  # offsets, to slice the context words
         self.have, self.pos, self.sent = n_ex, 0, s1
-        self.co_host = self.co[:n_ex + 1].cpu().numpy()      # offsets, to slice the context words
         self.tokens_used += t1 - t0
 
     def next(self):
