@@ -729,3 +729,43 @@ def test_new_counts_void_an_announced_minibatch():
     for sh in (told, plain):
         sh.status()
         sh.destroy()
+
+
+def test_pair_formation_on_its_own_stream_beside_training():
+    # blocks of text are turned into pairs on a second stream while the training calls on the
+    # pairs of the block before are still queued on the first: same pairs, same vectors as one
+    # stream doing one thing after the other
+    V, d, k, B, blocks, n_tok = 2000, 300, 5, 5, 4, 60_000
+    rng = np.random.default_rng(12)
+    cdf = workloads.zipf_cdf(V, 1.0)
+    counts = zipf_counts(V)
+    texts = [workloads.zipf_draw(cdf, n_tok, rng) for _ in range(blocks)]
+    off = torch.from_numpy(np.arange(0, n_tok + 1, 20, dtype=np.int64)).cuda()
+    side = torch.cuda.Stream()
+    results = []
+    for overlapped in (False, True):
+        sh = make_shard(V, d, 6, counts, t=1e-3)
+        bufs = [(torch.empty(n_tok * 2 * B, dtype=torch.int32, device="cuda"),
+                 torch.empty(n_tok * 2 * B, dtype=torch.int32, device="cuda")) for _ in range(blocks)]
+        formed = []
+        for j in range(blocks):
+            gi, go = bufs[j]
+            if overlapped:
+                with torch.cuda.stream(side):
+                    cnt = sh.make_pairs(dev(texts[j]), off, j * n_tok, 0, 77, B, gi, go)
+            else:
+                cnt = sh.make_pairs(dev(texts[j]), off, j * n_tok, 0, 77, B, gi, go)
+            formed.append(cnt)
+            for h, lo in enumerate(range(0, cnt - 4095, 4096)):          # whole minibatches
+                w2v.train_minibatch([sh], gi[lo:lo + 4096], go[lo:lo + 4096], k,
+                                    w2v.minibatch_seed(j, h), 0.002)
+        torch.cuda.synchronize()
+        results.append((formed, [w2v.index_to_numpy(a[:c]).copy() for (a, _), c in zip(bufs, formed)],
+                        all_rows(sh, 0), all_rows(sh, 1)))
+        sh.status()
+        sh.destroy()
+    assert results[0][0] == results[1][0] and min(results[0][0]) > 4096
+    for a, b in zip(results[0][1], results[1][1]):
+        assert np.array_equal(a, b)
+    assert np.isfinite(results[0][2]).all() and np.isfinite(results[0][3]).all()
+    assert np.array_equal(results[0][2], results[1][2]) and np.array_equal(results[0][3], results[1][3])
