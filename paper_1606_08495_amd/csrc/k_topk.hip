@@ -92,10 +92,11 @@ template <int TM, int TN, int WPE, bool VEC4>
 __global__ __launch_bounds__(TK_THREADS, WPE) void topk_scores_kernel(TopkArgs a) {
     constexpr int BQ = 64 * TM, BC = 64 * TN;
     constexpr int MOVES_A = BQ * TK_BK / 4 / TK_THREADS, MOVES_B = BC * TK_BK / 4 / TK_THREADS;
-    __shared__ float As[BQ][TK_LD];
-    __shared__ float Bs[BC][TK_LD];
+    __shared__ __align__(16) float As[BQ][TK_LD];
+    __shared__ __align__(16) float Bs[BC][TK_LD];
     __shared__ float s_invq[BQ];
     __shared__ float s_theta[BQ];
+    __shared__ __align__(16) float s_tq[BQ];
 
     const uint32_t total = a.nq_tiles * a.nc_tiles;
     const uint32_t per_xcd = (total + 7u) / 8u;
@@ -108,8 +109,21 @@ __global__ __launch_bounds__(TK_THREADS, WPE) void topk_scores_kernel(TopkArgs a
     const int wm = wave / 2, wn = wave % 2;
     for (int i = tid; i < BQ; i += TK_THREADS) {
         const uint32_t q = q0 + i;
-        s_invq[i] = q < a.Q ? a.invq[q] : 0.f;
-        s_theta[i] = q < a.Q ? a.theta[q] : INFINITY;
+        const float iq = q < a.Q ? a.invq[q] : 0.f;
+        const float th = q < a.Q ? a.theta[q] : INFINITY;
+        s_invq[i] = iq;
+        s_theta[i] = th;
+        // The same threshold for the raw product dot x (1/|c|), lowered by 2^-20 of itself so that
+        // no score the exact test below accepts is missed (the two roundings of the score and the
+        // ones made here stay under 2^-22 relative); -inf sends every element to the exact test.
+        float t;
+        if (iq == 0.f) {
+            t = th <= 0.f ? -INFINITY : INFINITY;         // every score of a zero query is 0
+        } else {
+            const float r = th / iq;
+            t = fabsf(r) < INFINITY ? r - fabsf(r) * 0x1p-20f : (r > 0.f && th == INFINITY ? INFINITY : -INFINITY);
+        }
+        s_tq[i] = t;
     }
 
     // staging: thread t moves float4 number t, t+256, ... of each panel of TK_BK columns, i.e. the
@@ -158,9 +172,11 @@ __global__ __launch_bounds__(TK_THREADS, WPE) void topk_scores_kernel(TopkArgs a
                                         kb + TK_BK + scol, a.d);
         }
         const int kmax = (int)min((uint32_t)TK_BK, a.d - kb);   // columns beyond d hold zeros: skipped
-#pragma unroll
-        for (int kk = 0; kk < TK_BK; kk += 2) {
-            if (kk >= kmax) break;
+        // one step of two columns per trip (longer straight runs, which would let the compiler
+        // issue LDS reads under earlier products, measured the same or slower; so did 16-byte LDS
+        // accesses on a column order that gives each lane four adjacent floats per four steps)
+#pragma unroll 1
+        for (int kk = 0; kk < kmax; kk += 2) {
             float av[TM], bv[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) av[i] = As[wm * 32 * TM + i * 32 + fr][kk + fk];
@@ -177,16 +193,30 @@ __global__ __launch_bounds__(TK_THREADS, WPE) void topk_scores_kernel(TopkArgs a
     // filter: a score at or above the query's threshold joins the query's pending list.  For a
     // given accumulator register the 32 lanes of a half-wavefront hold 32 candidates of one query,
     // so each half reserves its slots with a single atomic.
+    // Most tiles hold no such score once the thresholds have risen, so each 32 x 32 tile is first
+    // screened with two instructions per element (raw product against the lowered threshold);
+    // only a tile with a hit goes through the exact test.
 #pragma unroll
     for (int ti = 0; ti < TM; ++ti) {
+        const int qbase = wm * 32 * TM + ti * 32 + 4 * fk;   // this lane's queries: qbase + 8 (v/4) + v%4
+        float tq[16];
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            const float4 t4 = *reinterpret_cast<const float4*>(&s_tq[qbase + 8 * v4]);
+            tq[4 * v4 + 0] = t4.x; tq[4 * v4 + 1] = t4.y; tq[4 * v4 + 2] = t4.z; tq[4 * v4 + 3] = t4.w;
+        }
 #pragma unroll
         for (int tj = 0; tj < TN; ++tj) {
             const uint32_t c = c0 + wn * 32 * TN + tj * 32 + fr;
             const bool c_ok = c < a.c_end;
             const float ic = c_ok ? a.invc[c] : 0.f;
+            float over = -INFINITY;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) over = fmaxf(over, fmaf(acc[ti][tj][v], ic, -tq[v]));
+            if (__ballot(over >= 0.f) == 0) continue;        // uniform per wavefront
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int ql = wm * 32 * TM + ti * 32 + 8 * (v / 4) + 4 * fk + (v % 4);
+                const int ql = qbase + 8 * (v / 4) + (v % 4);
                 const float s = acc[ti][tj][v] * s_invq[ql] * ic;
                 const bool pass = c_ok && s >= s_theta[ql];  // padded queries carry +inf: never
                 const uint64_t both = __ballot(pass);
