@@ -18,7 +18,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int TK_BQ = 128;          // queries per block tile (2 x 2 wavefronts x 2 x 2 tiles of 32)
 constexpr int TK_BC = 128;          // candidates per block tile; granularity of a round
-constexpr int TK_BK = 32;           // columns staged per step (16 and 64 measured slower)
+constexpr int TK_BK = 16;           // columns per panel; two panels are held in LDS
 constexpr int TK_LD = TK_BK + 1;    // LDS row pitch (odd: conflict-free column reads)
 constexpr int TK_THREADS = 256;     // four wavefronts
 constexpr int TK_RPM = TK_THREADS / (TK_BK / 4);            // rows covered by one move of the block
@@ -92,8 +92,8 @@ template <int TM, int TN, int WPE, bool VEC4>
 __global__ __launch_bounds__(TK_THREADS, WPE) void topk_scores_kernel(TopkArgs a) {
     constexpr int BQ = 64 * TM, BC = 64 * TN;
     constexpr int MOVES_A = BQ * TK_BK / 4 / TK_THREADS, MOVES_B = BC * TK_BK / 4 / TK_THREADS;
-    __shared__ __align__(16) float As[BQ][TK_LD];
-    __shared__ __align__(16) float Bs[BC][TK_LD];
+    __shared__ float As[2][BQ][TK_LD];
+    __shared__ float Bs[2][BC][TK_LD];
     __shared__ float s_invq[BQ];
     __shared__ float s_theta[BQ];
     __shared__ __align__(16) float s_tq[BQ];
@@ -126,20 +126,36 @@ __global__ __launch_bounds__(TK_THREADS, WPE) void topk_scores_kernel(TopkArgs a
         s_tq[i] = t;
     }
 
-    // staging: thread t moves float4 number t, t+256, ... of each panel of TK_BK columns, i.e. the
-    // same four columns of rows srow0, srow0 + TK_RPM, ...
+    // Staging through two LDS buffers of TK_BK columns: while a panel is multiplied, the next one
+    // is written to the other buffer (from registers loaded during the panel before) and the one
+    // after is requested from memory; one barrier per panel.  Thread t moves float4 number t,
+    // t + 256, ... of a panel, i.e. the same four columns of rows srow0, srow0 + TK_RPM, ...
+    // (One buffer of 32 columns with a barrier on either side of its refill measured 1 % slower.)
     const int srow0 = tid / (TK_BK / 4), scol = (tid % (TK_BK / 4)) * 4;
     const float* arow0 = a.Qm + (uint64_t)(q0 + srow0) * a.d;      // not dereferenced past Q / c_end
     const float* brow0 = a.Cm + (uint64_t)(c0 + srow0) * a.d;
     const uint64_t row_step = (uint64_t)TK_RPM * a.d;
     float4 ra[MOVES_A], rb[MOVES_B];
+    auto fetch = [&](uint32_t col0) {
 #pragma unroll
-    for (int i = 0; i < MOVES_A; ++i)
-        ra[i] = load_cols<VEC4>(arow0 + i * row_step, q0 + srow0 + i * TK_RPM < a.Q, scol, a.d);
+        for (int i = 0; i < MOVES_A; ++i)
+            ra[i] = load_cols<VEC4>(arow0 + i * row_step, q0 + srow0 + i * TK_RPM < a.Q, col0 + scol, a.d);
 #pragma unroll
-    for (int i = 0; i < MOVES_B; ++i)
-        rb[i] = load_cols<VEC4>(brow0 + i * row_step, c0 + srow0 + i * TK_RPM < a.c_end, scol, a.d);
-
+        for (int i = 0; i < MOVES_B; ++i)
+            rb[i] = load_cols<VEC4>(brow0 + i * row_step, c0 + srow0 + i * TK_RPM < a.c_end, col0 + scol, a.d);
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < MOVES_A; ++i) {
+            float* pa = &As[buf][srow0 + i * TK_RPM][scol];
+            pa[0] = ra[i].x; pa[1] = ra[i].y; pa[2] = ra[i].z; pa[3] = ra[i].w;
+        }
+#pragma unroll
+        for (int i = 0; i < MOVES_B; ++i) {
+            float* pb = &Bs[buf][srow0 + i * TK_RPM][scol];
+            pb[0] = rb[i].x; pb[1] = rb[i].y; pb[2] = rb[i].z; pb[3] = rb[i].w;
+        }
+    };
     v16f acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -148,46 +164,34 @@ __global__ __launch_bounds__(TK_THREADS, WPE) void topk_scores_kernel(TopkArgs a
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     const int fr = lane & 31, fk = lane >> 5;
-    for (uint32_t kb = 0; kb < a.d; kb += TK_BK) {
-        __syncthreads();                                     // the previous panel has been consumed
-#pragma unroll
-        for (int i = 0; i < MOVES_A; ++i) {
-            float* pa = &As[srow0 + i * TK_RPM][scol];
-            pa[0] = ra[i].x; pa[1] = ra[i].y; pa[2] = ra[i].z; pa[3] = ra[i].w;
+    fetch(0);
+    stash(0);
+    if (TK_BK < a.d) fetch(TK_BK);
+    __syncthreads();
+    int cur = 0;
+    for (uint32_t kb = 0; kb < a.d; kb += TK_BK, cur ^= 1) {
+        if (kb + TK_BK < a.d) {
+            stash(cur ^ 1);
+            if (kb + 2 * TK_BK < a.d) fetch(kb + 2 * TK_BK);
         }
-#pragma unroll
-        for (int i = 0; i < MOVES_B; ++i) {
-            float* pb = &Bs[srow0 + i * TK_RPM][scol];
-            pb[0] = rb[i].x; pb[1] = rb[i].y; pb[2] = rb[i].z; pb[3] = rb[i].w;
-        }
-        __syncthreads();
-        if (kb + TK_BK < a.d) {                              // next panel on its way during the math
-#pragma unroll
-            for (int i = 0; i < MOVES_A; ++i)
-                ra[i] = load_cols<VEC4>(arow0 + i * row_step, q0 + srow0 + i * TK_RPM < a.Q,
-                                        kb + TK_BK + scol, a.d);
-#pragma unroll
-            for (int i = 0; i < MOVES_B; ++i)
-                rb[i] = load_cols<VEC4>(brow0 + i * row_step, c0 + srow0 + i * TK_RPM < a.c_end,
-                                        kb + TK_BK + scol, a.d);
-        }
-        const int kmax = (int)min((uint32_t)TK_BK, a.d - kb);   // columns beyond d hold zeros: skipped
+        const int kmax = (int)min((uint32_t)TK_BK, a.d - kb);     // columns beyond d hold zeros: skipped
         // one step of two columns per trip (longer straight runs, which would let the compiler
-        // issue LDS reads under earlier products, measured the same or slower; so did 16-byte LDS
-        // accesses on a column order that gives each lane four adjacent floats per four steps)
+        // issue LDS reads under earlier products, measured the same; 16-byte LDS accesses on a
+        // column order that gives each lane four adjacent floats per four steps measured slower)
 #pragma unroll 1
         for (int kk = 0; kk < kmax; kk += 2) {
             float av[TM], bv[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) av[i] = As[wm * 32 * TM + i * 32 + fr][kk + fk];
+            for (int i = 0; i < TM; ++i) av[i] = As[cur][wm * 32 * TM + i * 32 + fr][kk + fk];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bv[j] = Bs[wn * 32 * TN + j * 32 + fr][kk + fk];
+            for (int j = 0; j < TN; ++j) bv[j] = Bs[cur][wn * 32 * TN + j * 32 + fr][kk + fk];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
+        __syncthreads();
     }
 
     // filter: a score at or above the query's threshold joins the query's pending list.  For a
