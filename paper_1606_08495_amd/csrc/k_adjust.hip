@@ -585,8 +585,11 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
 // latency-bound (rows in flight per SIMD x row size / memory latency), and registers spent on
 // rows in flight buy more than registers spent on extra resident waves.
 // ---------------------------------------------------------------------------------------------
+// Register budget for five wavefronts per SIMD: at two float4 per lane the fused form would take
+// 102 registers and run four; held to 96 it spills five and is 1.6 % faster.  (Six: 30 % slower.
+// The same squeeze on the generic kernel or on the output-side kernel costs more than it gives.)
 template <int G, int NV, int T, int PB, bool FUSED, bool OWN>
-__global__ __launch_bounds__(ADJ_THREADS) void useg_multi_kernel(USideArgs a, uint32_t CP) {
+__global__ __launch_bounds__(ADJ_THREADS, 5) void useg_multi_kernel(USideArgs a, uint32_t CP) {
     constexpr bool NEED_U = FUSED || OWN;
     constexpr int GROUPS = ADJ_THREADS / G;
     constexpr int MAXP = 16, MAXE = MAXP * T;
