@@ -19,9 +19,10 @@
  *     one shard share that shard's scratch memory and must be stream-ordered with one another (same
  *     stream, or the caller orders them).  Scratch grows to the largest request seen and is then
  *     reused, so a steady-state training loop allocates nothing (cf. Section 6.1.3: the paper's
- *     shards also create no objects in steady state).  Part of a call's work may run on a second
- *     stream the shard owns, forked from `stream` and joined back into it by events before the call
- *     returns: for the caller everything is ordered on `stream`.
+ *     shards also create no objects in steady state).  Part of a call's work may run on streams
+ *     the shard owns (one for work beside the call's main kernels, one for announced minibatches),
+ *     forked from `stream` and joined back into it by events before the call returns: for the
+ *     caller everything is ordered on `stream`.
  *   - index arrays are uint32 word indices < V.  An index >= V never causes an out-of-range access:
  *     the kernel substitutes word 0 and raises a sticky flag that w2v_shard_status() reports.
  *   - layouts are row-major and dense: partial_dots / coeffs are [n][k+1] with the positive output
@@ -152,7 +153,7 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
 /* Optional look-ahead for a training loop on one shard.  Everything w2v_train_minibatch derives from
  * the indices alone -- the negatives, and the grouping of the minibatch's input and output rows that
  * makes the update deterministic -- depends on neither the vectors nor earlier minibatches.  This call
- * queues that work for a LATER minibatch on the shard's second stream, ordered after the work queued
+ * queues that work for a LATER minibatch on a stream the shard owns, ordered after the work queued
  * on `stream` so far, so that it runs beside the training call that is queued next:
  *     prefetch(h+1); train(h); prefetch(h+2); train(h+1); ...
  * or, on a column shard that serves the two calls of Section 5.1,

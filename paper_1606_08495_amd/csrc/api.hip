@@ -92,8 +92,11 @@ struct w2v_shard {
     // second stream for work that only depends on the keys (the output-side sort), joined back
     // into the caller's stream by an event before its result is used
     hipStream_t side = nullptr;
+    // third stream: the index work of announced minibatches (w2v_prefetch_minibatch), apart from
+    // `side` so that the current step's own second-stream work does not queue up behind it
+    hipStream_t ahead = nullptr;
     hipEvent_t ev_fork = nullptr, ev_keys = nullptr, ev_join = nullptr;
-    hipEvent_t ev_coeffs = nullptr, ev_wdone = nullptr, ev_tails = nullptr;
+    hipEvent_t ev_coeffs = nullptr, ev_wdone = nullptr, ev_tails = nullptr, ev_utails = nullptr;
     bool overlap = true;
     bool own_rows = true;           // fused step: singly named output rows updated by the input side
     bool last_update_fused = true;  // what the last update on this shard was: an announced minibatch
@@ -250,13 +253,18 @@ Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_
     return p;
 }
 
-// Reduce the partial slots of one side level by level into matrix M (in place).
+// Reduce the partial slots of one side level by level into matrix M (in place) -- or, for the
+// input side of the skip-gram step (defer_rows given), into the delta buffer, so that these passes
+// need not wait for the output side to finish reading M.
 void run_tails(w2v_shard* sh, float* M, float alpha, float* rows_a, uint32_t* keys_a, uint32_t slots,
-               float* rows_b, uint32_t* keys_b, hipStream_t st) {
+               float* rows_b, uint32_t* keys_b, hipStream_t st, float* defer_rows = nullptr,
+               uint32_t* defer_keys = nullptr, uint32_t cp = 0) {
     float* src_rows = rows_a; uint32_t* src_keys = keys_a;
     float* dst_rows = rows_b; uint32_t* dst_keys = keys_b;
+    uint32_t level = 0;
     while (slots > 0) {
         TailArgs t{M, sh->g, alpha, src_rows, src_keys, slots, dst_rows, dst_keys};
+        t.defer_rows = defer_rows; t.defer_keys = defer_keys; t.level = ++level; t.cp = cp;
         launch_tail(t, st);
         slots = slots_after(slots, tail_entries_per_chunk());
         std::swap(src_rows, dst_rows);
@@ -267,12 +275,14 @@ void run_tails(w2v_shard* sh, float* M, float alpha, float* rows_a, uint32_t* ke
 int ensure_side_stream(w2v_shard* sh) {
     if (sh->side) return W2V_OK;
     HIP_TRY(hipStreamCreateWithFlags(&sh->side, hipStreamNonBlocking));
+    HIP_TRY(hipStreamCreateWithFlags(&sh->ahead, hipStreamNonBlocking));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_fork, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_keys, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_join, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_coeffs, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_wdone, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_tails, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&sh->ev_utails, hipEventDisableTiming));
     return W2V_OK;
 }
 
@@ -363,8 +373,8 @@ int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
     int rc = ensure_set(sh, x, n, M);
     if (rc) return rc;
     HIP_TRY(hipEventRecord(sh->ev_pfork, st));
-    HIP_TRY(hipStreamWaitEvent(sh->side, sh->ev_pfork, 0));
-    hipStream_t side = sh->side;
+    HIP_TRY(hipStreamWaitEvent(sh->ahead, sh->ev_pfork, 0));
+    hipStream_t side = sh->ahead;
     const uint32_t bits = key_bits(sh->V);
     const bool marks = sh->own_rows && sh->last_update_fused;
     {
@@ -404,11 +414,12 @@ void join_output_sort(w2v_shard* sh, hipStream_t st) {
 }
 
 // The update of one shard from given coefficients (or, fused, from its own dots).
-// After the input-side kernel the coefficients exist, so the minibatch loss (if asked for, fused
-// form only) is summed on the second stream while the output side runs; after the output-side
-// kernel the two sides' remaining work is independent -- the output side's higher reduction levels
-// go to the second stream, the input side's write-back and levels stay on the caller's stream --
-// and the caller's stream finally waits for the second one.
+// After the input-side kernel the coefficients and the input side's partial sums exist, so the
+// minibatch loss (if asked for, fused form only) and the input side's higher reduction levels --
+// which park their results in the delta buffer and leave the input matrix alone -- run on the
+// second stream beside the output-side kernel.  After that kernel the output side's higher levels
+// follow on the second stream while the caller's stream writes the delta buffer back; the
+// caller's stream finally waits for the second one.
 void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* sku,
                   const uint32_t* perm, const uint32_t* skw, const uint32_t* sidx,
                   const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
@@ -425,14 +436,22 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         if (p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
         launch_useg(a, st);
     }
+    // The input side's higher levels only touch its slots and the delta buffer, and the loss only
+    // reads the coefficients: both go to the second stream and run beside the output-side kernel.
+    if (two) {
+        (void)hipEventRecord(ws_owner->ev_coeffs, st);
+        (void)hipStreamWaitEvent(side, ws_owner->ev_coeffs, 0);
+    }
     if (loss_out) {
-        if (two) {
-            (void)hipEventRecord(ws_owner->ev_coeffs, st);
-            (void)hipStreamWaitEvent(side, ws_owner->ev_coeffs, 0);
-        }
         Phase ph(ws_owner, W2V_PH_COEFF, side);
         launch_loss_from_coeffs(fused ? coeffs_out : coeffs_in, p.n, p.T, p.loss_tmp, loss_out, side);
     }
+    {
+        Phase ph(ws_owner, W2V_PH_APPLY, side);
+        run_tails(sh, sh->U, alpha, p.pa_rows, p.pa_keys, p.slots_u1, p.pe_rows, p.pe_keys, side,
+                  p.delta, p.dkey, useg_pairs_per_chunk(p.T));
+    }
+    if (two) (void)hipEventRecord(ws_owner->ev_utails, side);
     join_output_sort(ws_owner, st);
     {
         Phase ph(ws_owner, W2V_PH_WSIDE, st);
@@ -451,11 +470,13 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         Phase ph(ws_owner, W2V_PH_APPLY, side);
         run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, side);
     }
-    if (two) (void)hipEventRecord(ws_owner->ev_tails, side);
+    if (two) {
+        (void)hipEventRecord(ws_owner->ev_tails, side);
+        (void)hipStreamWaitEvent(st, ws_owner->ev_utails, 0);
+    }
     {
         Phase ph(ws_owner, W2V_PH_APPLY, st);
         launch_apply_delta(sh->U, sh->g, p.delta, p.dkey, p.n, alpha, st);
-        run_tails(sh, sh->U, alpha, p.pa_rows, p.pa_keys, p.slots_u1, p.pe_rows, p.pe_keys, st);
     }
     if (two) (void)hipStreamWaitEvent(st, ws_owner->ev_tails, 0);
 }
@@ -553,12 +574,14 @@ extern "C" int w2v_shard_destroy(w2v_shard* sh) {
     if (sh->ev_coeffs) (void)hipEventDestroy(sh->ev_coeffs);
     if (sh->ev_wdone) (void)hipEventDestroy(sh->ev_wdone);
     if (sh->ev_tails) (void)hipEventDestroy(sh->ev_tails);
+    if (sh->ev_utails) (void)hipEventDestroy(sh->ev_utails);
     if (sh->ev_pfork) (void)hipEventDestroy(sh->ev_pfork);
     for (auto& x : sh->sets) {
         if (x.ready) (void)hipEventDestroy(x.ready);
         if (x.base) (void)hipFree(x.base);
     }
     if (sh->side) (void)hipStreamDestroy(sh->side);
+    if (sh->ahead) (void)hipStreamDestroy(sh->ahead);
     delete sh;
     return W2V_OK;
 }

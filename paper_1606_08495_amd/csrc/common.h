@@ -144,6 +144,9 @@ struct TailArgs {
     float* M; RowGeom g; float alpha;
     const float* src_rows; const uint32_t* src_keys; uint32_t entries;
     float* prows; uint32_t* pkeys;
+    // input side only: finished sums go to the delta buffer (rows, keys) instead of into M;
+    // level = 1 for the first pass over the input-side kernel's slots, cp = its pairs per chunk
+    float* defer_rows = nullptr; uint32_t* defer_keys = nullptr; uint32_t level = 0, cp = 0;
 };
 void launch_tail(const TailArgs& a, hipStream_t st);
 

@@ -50,9 +50,19 @@ struct SegArgs {
     float alpha;
     float4* prows; uint32_t* pkeys;    // this level's partial slots
     bool skip_alone;                   // wown_kernel: runs of length one are handled elsewhere
+    // DEFER: finished sums are not added to dst but parked in the input side's delta buffer
+    float4* defer_rows; uint32_t* defer_keys;
+    uint32_t level, cp;                // level of this pass (1 = first), pairs per input-side chunk
 };
 
-template <int G, int NV, int C, int D, int SRC>
+// DEFER (higher levels of the input side): a run finished here must not touch the input matrix
+// yet -- the output side may still be reading it -- so its sum goes to the delta buffer, from
+// where apply_delta_kernel adds it with the same fma.  Its place there: every entry of a higher
+// level stands at a chunk border of the level below, and so, level by level, at a border of the
+// input-side kernel's chunk grid; the pair position right after that border lies inside the run,
+// is not the run's first pair (the run was cut there), and so holds no sum of its own.  Runs are
+// disjoint ranges of pair positions, hence no two finished runs share a place.
+template <int G, int NV, int C, int D, int SRC, bool DEFER = false>
 __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
     static_assert(C <= G && C % D == 0, "chunk must fit a lane group");
     const int l = threadIdx.x % G;
@@ -111,7 +121,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
         int cm = __shfl(complete, e, G);
         uint32_t dk = __shfl(key, e, G);
         load_row_if<G, NV>(h != 0, a.src + (uint64_t)sr * s4, d4, l, sv);
-        load_row_if<G, NV>(cm != 0, a.dst + (uint64_t)(cm ? dk : 0u) * s4, d4, l, dv);
+        load_row_if<G, NV>(cm != 0 && !DEFER, a.dst + (uint64_t)(cm ? dk : 0u) * s4, d4, l, dv);
     };
 #pragma unroll
     for (int t = 0; t < D; ++t) fetch(t, srcv[t], dstv[t]);
@@ -129,7 +139,13 @@ __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
             uint32_t dk = __shfl(key, e, G);
             if (h) axpy<NV>(cf, srcv[t], acc);
             if (en) {
-                if (cm) {
+                if (cm && DEFER) {
+                    uint32_t pos = e0 + (uint32_t)e;
+                    for (uint32_t lv = a.level; lv > 1; --lv) pos = ((pos + 2) >> 1) * (uint32_t)C;
+                    pos = ((pos + 2) >> 1) * a.cp;
+                    store_row<G, NV>(a.defer_rows + (uint64_t)pos * s4, d4, l, acc);
+                    if (l == 0) a.defer_keys[pos] = dk;
+                } else if (cm) {
                     float4 out[NV];
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
@@ -370,7 +386,7 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ x,
 
 void launch_wseg(const WSideArgs& w, hipStream_t st) {
     if (w.M == 0) return;
-    SegArgs a;
+    SegArgs a{};
     a.src = (const float4*)w.U; a.dst = (float4*)w.W; a.g = w.g; a.skey = w.skey; a.sidx = w.sidx;
     a.in_idx = w.in_idx; a.coeffs = w.coeffs; a.entries = w.M; a.T = w.T;
     a.alpha = w.alpha; a.prows = (float4*)w.prows; a.pkeys = w.pkeys;
@@ -392,16 +408,24 @@ void launch_wseg(const WSideArgs& w, hipStream_t st) {
 
 void launch_tail(const TailArgs& t, hipStream_t st) {
     if (t.entries == 0) return;
-    SegArgs a;
+    SegArgs a{};
     a.src = (const float4*)t.src_rows; a.dst = (float4*)t.M; a.g = t.g; a.skey = t.src_keys;
     a.sidx = nullptr; a.in_idx = nullptr; a.coeffs = nullptr; a.entries = t.entries; a.T = 1;
     a.skip_alone = false;
     a.alpha = t.alpha; a.prows = (float4*)t.prows; a.pkeys = t.pkeys;
+    a.defer_rows = (float4*)t.defer_rows; a.defer_keys = t.defer_keys; a.level = t.level; a.cp = t.cp;
     uint32_t nchunks = (t.entries + TAIL_C - 1) / TAIL_C;
 #define CALL(G, NV)                                                                              \
-    hipLaunchKernelGGL((seg_kernel<G, NV, TAIL_C, (NV <= 2 ? 4 : 2), 1>),                        \
-                       dim3(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)), dim3(ADJ_THREADS), 0, \
-                       st, a)
+    do {                                                                                         \
+        if (t.defer_rows)                                                                        \
+            hipLaunchKernelGGL((seg_kernel<G, NV, TAIL_C, (NV <= 2 ? 4 : 2), 1, true>),          \
+                               dim3(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)),             \
+                               dim3(ADJ_THREADS), 0, st, a);                                     \
+        else                                                                                     \
+            hipLaunchKernelGGL((seg_kernel<G, NV, TAIL_C, (NV <= 2 ? 4 : 2), 1>),                \
+                               dim3(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)),             \
+                               dim3(ADJ_THREADS), 0, st, a);                                     \
+    } while (0)
     W2V_DISPATCH_GEOM(t.g.d4, CALL);
 #undef CALL
 }
