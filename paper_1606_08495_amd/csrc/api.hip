@@ -96,7 +96,7 @@ struct w2v_shard {
     // `side` so that the current step's own second-stream work does not queue up behind it
     hipStream_t ahead = nullptr;
     hipEvent_t ev_fork = nullptr, ev_keys = nullptr, ev_join = nullptr;
-    hipEvent_t ev_coeffs = nullptr, ev_wdone = nullptr, ev_tails = nullptr, ev_utails = nullptr;
+    hipEvent_t ev_coeffs = nullptr, ev_wdone = nullptr, ev_tails = nullptr;
     bool overlap = true;
     bool own_rows = true;           // fused step: singly named output rows updated by the input side
     bool last_update_fused = true;  // what the last update on this shard was: an announced minibatch
@@ -282,7 +282,6 @@ int ensure_side_stream(w2v_shard* sh) {
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_coeffs, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_wdone, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&sh->ev_tails, hipEventDisableTiming));
-    HIP_TRY(hipEventCreateWithFlags(&sh->ev_utails, hipEventDisableTiming));
     return W2V_OK;
 }
 
@@ -418,7 +417,7 @@ void join_output_sort(w2v_shard* sh, hipStream_t st) {
 // minibatch loss (if asked for, fused form only) and the input side's higher reduction levels --
 // which park their results in the delta buffer and leave the input matrix alone -- run on the
 // second stream beside the output-side kernel.  After that kernel the output side's higher levels
-// follow on the second stream while the caller's stream writes the delta buffer back; the
+// follow on the caller's stream while the second stream writes the delta buffer back; the
 // caller's stream finally waits for the second one.
 void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* sku,
                   const uint32_t* perm, const uint32_t* skw, const uint32_t* sidx,
@@ -451,7 +450,6 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         run_tails(sh, sh->U, alpha, p.pa_rows, p.pa_keys, p.slots_u1, p.pe_rows, p.pe_keys, side,
                   p.delta, p.dkey, useg_pairs_per_chunk(p.T));
     }
-    if (two) (void)hipEventRecord(ws_owner->ev_utails, side);
     join_output_sort(ws_owner, st);
     {
         Phase ph(ws_owner, W2V_PH_WSIDE, st);
@@ -462,21 +460,21 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         w.skip_alone = p.own_rows;
         launch_wseg(w, st);
     }
+    // After the output-side kernel: its higher levels stay on the caller's stream (no wait in
+    // between), the write-back of the delta buffer goes to the second stream, behind the input
+    // side's levels there.
     if (two) {
         (void)hipEventRecord(ws_owner->ev_wdone, st);
         (void)hipStreamWaitEvent(side, ws_owner->ev_wdone, 0);
     }
     {
         Phase ph(ws_owner, W2V_PH_APPLY, side);
-        run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, side);
+        launch_apply_delta(sh->U, sh->g, p.delta, p.dkey, p.n, alpha, side);
     }
-    if (two) {
-        (void)hipEventRecord(ws_owner->ev_tails, side);
-        (void)hipStreamWaitEvent(st, ws_owner->ev_utails, 0);
-    }
+    if (two) (void)hipEventRecord(ws_owner->ev_tails, side);
     {
         Phase ph(ws_owner, W2V_PH_APPLY, st);
-        launch_apply_delta(sh->U, sh->g, p.delta, p.dkey, p.n, alpha, st);
+        run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st);
     }
     if (two) (void)hipStreamWaitEvent(st, ws_owner->ev_tails, 0);
 }
@@ -574,7 +572,6 @@ extern "C" int w2v_shard_destroy(w2v_shard* sh) {
     if (sh->ev_coeffs) (void)hipEventDestroy(sh->ev_coeffs);
     if (sh->ev_wdone) (void)hipEventDestroy(sh->ev_wdone);
     if (sh->ev_tails) (void)hipEventDestroy(sh->ev_tails);
-    if (sh->ev_utails) (void)hipEventDestroy(sh->ev_utails);
     if (sh->ev_pfork) (void)hipEventDestroy(sh->ev_pfork);
     for (auto& x : sh->sets) {
         if (x.ready) (void)hipEventDestroy(x.ready);
