@@ -89,8 +89,9 @@ struct w2v_shard {
     // scratch of the pair formation, apart from the training calls' so that the two may overlap
     char* pairs_ws = nullptr;
     size_t pairs_ws_cap = 0;
-    // second stream for work that only depends on the keys (the output-side sort), joined back
-    // into the caller's stream by an event before its result is used
+    // second stream: the part of a call that can run beside its main kernels (key generation and
+    // output-side sort; loss, the input side's higher levels, the write-back of the delta buffer),
+    // forked from the caller's stream and joined back into it by events
     hipStream_t side = nullptr;
     // third stream: the index work of announced minibatches (w2v_prefetch_minibatch), apart from
     // `side` so that the current step's own second-stream work does not queue up behind it
