@@ -83,8 +83,11 @@ def test_full300_step_sampled(init_w):
     cap = wl.n_pairs * 2
     gi = torch.empty(cap, dtype=torch.int32, device="cuda")
     go = torch.empty(cap, dtype=torch.int32, device="cuda")
-    cnt = sh.make_pairs(dev(tokens), torch.from_numpy(off.astype(np.int64)).cuda(), 0, 0, wl.seed,
-                        wl.window, gi, go)
+    # (init_w: as bench.py runs it -- pairs formed on a stream of their own, the minibatch announced
+    # to the shard before the step; otherwise everything on one stream, nothing announced)
+    tok_dev, off_dev = dev(tokens), torch.from_numpy(off.astype(np.int64)).cuda()
+    with torch.cuda.stream(torch.cuda.Stream() if init_w else torch.cuda.current_stream()):
+        cnt = sh.make_pairs(tok_dev, off_dev, 0, 0, wl.seed, wl.window, gi, go)
     oi, oo, ocnt = oracle.make_pairs(tokens, off, 0, 0, wl.seed, wl.window, kt)
     assert cnt == ocnt and cnt >= wl.n_pairs
     assert np.array_equal(w2v.index_to_numpy(gi[:cnt]), oi) and np.array_equal(w2v.index_to_numpy(go[:cnt]), oo)
@@ -114,6 +117,8 @@ def test_full300_step_sampled(init_w):
     # the fused step, then sampled rows
     loss = torch.zeros(1, dtype=torch.float64, device="cuda")
     alpha = workloads.alpha_schedule(wl, 0, 1000)
+    if init_w:
+        sh.prefetch_minibatch(a, b, wl.k, seed)
     w2v.train_minibatch([sh], a, b, wl.k, seed, alpha, loss=loss)
     sh.status()
     samp_u = sample_rows(in_idx, 24, 200, rng)
@@ -151,6 +156,7 @@ def test_slice60_dotprod_adjust_sampled():
     assert np.array_equal(w2v.index_to_numpy(sh.negatives(b, wl.k, seed)), neg)
     rows = np.concatenate([out_idx[:, None], neg], axis=1)
 
+    sh.prefetch_minibatch(a, b, wl.k, seed)          # as bench.py runs it: the minibatch announced
     dots = sh.dotprod(a, b, wl.k, seed).cpu().numpy()
     pick = rng.choice(n, 8192, replace=False)
     U, W, cin, cr, _, _ = compact_problem(wl, in_idx[pick], rows[pick], True)
