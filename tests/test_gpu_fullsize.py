@@ -283,8 +283,9 @@ def full_n_step(name, n_tokens):
            [sh.get_rows(1, dev(x)).cpu().numpy() for x in (samp_w, hot_w)] + [loss.item()]
     sh.destroy()
     del sh
-    say("   the same step on a fresh shard")
+    say("   the same step on a fresh shard, announced ahead as bench.py does")
     sh = fresh()
+    sh.prefetch_minibatch(a, b, wl.k, seed)
     w2v.train_minibatch([sh], a, b, wl.k, seed, wl.alpha, loss=loss)
     again = [sh.get_rows(0, dev(x)).cpu().numpy() for x in (samp_u, hot_u)] + \
             [sh.get_rows(1, dev(x)).cpu().numpy() for x in (samp_w, hot_w)] + [loss.item()]
