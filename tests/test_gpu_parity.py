@@ -769,3 +769,23 @@ def test_pair_formation_on_its_own_stream_beside_training():
         assert np.array_equal(a, b)
     assert np.isfinite(results[0][2]).all() and np.isfinite(results[0][3]).all()
     assert np.array_equal(results[0][2], results[1][2]) and np.array_equal(results[0][3], results[1][3])
+
+
+@pytest.mark.parametrize("V,d,n,k", [(50, 60, 1, 0), (50, 60, 700, 0), (3, 300, 1, 5), (2000, 100, 4097, 64)])
+def test_announced_edge_shapes_give_the_same_bits(V, d, n, k):
+    rng = np.random.default_rng(n + k)
+    counts = zipf_counts(V)
+    a, b = dev(rng.integers(0, V, n)), dev(rng.integers(0, V, n))
+    told, plain = make_shard(V, d, 2, counts), make_shard(V, d, 2, counts)
+    la, lb = (torch.zeros(1, dtype=torch.float64, device="cuda") for _ in range(2))
+    told.prefetch_minibatch(a[:0], b[:0], k, 1)                # an empty announcement is a no-op
+    for h in range(3):
+        told.prefetch_minibatch(a, b, k, 10 + h)
+        w2v.train_minibatch([told], a, b, k, 10 + h, 0.01, loss=la)
+        w2v.train_minibatch([plain], a, b, k, 10 + h, 0.01, loss=lb)
+        assert la.item() == lb.item()
+    for which in (0, 1):
+        assert np.array_equal(all_rows(told, which), all_rows(plain, which))
+    for sh in (told, plain):
+        sh.status()
+        sh.destroy()
