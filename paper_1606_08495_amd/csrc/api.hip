@@ -904,7 +904,8 @@ struct CbowPlan {
     float* pa_rows; uint32_t* pa_keys;               // unused slots of the per-example pass
     float* pb_rows; uint32_t* pb_keys;               // output side, level 1
     float* pd_rows; uint32_t* pd_keys;               // input side, level 1
-    float* pc_rows; uint32_t* pc_keys;               // level 2 of either side
+    float* pc_rows; uint32_t* pc_keys;               // level 2, output side
+    float* pe_rows; uint32_t* pe_keys;               // level 2, input side (the two sides overlap)
     uint32_t slots_a, slots_w1, slots_c1, slots_2;
     size_t bytes;
 };
@@ -940,6 +941,7 @@ CbowPlan make_cbow_plan(char* base, uint32_t n, uint32_t k, uint32_t m, uint32_t
         p.pb_rows = c.take<float>((size_t)p.slots_w1 * row); p.pb_keys = c.take<uint32_t>(p.slots_w1 + 1);
         p.pd_rows = c.take<float>((size_t)p.slots_c1 * row); p.pd_keys = c.take<uint32_t>(p.slots_c1 + 1);
         p.pc_rows = c.take<float>((size_t)p.slots_2 * row);  p.pc_keys = c.take<uint32_t>(p.slots_2 + 1);
+        p.pe_rows = c.take<float>((size_t)p.slots_2 * row);  p.pe_keys = c.take<uint32_t>(p.slots_2 + 1);
     }
     p.bytes = c.off + 256;
     return p;
@@ -1012,7 +1014,8 @@ void queue_cbow_hidden(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
 // E, forming dots and coefficients on the way when fused; the output side adds g_pj h_p to its
 // rows; the input side adds e_p / |C_p| to the input vector of every context entry.  H holds the
 // start-of-call input vectors and E the start-of-call output vectors, so the order of the two
-// write-backs does not matter.
+// write-backs does not matter -- with the second stream they run beside each other: the input side
+// there, behind its sort, the output side on the caller's stream.
 void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint32_t* skw,
                        const uint32_t* sidx, const uint32_t* skc, const uint32_t* cidx,
                        const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
@@ -1027,6 +1030,22 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
         if (fused && p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }   // source: the hidden vector
         launch_useg(a, st);
     }
+    const bool two = owner->overlap && owner->side;
+    hipStream_t side = two ? owner->side : st;
+    if (two) {
+        (void)hipEventRecord(owner->ev_coeffs, st);
+        (void)hipStreamWaitEvent(side, owner->ev_coeffs, 0);
+    }
+    {
+        Phase ph(owner, W2V_PH_APPLY, side);
+        WSideArgs u{};
+        u.U = p.E; u.W = sh->U; u.g = sh->g; u.skey = skc; u.sidx = cidx; u.M = p.m; u.T = 1;
+        u.in_idx = p.ex_of; u.coeffs = p.weight; u.alpha = alpha;
+        u.prows = p.pd_rows; u.pkeys = p.pd_keys;
+        launch_wseg(u, side);
+        run_tails(sh, sh->U, alpha, p.pd_rows, p.pd_keys, p.slots_c1, p.pe_rows, p.pe_keys, side);
+    }
+    if (two) (void)hipEventRecord(owner->ev_tails, side);
     join_output_sort(owner, st);
     {
         Phase ph(owner, W2V_PH_WSIDE, st);
@@ -1038,15 +1057,7 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
         launch_wseg(w, st);
         run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st);
     }
-    {
-        Phase ph(owner, W2V_PH_APPLY, st);
-        WSideArgs u{};
-        u.U = p.E; u.W = sh->U; u.g = sh->g; u.skey = skc; u.sidx = cidx; u.M = p.m; u.T = 1;
-        u.in_idx = p.ex_of; u.coeffs = p.weight; u.alpha = alpha;
-        u.prows = p.pd_rows; u.pkeys = p.pd_keys;
-        launch_wseg(u, st);
-        run_tails(sh, sh->U, alpha, p.pd_rows, p.pd_keys, p.slots_c1, p.pc_rows, p.pc_keys, st);
-    }
+    if (two) (void)hipStreamWaitEvent(st, owner->ev_tails, 0);
 }
 
 int check_cbow_pointers(const uint32_t* ctx_off, const uint32_t* ctx_idx, uint32_t m,
