@@ -150,7 +150,9 @@ class ExampleStream:
     token block gives a run of examples; whole minibatches are cut from it and the block's last,
     incomplete minibatch is dropped (its formation cost still counts).  Blocks alternate between
     two sets of buffers and are formed on a stream of their own, beside the training calls queued
-    before; a set is refilled only after the training calls that read it have finished (event)."""
+    before; a set is refilled only after the training calls that read it have finished (event).
+    The minibatch after the current one is cut ahead as well (peek), so that it can be announced to
+    the shard."""
 
     def __init__(self, shard, wl, tokens, sent_off, block_tokens, n, torch):
         self.torch, self.sh, self.wl, self.n = torch, shard, wl, n
@@ -161,8 +163,10 @@ class ExampleStream:
         self.sets = [(torch.empty(block_tokens + 64, dtype=torch.int32, device="cuda"),
                       torch.empty((block_tokens + 63) * 2 * wl.window, dtype=torch.int32, device="cuda"),
                       torch.empty(block_tokens + 63, dtype=torch.int32, device="cuda")) for _ in range(2)]
-        self.done = [None, None]        # event: the training calls that read set i have been queued
+        self.done = [None, None]        # event after the last training call queued on set i
         self.which = 1
+        self.ahead = None               # the minibatch after the current one: (set, arrays)
+        self.current_set = None
         self.side = torch.cuda.Stream()
         self.have = self.pos = self.sent = self.epoch = 0
         self.tokens_used = 0
@@ -176,9 +180,6 @@ class ExampleStream:
         s1 = int(np.searchsorted(off, t0 + self.block_tokens, side="right")) - 1
         s1 = min(max(s1, s0 + 1), off.size - 1)
         t1 = int(off[s1])
-        ev = torch.cuda.Event()                      # everything queued so far reads the current set
-        ev.record(torch.cuda.current_stream())
-        self.done[self.which] = ev
         self.which ^= 1
         self.co, self.cx, self.ce = self.sets[self.which]
         with torch.cuda.stream(self.side):
@@ -192,13 +193,33 @@ class ExampleStream:
         self.have, self.pos, self.sent = n_ex, 0, s1
         self.tokens_used += t1 - t0
 
-    def next(self):
+    def _cut(self):
         while self.have - self.pos < self.n:
             self._refill()
         a, b = self.pos, self.pos + self.n
         self.pos = b
         lo, hi = int(self.co_host[a]), int(self.co_host[b])
-        return (self.co[a:b + 1] - lo), self.cx[lo:hi], self.ce[a:b]
+        return self.which, ((self.co[a:b + 1] - lo), self.cx[lo:hi], self.ce[a:b])
+
+    def next(self):
+        """The current minibatch (the arrays peek() returned before, if it was called)."""
+        if self.ahead is None:
+            self.ahead = self._cut()
+        self.current_set, arrays = self.ahead
+        self.ahead = None
+        return arrays
+
+    def peek(self):
+        """The minibatch the following next() will return (same device arrays)."""
+        if self.ahead is None:
+            self.ahead = self._cut()
+        return self.ahead[1]
+
+    def consumed(self):
+        """Call after the training call on the current minibatch has been queued."""
+        ev = self.torch.cuda.Event()
+        ev.record(self.torch.cuda.current_stream())
+        self.done[self.current_set] = ev
 
 
 def run_cbow(args, torch, w2v, workloads):
@@ -225,8 +246,11 @@ def run_cbow(args, torch, w2v, workloads):
 
     def step(h):
         co, cx, ce = stream.next()
+        if not args.no_prefetch:                           # the next minibatch's index work, ahead
+            sh.cbow_prefetch_minibatch(*stream.peek(), wl.k, w2v.minibatch_seed(wl.seed, h + 1))
         w2v.cbow_train_minibatch([sh], co, cx, ce, wl.k, w2v.minibatch_seed(wl.seed, h),
                                  workloads.alpha_schedule(wl, h, H), loss=loss)
+        stream.consumed()
         return co, cx, ce
 
     first = None
@@ -294,7 +318,7 @@ def run_cbow(args, torch, w2v, workloads):
                    "zipf_s": wl.zipf_s, "window": wl.window, "subsample_t": wl.subsample_t,
                    "path": "make_cbow_examples+cbow_train_minibatch",
                    "distinct_input_rows": du, "distinct_output_rows": dw,
-                   "output_rows_named_once": single},
+                   "output_rows_named_once": single, "prefetch": not args.no_prefetch},
         "context_words_per_s": ctx_total / dt,
         "roofline": {"bound": "hbm", "kernel": "cbow_hidden_kernel" if dom == "dot" else
                      KERNEL_OF_PHASE.get(dom, dom), "phase": dom, "achieved": achieved,

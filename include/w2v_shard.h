@@ -209,6 +209,17 @@ int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S, const uint32_
                              uint32_t n, uint32_t k, uint64_t seed, float alpha, double* loss_dev,
                              void* stream);
 
+/* Look-ahead for the bag-of-words calls, as w2v_prefetch_minibatch is for the skip-gram ones: the
+ * checked context entries, the negatives and both groupings of a LATER minibatch are computed on a
+ * stream the shard owns, beside the calls queued next.  A w2v_cbow_train_minibatch whose first
+ * shard is this one, a w2v_cbow_dotprod or a w2v_cbow_adjust on this shard with the same three
+ * index arrays (same pointers, contents unchanged in between), m, n, k and seed uses the prepared
+ * work (the dotprod leaves it in place, an update consumes it); results are identical either way.
+ * Two minibatches can be held ahead; w2v_shard_set_counts voids what was announced before it. */
+int w2v_cbow_prefetch_minibatch(w2v_shard* shard, const uint32_t* ctx_off_dev,
+                                const uint32_t* ctx_idx_dev, uint32_t m, const uint32_t* out_idx_dev,
+                                uint32_t n, uint32_t k, uint64_t seed, void* stream);
+
 /* Examples from text: the same subsampling and window draws as w2v_make_pairs.  Every surviving
  * center with at least one surviving neighbour inside its window gives one example; its contexts are
  * those neighbours by increasing position (the pair stream's output words, grouped by center).

@@ -70,6 +70,24 @@ struct Prepared {
     uint32_t n = 0, k = 0; uint64_t seed = 0;
 };
 
+// The same for a bag-of-words minibatch (w2v_cbow_prefetch_minibatch): the checked context entries
+// with their example numbers and weights, the destination keys, and both sorts.
+struct CbowSet {
+    char* base = nullptr; size_t cap = 0;
+    uint32_t *keys = nullptr, *ctx_safe = nullptr, *ex_of = nullptr, *iota = nullptr;
+    float* weight = nullptr;
+    uint32_t *wk0 = nullptr, *wv0 = nullptr, *wk1 = nullptr, *wv1 = nullptr, *sort_tmp_w = nullptr;
+    uint32_t *ck0 = nullptr, *cv0 = nullptr, *ck1 = nullptr, *cv1 = nullptr, *sort_tmp_c = nullptr;
+    uint32_t *skw = nullptr, *sidx = nullptr, *skc = nullptr, *cidx = nullptr;   // sorted results
+    hipEvent_t ready = nullptr;
+};
+
+struct CbowPrepared {
+    bool valid = false; bool own_rows = false;
+    const uint32_t* ctx_off = nullptr; const uint32_t* ctx_idx = nullptr; const uint32_t* out_idx = nullptr;
+    uint32_t n = 0, k = 0, m = 0; uint64_t seed = 0;
+};
+
 struct w2v_shard {
     int device = 0;
     uint32_t V = 0, d_total = 0, col_begin = 0, d_slice = 0;
@@ -105,6 +123,9 @@ struct w2v_shard {
     IndexSet sets[2];
     Prepared prep[2];               // what sets[i] holds
     int next_set = 0;
+    CbowSet csets[2];
+    CbowPrepared cprep[2];
+    int next_cset = 0;
     hipEvent_t ev_pfork = nullptr;
     // timing
     bool timing = false;
@@ -578,6 +599,10 @@ extern "C" int w2v_shard_destroy(w2v_shard* sh) {
         if (x.ready) (void)hipEventDestroy(x.ready);
         if (x.base) (void)hipFree(x.base);
     }
+    for (auto& x : sh->csets) {
+        if (x.ready) (void)hipEventDestroy(x.ready);
+        if (x.base) (void)hipFree(x.base);
+    }
     if (sh->side) (void)hipStreamDestroy(sh->side);
     if (sh->ahead) (void)hipStreamDestroy(sh->ahead);
     delete sh;
@@ -617,6 +642,7 @@ extern "C" int w2v_shard_set_counts(w2v_shard* sh, const uint64_t* counts, doubl
     sh->has_tables = true;
     sh->table_tag = tag;
     sh->prep[0].valid = sh->prep[1].valid = false;   // negatives drawn from the old table are void
+    sh->cprep[0].valid = sh->cprep[1].valid = false;
     return W2V_OK;
 }
 
@@ -1019,7 +1045,7 @@ void queue_cbow_hidden(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
 void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint32_t* skw,
                        const uint32_t* sidx, const uint32_t* skc, const uint32_t* cidx,
                        const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
-                       hipStream_t st) {
+                       bool join_sorts, hipStream_t st) {
     {
         Phase ph(owner, W2V_PH_USIDE, st);
         USideArgs a{};
@@ -1046,7 +1072,7 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
         run_tails(sh, sh->U, alpha, p.pd_rows, p.pd_keys, p.slots_c1, p.pe_rows, p.pe_keys, side);
     }
     if (two) (void)hipEventRecord(owner->ev_tails, side);
-    join_output_sort(owner, st);
+    if (join_sorts) join_output_sort(owner, st);
     {
         Phase ph(owner, W2V_PH_WSIDE, st);
         WSideArgs w{};
@@ -1058,6 +1084,105 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
         run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st);
     }
     if (two) (void)hipStreamWaitEvent(st, owner->ev_tails, 0);
+}
+
+// Buffers of one announced bag-of-words minibatch, carved from the set's own allocation.
+int ensure_cset(w2v_shard* sh, CbowSet& x, uint32_t n, uint32_t M, uint32_t m) {
+    for (int pass = 0; pass < 2; ++pass) {
+        Carver c(pass ? x.base : nullptr);
+        uint32_t* keys = c.take<uint32_t>(M);
+        uint32_t* ctx_safe = c.take<uint32_t>(m); uint32_t* ex_of = c.take<uint32_t>(m);
+        float* weight = c.take<float>(m);
+        uint32_t* iota = c.take<uint32_t>(n);
+        uint32_t* wk0 = c.take<uint32_t>(M); uint32_t* wv0 = c.take<uint32_t>(M);
+        uint32_t* wk1 = c.take<uint32_t>(M); uint32_t* wv1 = c.take<uint32_t>(M);
+        uint32_t* tw = c.take<uint32_t>(sort_scratch_u32(M ? M : 1));
+        uint32_t* ck0 = c.take<uint32_t>(m); uint32_t* cv0 = c.take<uint32_t>(m);
+        uint32_t* ck1 = c.take<uint32_t>(m); uint32_t* cv1 = c.take<uint32_t>(m);
+        uint32_t* tc = c.take<uint32_t>(sort_scratch_u32(m ? m : 1));
+        const size_t need = c.off + 256;
+        if (pass == 0) {
+            int rc = ensure_region(x.base, x.cap, need);
+            if (rc) return rc;
+        } else {
+            x.keys = keys; x.ctx_safe = ctx_safe; x.ex_of = ex_of; x.weight = weight; x.iota = iota;
+            x.wk0 = wk0; x.wv0 = wv0; x.wk1 = wk1; x.wv1 = wv1; x.sort_tmp_w = tw;
+            x.ck0 = ck0; x.cv0 = cv0; x.ck1 = ck1; x.cv1 = cv1; x.sort_tmp_c = tc;
+        }
+    }
+    if (!x.ready) HIP_TRY(hipEventCreateWithFlags(&x.ready, hipEventDisableTiming));
+    if (!sh->ev_pfork) HIP_TRY(hipEventCreateWithFlags(&sh->ev_pfork, hipEventDisableTiming));
+    return W2V_OK;
+}
+
+// The index work of an announced bag-of-words minibatch, queued on the third stream behind
+// everything queued on `st` so far.
+int run_cbow_prefetch_chain(w2v_shard* sh, const CbowPrepared& want, hipStream_t st) {
+    const int which = sh->next_cset;
+    CbowSet& x = sh->csets[which];
+    sh->cprep[which].valid = false;
+    const uint32_t n = want.n, k = want.k, m = want.m, M = n * (k + 1);
+    int rc = ensure_cset(sh, x, n, M, m);
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(sh->ev_pfork, st));
+    HIP_TRY(hipStreamWaitEvent(sh->ahead, sh->ev_pfork, 0));
+    hipStream_t ah = sh->ahead;
+    const uint32_t bits = key_bits(sh->V);
+    {
+        Phase ph(sh, W2V_PH_NEG, ah);
+        launch_cbow_entries(want.ctx_off, want.ctx_idx, n, m, sh->V, x.ctx_safe, x.ex_of, x.weight,
+                            sh->err, ah);
+        launch_iota(x.iota, n, ah);
+        launch_dest_keys(NoiseTable{sh->bins, sh->V}, want.out_idx, n, k, want.seed, x.keys, sh->err, ah);
+    }
+    {
+        Phase ph(sh, W2V_PH_SORT, ah);
+        launch_sort_pairs(x.keys, x.wk0, x.wv0, x.wk1, x.wv1, M, bits, x.sort_tmp_w, &x.skw, &x.sidx, ah);
+        if (sh->own_rows) launch_mark_alone(x.skw, x.sidx, M, x.keys, ah);
+        launch_sort_pairs(x.ctx_safe, x.ck0, x.cv0, x.ck1, x.cv1, m, bits, x.sort_tmp_c, &x.skc, &x.cidx, ah);
+    }
+    HIP_TRY(hipEventRecord(x.ready, ah));
+    HIP_TRY(hipGetLastError());
+    CbowPrepared& pr = sh->cprep[which];
+    pr = want;
+    pr.valid = true; pr.own_rows = sh->own_rows;
+    sh->next_cset = which ^ 1;
+    return W2V_OK;
+}
+
+// The set that w2v_cbow_prefetch_minibatch filled for exactly this minibatch, or -1.
+int find_cbow_prepared(const w2v_shard* sh, const uint32_t* ctx_off, const uint32_t* ctx_idx,
+                       uint32_t m, const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed) {
+    for (int i = 0; i < 2; ++i) {
+        const CbowPrepared& pr = sh->cprep[i];
+        if (pr.valid && pr.ctx_off == ctx_off && pr.ctx_idx == ctx_idx && pr.out_idx == out_idx &&
+            pr.n == n && pr.k == k && pr.m == m && pr.seed == seed)
+            return i;
+    }
+    return -1;
+}
+
+// Point the plan at a prepared set (the caller's stream waits for it) ...
+int use_cbow_prepared(w2v_shard* sh, int which, CbowPlan& p, bool spend, bool fused, uint32_t** skw,
+                      uint32_t** sidx, uint32_t** skc, uint32_t** cidx, hipStream_t st) {
+    CbowSet& x = sh->csets[which];
+    if (spend) sh->cprep[which].valid = false;            // a set serves one update
+    HIP_TRY(hipStreamWaitEvent(st, x.ready, 0));
+    p.keys = x.keys; p.ctx_safe = x.ctx_safe; p.ex_of = x.ex_of; p.weight = x.weight; p.iota = x.iota;
+    p.own_rows = fused && sh->cprep[which].own_rows;
+    if (skw) { *skw = x.skw; *sidx = x.sidx; *skc = x.skc; *cidx = x.cidx; }
+    return W2V_OK;
+}
+
+// ... or compute the index work within the call.
+int cbow_indices(w2v_shard* sh, CbowPlan& p, const uint32_t* ctx_off, const uint32_t* ctx_idx,
+                 uint32_t m, const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed,
+                 bool sorts, bool spend, bool fused, uint32_t** skw, uint32_t** sidx, uint32_t** skc,
+                 uint32_t** cidx, bool* prepared, hipStream_t st) {
+    const int ahead = find_cbow_prepared(sh, ctx_off, ctx_idx, m, out_idx, n, k, seed);
+    *prepared = ahead >= 0;
+    if (ahead >= 0) return use_cbow_prepared(sh, ahead, p, spend, fused, skw, sidx, skc, cidx, st);
+    return queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, sorts, skw, sidx, skc, cidx, st);
 }
 
 int check_cbow_pointers(const uint32_t* ctx_off, const uint32_t* ctx_idx, uint32_t m,
@@ -1084,8 +1209,9 @@ extern "C" int w2v_cbow_dotprod(w2v_shard* sh, const uint32_t* ctx_off, const ui
     rc = ensure_ws(sh, sz.bytes);
     if (rc) return rc;
     CbowPlan p = make_cbow_plan(sh->ws, n, k, m, sh->g.stride4, 0, false, false);
-    rc = queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, false, nullptr, nullptr,
-                            nullptr, nullptr, st);
+    bool prepared = false;              // an announced set is used and left for the update
+    rc = cbow_indices(sh, p, ctx_off, ctx_idx, m, out_idx, n, k, seed, false, false, false, nullptr,
+                      nullptr, nullptr, nullptr, &prepared, st);
     if (rc) return rc;
     queue_cbow_hidden(sh, sh, p, ctx_off, st);
     {
@@ -1111,11 +1237,13 @@ extern "C" int w2v_cbow_adjust(w2v_shard* sh, const uint32_t* ctx_off, const uin
     if (rc) return rc;
     CbowPlan p = make_cbow_plan(sh->ws, n, k, m, sh->g.stride4, 0, true, false);
     uint32_t *skw, *sidx, *skc, *cidx;
-    rc = queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, true, &skw, &sidx, &skc, &cidx, st);
+    bool prepared = false;
+    rc = cbow_indices(sh, p, ctx_off, ctx_idx, m, out_idx, n, k, seed, true, true, false, &skw, &sidx,
+                      &skc, &cidx, &prepared, st);
     if (rc) return rc;
     queue_cbow_hidden(sh, sh, p, ctx_off, st);
-    cbow_wait_keys(sh, st);
-    queue_cbow_adjust(sh, sh, p, skw, sidx, skc, cidx, coeffs, nullptr, false, alpha, st);
+    if (!prepared) cbow_wait_keys(sh, st);
+    queue_cbow_adjust(sh, sh, p, skw, sidx, skc, cidx, coeffs, nullptr, false, alpha, !prepared, st);
     HIP_TRY(hipGetLastError());
     return W2V_OK;
 }
@@ -1153,12 +1281,14 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
     CbowPlan p = make_cbow_plan(s0->ws, n, k, m, stride_max, fused ? 0 : S, true, true);
     p.own_rows = fused && s0->own_rows;
     uint32_t *skw, *sidx, *skc, *cidx;
-    rc = queue_cbow_indices(s0, p, ctx_off, ctx_idx, out_idx, k, seed, true, &skw, &sidx, &skc, &cidx, st);
+    bool prepared = false;
+    rc = cbow_indices(s0, p, ctx_off, ctx_idx, m, out_idx, n, k, seed, true, true, fused, &skw, &sidx,
+                      &skc, &cidx, &prepared, st);
     if (rc) return rc;
     if (fused) {
         queue_cbow_hidden(s0, s0, p, ctx_off, st);
-        cbow_wait_keys(s0, st);
-        queue_cbow_adjust(s0, s0, p, skw, sidx, skc, cidx, nullptr, p.coeffs, true, alpha, st);
+        if (!prepared) cbow_wait_keys(s0, st);
+        queue_cbow_adjust(s0, s0, p, skw, sidx, skc, cidx, nullptr, p.coeffs, true, alpha, !prepared, st);
         if (loss) {
             Phase ph(s0, W2V_PH_COEFF, st);
             launch_loss_from_coeffs(p.coeffs, n, p.T, p.loss_tmp, loss, st);
@@ -1170,7 +1300,7 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
         for (uint32_t s = 0; s < S; ++s) {
             float* d = p.dots + (size_t)s * p.M;
             queue_cbow_hidden(s0, shards[s], p, ctx_off, st);
-            cbow_wait_keys(s0, st);
+            if (!prepared) cbow_wait_keys(s0, st);
             Phase ph(s0, W2V_PH_DOT, st);
             launch_dots(p.H, shards[s]->W, shards[s]->g, p.iota, p.keys, n, p.T, d, st);
             pp.p[s] = d;
@@ -1181,11 +1311,30 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
         }
         for (uint32_t s = 0; s < S; ++s) {
             queue_cbow_hidden(s0, shards[s], p, ctx_off, st);
-            queue_cbow_adjust(s0, shards[s], p, skw, sidx, skc, cidx, p.coeffs, nullptr, false, alpha, st);
+            queue_cbow_adjust(s0, shards[s], p, skw, sidx, skc, cidx, p.coeffs, nullptr, false, alpha,
+                              !prepared, st);
         }
     }
     HIP_TRY(hipGetLastError());
     return W2V_OK;
+}
+
+extern "C" int w2v_cbow_prefetch_minibatch(w2v_shard* sh, const uint32_t* ctx_off,
+                                           const uint32_t* ctx_idx, uint32_t m,
+                                           const uint32_t* out_idx, uint32_t n, uint32_t k,
+                                           uint64_t seed, void* stream) {
+    if (!sh) return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_cbow_pointers(ctx_off, ctx_idx, m, out_idx, n);
+    if (!rc) rc = check_device(sh);
+    if (!rc) rc = check_cbow_batch(sh, n, k, m);
+    if (rc) return rc;
+    if (n == 0 || !sh->overlap) return W2V_OK;            // nothing to gain without the other streams
+    rc = ensure_side_stream(sh);
+    if (rc) return rc;
+    CbowPrepared want;
+    want.ctx_off = ctx_off; want.ctx_idx = ctx_idx; want.out_idx = out_idx;
+    want.n = n; want.k = k; want.m = m; want.seed = seed;
+    return run_cbow_prefetch_chain(sh, want, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -37,6 +37,8 @@ _SIGNATURES = {
     "w2v_train_minibatch": (ctypes.c_int, [ctypes.POINTER(c_vp), c_u32, c_vp, c_vp, c_u32, c_u32,
                                            c_u64, ctypes.c_float, c_vp, c_vp]),
     "w2v_prefetch_minibatch": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp]),
+    "w2v_cbow_prefetch_minibatch": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_vp, c_u32, c_u32, c_u64,
+                                                   c_vp]),
     "w2v_make_pairs": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_u32, c_u64, c_u32,
                                       c_vp, c_vp, c_u64, ctypes.POINTER(c_u64), c_vp]),
     "w2v_make_pairs_interleaved": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_u32, c_u64,
@@ -250,6 +252,13 @@ class Shard:
                                      _dev(out_idx, IDX, "out_idx"), out_idx.numel(), int(k), int(seed),
                                      _dev(coeffs, torch.float32, "coeffs"), float(alpha),
                                      _stream(stream)))
+
+    def cbow_prefetch_minibatch(self, ctx_off, ctx_idx, out_idx, k, seed, stream=None):
+        """Index work of a later bag-of-words minibatch, queued beside the calls that follow."""
+        _check(lib().w2v_cbow_prefetch_minibatch(self.h, _dev(ctx_off, IDX, "ctx_off"),
+                                                 _dev(ctx_idx, IDX, "ctx_idx"), ctx_idx.numel(),
+                                                 _dev(out_idx, IDX, "out_idx"), out_idx.numel(),
+                                                 int(k), int(seed), _stream(stream)))
 
     def make_cbow_examples(self, tokens, sent_off, token_base, epoch, corpus_seed, B, ctx_off, ctx_idx,
                            out_idx, stream=None):

@@ -307,3 +307,59 @@ def test_cbow_no_examples_and_no_text():
     assert (n_ex, n_ctx) == (0, 0) and co[0].item() == 0
     sh.status()
     sh.destroy()
+
+
+@pytest.mark.parametrize("S,V,d,k,max_ctx,empty", [(1, 3000, 300, 5, 12, False), (1, 2000, 60, 10, 20, True),
+                                                   (3, 1500, 100, 5, 8, False), (1, 30, 64, 2, 40, True)])
+def test_announced_cbow_minibatches_give_the_same_bits(S, V, d, k, max_ctx, empty):
+    # each minibatch announced one step ahead (w2v_cbow_prefetch_minibatch): the fused step, the
+    # step over several shards and the two calls must give the bits of shards that were told nothing
+    say("announced cbow", S, V, d, k)
+    n, steps = 2049, 4
+    rng = np.random.default_rng(V + S)
+    counts = zipf_counts(V)
+    data = []
+    for _ in range(steps + 1):
+        off, ctx, ctr = examples(V, n, max_ctx, rng, empty=empty)
+        data.append((dev(off), dev(ctx), dev(ctr)))
+    seeds = [w2v.minibatch_seed(4, h) for h in range(steps + 1)]
+    cuts = [(0, d)] if S == 1 else [(0, 20), (20, 50), (70, d - 70)]
+    told = [make_shard(V, w, 5, counts, d_total=d, col_begin=b) for b, w in cuts]
+    plain = [make_shard(V, w, 5, counts, d_total=d, col_begin=b) for b, w in cuts]
+    la, lb = (torch.zeros(1, dtype=torch.float64, device="cuda") for _ in range(2))
+    told[0].cbow_prefetch_minibatch(*data[0], k, seeds[0])
+    for h in range(steps):
+        told[0].cbow_prefetch_minibatch(*data[h + 1], k, seeds[h + 1])
+        w2v.cbow_train_minibatch(told, *data[h], k, seeds[h], 0.02, loss=la)
+        w2v.cbow_train_minibatch(plain, *data[h], k, seeds[h], 0.02, loss=lb)
+        assert la.item() == lb.item()
+    for a, b in zip(told, plain):
+        for which in (0, 1):
+            assert np.array_equal(all_rows(a, which), all_rows(b, which))
+    # the two calls on the first shard: dots from the announced set, then the update spends it;
+    # a mismatching announcement (other seed) is ignored
+    g = torch.from_numpy(workloads.uniform_coeffs(n, k + 1, 9)).cuda()
+    told[0].cbow_prefetch_minibatch(*data[steps], k, seeds[steps] + 1)
+    da = told[0].cbow_dotprod(*data[steps], k, seeds[steps]).cpu().numpy()
+    dp = plain[0].cbow_dotprod(*data[steps], k, seeds[steps]).cpu().numpy()
+    assert np.array_equal(da, dp)
+    told[0].cbow_adjust(*data[steps], k, seeds[steps], g, 0.02)
+    plain[0].cbow_adjust(*data[steps], k, seeds[steps], g, 0.02)
+    for which in (0, 1):
+        assert np.array_equal(all_rows(told[0], which), all_rows(plain[0], which))
+    for s in told + plain:
+        s.status()
+        s.destroy()
+    # and the oracle agrees with the announced fused step
+    if S == 1:
+        sh = make_shard(V, d, 5, counts)
+        U, W = oracle_state(V, d, 5)
+        th, al = oracle.build_alias(counts)
+        for h in range(2):
+            sh.cbow_prefetch_minibatch(*data[h], k, seeds[h])
+            w2v.cbow_train_minibatch([sh], *data[h], k, seeds[h], 0.02)
+            oracle.cbow_train_minibatch([U], [W], *(w2v.index_to_numpy(x) for x in data[h]), k, seeds[h],
+                                        th, al, 0.02)
+        assert vec_error(all_rows(sh, 0), U) <= 2 * TOL1 and vec_error(all_rows(sh, 1), W) <= 2 * TOL1
+        sh.status()
+        sh.destroy()
