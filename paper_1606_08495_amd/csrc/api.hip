@@ -261,7 +261,7 @@ Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_
         const size_t row = (size_t)stride4_max * 4;
         p.delta = c.take<float>((size_t)n * row);
         p.dkey = c.take<uint32_t>(n);
-        p.slots_u1 = slots_after(n, useg_pairs_per_chunk(p.T));
+        p.slots_u1 = slots_after(n, useg_pairs_per_chunk(p.T, 1));    // the most any shard needs
         p.slots_w1 = slots_after(p.M, wseg_entries_per_chunk());
         uint32_t s2u = slots_after(p.slots_u1, tail_entries_per_chunk());
         uint32_t s2w = slots_after(p.slots_w1, tail_entries_per_chunk());
@@ -469,8 +469,9 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
     }
     {
         Phase ph(ws_owner, W2V_PH_APPLY, side);
-        run_tails(sh, sh->U, alpha, p.pa_rows, p.pa_keys, p.slots_u1, p.pe_rows, p.pe_keys, side,
-                  p.delta, p.dkey, useg_pairs_per_chunk(p.T));
+        const uint32_t cp = useg_pairs_per_chunk(p.T, sh->g.d4);      // this shard's chunk size
+        run_tails(sh, sh->U, alpha, p.pa_rows, p.pa_keys, slots_after(p.n, cp), p.pe_rows, p.pe_keys,
+                  side, p.delta, p.dkey, cp);
     }
     join_output_sort(ws_owner, st);
     {
@@ -958,7 +959,7 @@ CbowPlan make_cbow_plan(char* base, uint32_t n, uint32_t k, uint32_t m, uint32_t
         p.ck0 = c.take<uint32_t>(m); p.cv0 = c.take<uint32_t>(m);
         p.ck1 = c.take<uint32_t>(m); p.cv1 = c.take<uint32_t>(m);
         p.sort_tmp_c = c.take<uint32_t>(sort_scratch_u32(m ? m : 1));
-        p.slots_a = slots_after(n, useg_pairs_per_chunk(p.T));
+        p.slots_a = slots_after(n, useg_pairs_per_chunk(p.T, 1));
         p.slots_w1 = slots_after(p.M, wseg_entries_per_chunk());
         p.slots_c1 = slots_after(m, wseg_entries_per_chunk());
         p.slots_2 = std::max(slots_after(p.slots_w1, tail_entries_per_chunk()),

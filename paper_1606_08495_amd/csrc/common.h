@@ -95,7 +95,8 @@ void launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32
 
 // ---- adjust ------------------------------------------------------------------------------------
 // Chunk sizes of the segmented reductions (entries per lane group).
-uint32_t useg_pairs_per_chunk(uint32_t T);
+uint32_t useg_pairs_per_chunk(uint32_t T, uint32_t d4);   // by slots per pair and row geometry;
+                                                          // smallest for the narrowest rows (d4 = 1)
 uint32_t wseg_entries_per_chunk();
 uint32_t tail_entries_per_chunk();
 

@@ -24,10 +24,20 @@ constexpr uint32_t NOKEY = 0xFFFFFFFFu;   // compares unequal to every masked ke
 constexpr uint32_t ALONE = KEY_ALONE;
 
 uint32_t tail_entries_per_chunk() { return TAIL_C; }
-uint32_t useg_pairs_per_chunk(uint32_t T) {     // about 48 entries, 2..16 pairs, <= 136 entries
-    uint32_t c = (48 + T - 1) / T;
+// Pairs per chunk of the input-side kernel: about useg_e(G) entries (pairs x slots), 2..useg_maxp(G)
+// pairs.  Longer chunks cut fewer runs (fewer partial rows for the higher levels: -2.7 % on the
+// benchmark step, -6 % with k = 25, against chunks of 48 entries); with sixteen groups to a block
+// (rows of up to 64 floats) the short chunks stay: there the longer ones measured 1 % slower.
+constexpr int useg_e(int G) { return G == 16 ? 48 : 192; }
+constexpr int useg_maxp(int G) { return G == 16 ? 16 : 32; }            // pairs per chunk, at most
+constexpr int useg_maxe(int G) {                 // entries, at most: c T < E + T, and 2 T, T <= 65
+    return useg_e(G) + 66 < 136 ? 136 : useg_e(G) + 66;
+}
+uint32_t useg_pairs_per_chunk(uint32_t T, uint32_t d4) {
+    const int G = d4 <= 16 ? 16 : (d4 <= 32 ? 32 : 64);                 // as W2V_DISPATCH_GEOM
+    uint32_t c = ((uint32_t)useg_e(G) + T - 1) / T;
     if (c < 2) c = 2;
-    if (c > 16) c = 16;
+    if (c > (uint32_t)useg_maxp(G)) c = useg_maxp(G);
     return c;
 }
 
@@ -442,8 +452,6 @@ void launch_tail(const TailArgs& t, hipStream_t st) {
 // when it is small.
 __device__ __forceinline__ float sigmoid_of_minus(float x) { return 1.0f / (1.0f + expf(x)); }
 
-constexpr int USEG_MAXP = 16;     // pairs per chunk, at most
-constexpr int USEG_MAXE = 136;    // entries (pairs x slots) per chunk, at most
 
 template <int G, int NV, int TB, bool FUSED, bool OWN>
 __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t CP) {
@@ -451,6 +459,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
     constexpr int GROUPS = ADJ_THREADS / G;
     // The chunk's indices are staged in LDS first (two dependent gathers for the whole chunk), so
     // that the row loads of the main loop depend on nothing but LDS reads.
+    constexpr int USEG_MAXE = useg_maxe(G), USEG_MAXP = useg_maxp(G);
     __shared__ uint32_t s_key[GROUPS][USEG_MAXE];                 // output row of every entry
     __shared__ float s_cf[FUSED ? 1 : GROUPS][FUSED ? 1 : USEG_MAXE];   // given coefficients
     __shared__ uint32_t s_pair[GROUPS][USEG_MAXP];                // pair number of every sorted pair
@@ -616,7 +625,7 @@ template <int G, int NV, int T, int PB, bool FUSED, bool OWN>
 __global__ __launch_bounds__(ADJ_THREADS, 5) void useg_multi_kernel(USideArgs a, uint32_t CP) {
     constexpr bool NEED_U = FUSED || OWN;
     constexpr int GROUPS = ADJ_THREADS / G;
-    constexpr int MAXP = 16, MAXE = MAXP * T;
+    constexpr int MAXP = useg_maxp(G), MAXE = MAXP * T;
     __shared__ uint32_t s_key[GROUPS][MAXE];
     __shared__ float s_cf[FUSED ? 1 : GROUPS][FUSED ? 1 : MAXE];
     __shared__ uint32_t s_pair[GROUPS][MAXP];
@@ -781,7 +790,7 @@ static void launch_useg_fixed(const USideArgs& a, uint32_t CP, dim3 grid, dim3 b
 
 template <int G, int NV>
 static void launch_useg_shape(const USideArgs& a, hipStream_t st) {
-    const uint32_t CP = useg_pairs_per_chunk(a.T);
+    const uint32_t CP = useg_pairs_per_chunk(a.T, a.g.d4);
     const uint32_t nchunks = (a.n + CP - 1) / CP;
     dim3 grid(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)), block(ADJ_THREADS);
     if constexpr (NV <= 2) {
