@@ -17,7 +17,12 @@ static inline unsigned blocks_for(uint64_t items, unsigned per_block) {
     return (unsigned)((items + per_block - 1) / per_block);
 }
 
-constexpr int ADJ_THREADS = 256;
+// Block sizes, measured per kernel family: the input-side kernels run 6 % faster in blocks of 128
+// than of 256 (and no faster in 64); the output-side kernel is 7 % slower in 128 at one wavefront
+// per row and 8 % faster at sixteen lanes per row.
+constexpr int ADJ_THREADS = 256;                   // higher levels, write-back
+constexpr int USEG_THREADS = 128;                  // input-side kernels
+constexpr int wown_threads(int G) { return G == 16 ? 128 : 256; }     // output-side kernel
 constexpr int TAIL_C = 16;     // entries per chunk, higher levels (even, so a border's two slots
                                // fall into one chunk)
 constexpr uint32_t NOKEY = 0xFFFFFFFFu;   // compares unequal to every masked key
@@ -223,8 +228,9 @@ enum : uint32_t { ACT_SKIP = 0, ACT_ADD = 1, ACT_COMPLETE = 2, ACT_HEAD = 3 };
 uint32_t wseg_entries_per_chunk() { return WOWN_L; }
 
 template <int G, int NV, int D>
-__global__ __launch_bounds__(ADJ_THREADS) void wown_kernel(SegArgs a) {
-    constexpr int GROUPS = ADJ_THREADS / G;
+__global__ __launch_bounds__(wown_threads(G)) void wown_kernel(SegArgs a) {
+    constexpr int WOWN_THREADS = wown_threads(G);
+    constexpr int GROUPS = WOWN_THREADS / G;
     constexpr int C = WOWN_C, L = WOWN_L;
     static_assert(L % C == 0 && C == 16 && G >= 16, "grid shapes");
     __shared__ uint32_t s_key[GROUPS][WOWN_WIN];
@@ -411,7 +417,8 @@ void launch_wseg(const WSideArgs& w, hipStream_t st) {
     uint32_t nchunks = (w.M + WOWN_C - 1) / WOWN_C;
 #define CALL(G, NV)                                                                              \
     hipLaunchKernelGGL((wown_kernel<G, NV, (NV <= 2 ? 4 : 2)>),                                   \
-                       dim3(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)), dim3(ADJ_THREADS), 0, \
+                       dim3(blocks_for((uint64_t)nchunks * G, wown_threads(G))),                 \
+                       dim3(wown_threads(G)), 0,                                                 \
                        st, a)
     W2V_DISPATCH_GEOM(w.g.d4, CALL);
 #undef CALL
@@ -455,9 +462,9 @@ __device__ __forceinline__ float sigmoid_of_minus(float x) { return 1.0f / (1.0f
 
 
 template <int G, int NV, int TB, bool FUSED, bool OWN>
-__global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t CP) {
+__global__ __launch_bounds__(USEG_THREADS) void useg_kernel(USideArgs a, uint32_t CP) {
     constexpr bool NEED_U = FUSED || OWN;      // the pair's input row: for the dots, for own rows
-    constexpr int GROUPS = ADJ_THREADS / G;
+    constexpr int GROUPS = USEG_THREADS / G;
     // The chunk's indices are staged in LDS first (two dependent gathers for the whole chunk), so
     // that the row loads of the main loop depend on nothing but LDS reads.
     constexpr int USEG_MAXE = useg_maxe(G), USEG_MAXP = useg_maxp(G);
@@ -623,9 +630,9 @@ __global__ __launch_bounds__(ADJ_THREADS) void useg_kernel(USideArgs a, uint32_t
 // 102 registers and run four; held to 96 it spills five and is 1.6 % faster.  (Six: 30 % slower.
 // The same squeeze on the generic kernel or on the output-side kernel costs more than it gives.)
 template <int G, int NV, int T, int PB, bool FUSED, bool OWN>
-__global__ __launch_bounds__(ADJ_THREADS, 5) void useg_multi_kernel(USideArgs a, uint32_t CP) {
+__global__ __launch_bounds__(USEG_THREADS, 5) void useg_multi_kernel(USideArgs a, uint32_t CP) {
     constexpr bool NEED_U = FUSED || OWN;
-    constexpr int GROUPS = ADJ_THREADS / G;
+    constexpr int GROUPS = USEG_THREADS / G;
     constexpr int MAXP = useg_maxp(G), MAXE = MAXP * T;
     __shared__ uint32_t s_key[GROUPS][MAXE];
     __shared__ float s_cf[FUSED ? 1 : GROUPS][FUSED ? 1 : MAXE];
@@ -793,7 +800,7 @@ template <int G, int NV>
 static void launch_useg_shape(const USideArgs& a, hipStream_t st) {
     const uint32_t CP = useg_pairs_per_chunk(a.T, a.g.d4);
     const uint32_t nchunks = (a.n + CP - 1) / CP;
-    dim3 grid(blocks_for((uint64_t)nchunks * G, ADJ_THREADS)), block(ADJ_THREADS);
+    dim3 grid(blocks_for((uint64_t)nchunks * G, USEG_THREADS)), block(USEG_THREADS);
     if constexpr (NV <= 2) {
         if (a.T == 6) return launch_useg_fixed<G, NV, 6>(a, CP, grid, block, st);
     }
