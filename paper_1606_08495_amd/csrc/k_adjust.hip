@@ -109,6 +109,20 @@ __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
         }
     }
     const uint32_t real_limit = (SRC == 0) ? NOKEY : KEY_MASK;   // keys >= this name no row
+    if (SRC == 1) {
+        // Most slots of a level are unused.  No run passes through a chunk of unused slots only:
+        // its own two slots are unused as well, and that is all there is to do.
+        const uint64_t any = __ballot(valid && key < real_limit);
+        const int first_lane = (int)(threadIdx.x % 64) / G * G;
+        const uint64_t group_bits = G >= 64 ? ~0ull : ((1ull << (G & 63)) - 1ull);
+        if (((any >> first_lane) & group_bits) == 0) {
+            if (l == 0) {
+                if (c > 0) a.pkeys[2 * c - 1] = KEY_NONE;
+                if (c + 1 < nchunks) a.pkeys[2 * c] = KEY_NONE;
+            }
+            return;
+        }
+    }
     uint32_t key_prev = NOKEY, key_after = NOKEY;
     if (e0 > 0) { uint32_t r = a.skey[e0 - 1]; key_prev = (SRC == 0) ? r : (r & KEY_MASK); }
     if (e0 + cnt < a.entries) { uint32_t r = a.skey[e0 + cnt]; key_after = (SRC == 0) ? r : (r & KEY_MASK); }
