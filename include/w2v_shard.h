@@ -164,6 +164,10 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
  * minibatch; an update consumes it); otherwise the call computes everything itself as if this call
  * had not been made.  Results are identical either way.  w2v_shard_set_counts voids what was
  * announced before it (the negatives came from the old table).
+ * The two index arrays are read on the shard's own stream, possibly after this call has returned
+ * (the one exception to the rule above that only work queued on `stream` touches the caller's
+ * arrays): keep them allocated and unchanged until the call that uses the prepared work has been
+ * queued on `stream`, or, if no such call follows, until the device has been synchronised.
  * Two minibatches can be held ahead (a third look-ahead replaces the older one); each keeps its own
  * device buffers (about 20 (k+2) n bytes, allocated on first use and reused). */
 int w2v_prefetch_minibatch(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
@@ -215,7 +219,9 @@ int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S, const uint32_
  * shard is this one, a w2v_cbow_dotprod or a w2v_cbow_adjust on this shard with the same three
  * index arrays (same pointers, contents unchanged in between), m, n, k and seed uses the prepared
  * work (the dotprod leaves it in place, an update consumes it); results are identical either way.
- * Two minibatches can be held ahead; w2v_shard_set_counts voids what was announced before it. */
+ * Two minibatches can be held ahead; w2v_shard_set_counts voids what was announced before it.
+ * As there, the three index arrays are read on the shard's own stream: keep them allocated and
+ * unchanged until the call that uses the prepared work has been queued (or the device synchronised). */
 int w2v_cbow_prefetch_minibatch(w2v_shard* shard, const uint32_t* ctx_off_dev,
                                 const uint32_t* ctx_idx_dev, uint32_t m, const uint32_t* out_idx_dev,
                                 uint32_t n, uint32_t k, uint64_t seed, void* stream);
