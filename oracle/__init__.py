@@ -157,6 +157,24 @@ def adjust_rows(U, W, in_idx, rows, coeffs_, alpha, sequential_fp32=False):
                           _p(g), ctypes.c_float(alpha), ctypes.c_int(int(sequential_fp32)))
 
 
+def adjust_deltas(U, W, in_idx, rows, coeffs_, want_u=None, want_w=None):
+    """The adjust routine's scratch sums (double, learning rate not applied) for the listed words
+    (default: every row of U / W); U and W are left as they are.  Returns (dU, dW)."""
+    U, W = _f32(U), _f32(W)
+    in_idx = _u32(in_idx)
+    rows = _u32(rows)
+    g = _f32(coeffs_)
+    n, T = rows.shape
+    want_u = _u32(np.arange(U.shape[0]) if want_u is None else want_u)
+    want_w = _u32(np.arange(W.shape[0]) if want_w is None else want_w)
+    d = U.shape[1]
+    dU = np.empty((want_u.size, d), np.float64)
+    dW = np.empty((want_w.size, d), np.float64)
+    lib().orc_adjust_deltas(_p(U), _p(W), U32(d), _p(in_idx), _p(rows), U64(n), U32(T), _p(g),
+                            _p(want_u), U64(want_u.size), _p(want_w), U64(want_w.size), _p(dU), _p(dW))
+    return dU, dW
+
+
 def adjust(U, W, in_idx, out_idx, k, seed, thresh, alias, coeffs_, alpha):
     assert U.dtype == np.float32 and W.dtype == np.float32
     assert U.flags.c_contiguous and W.flags.c_contiguous

@@ -265,10 +265,13 @@ void orc_coeffs(const float* const* partial, uint32_t S, uint64_t n, uint32_t T,
 // the summed changes are added at the end.  sequential_fp32 != 0 keeps the scratch sums in float
 // (for information; the default double sum is the reference).
 // ---------------------------------------------------------------------------------------------
-void orc_adjust_rows(float* U, float* W, uint32_t d, const uint32_t* in_idx, const uint32_t* rows,
-                     uint64_t n, uint32_t T, const float* coeffs, float alpha,
-                     int sequential_fp32) {
-    std::unordered_map<uint32_t, std::vector<double>> dU, dW;   // the scratch area
+typedef std::unordered_map<uint32_t, std::vector<double>> ScratchArea;   // word -> summed change
+
+// The loop of the adjust routine: fills the scratch area (du per input word, dv per output word)
+// from the start-of-call vectors, touching neither matrix.
+static void adjust_accumulate(const float* U, const float* W, uint32_t d, const uint32_t* in_idx,
+                              const uint32_t* rows, uint64_t n, uint32_t T, const float* coeffs,
+                              int sequential_fp32, ScratchArea& dU, ScratchArea& dW) {
     for (uint64_t p = 0; p < n; ++p) {
         uint32_t wi = in_idx[p];
         const float* u = U + (uint64_t)wi * d;
@@ -291,6 +294,13 @@ void orc_adjust_rows(float* U, float* W, uint32_t d, const uint32_t* in_idx, con
             }
         }
     }
+}
+
+void orc_adjust_rows(float* U, float* W, uint32_t d, const uint32_t* in_idx, const uint32_t* rows,
+                     uint64_t n, uint32_t T, const float* coeffs, float alpha,
+                     int sequential_fp32) {
+    ScratchArea dU, dW;
+    adjust_accumulate(U, W, d, in_idx, rows, n, T, coeffs, sequential_fp32, dU, dW);
     for (auto& kv : dU) {
         float* u = U + (uint64_t)kv.first * d;
         for (uint32_t c = 0; c < d; ++c) u[c] = (float)((double)u[c] + (double)alpha * kv.second[c]);
@@ -298,6 +308,25 @@ void orc_adjust_rows(float* U, float* W, uint32_t d, const uint32_t* in_idx, con
     for (auto& kv : dW) {
         float* v = W + (uint64_t)kv.first * d;
         for (uint32_t c = 0; c < d; ++c) v[c] = (float)((double)v[c] + (double)alpha * kv.second[c]);
+    }
+}
+
+// Read-only view of the adjust routine's scratch area: the summed changes du, dv (double, before the
+// learning rate is applied) of the listed words, zero for a word the minibatch does not touch.
+// want_u[mu], want_w[mw] are word indices; dU_out is [mu][d], dW_out is [mw][d].  Changes nothing.
+void orc_adjust_deltas(const float* U, const float* W, uint32_t d, const uint32_t* in_idx,
+                       const uint32_t* rows, uint64_t n, uint32_t T, const float* coeffs,
+                       const uint32_t* want_u, uint64_t mu, const uint32_t* want_w, uint64_t mw,
+                       double* dU_out, double* dW_out) {
+    ScratchArea dU, dW;
+    adjust_accumulate(U, W, d, in_idx, rows, n, T, coeffs, 0, dU, dW);
+    for (uint64_t i = 0; i < mu; ++i) {
+        auto it = dU.find(want_u[i]);
+        for (uint32_t c = 0; c < d; ++c) dU_out[i * d + c] = it == dU.end() ? 0.0 : it->second[c];
+    }
+    for (uint64_t i = 0; i < mw; ++i) {
+        auto it = dW.find(want_w[i]);
+        for (uint32_t c = 0; c < d; ++c) dW_out[i * d + c] = it == dW.end() ? 0.0 : it->second[c];
     }
 }
 

@@ -366,3 +366,36 @@ def test_lazy_store_matches_dense_store():
     for r in range(0, V, 7):
         assert np.array_equal(lazy.row(0, r), U[r]) and np.array_equal(lazy.row(1, r), W[r])
     lazy.close()
+
+
+def test_scratch_sums_match_a_brute_force_loop_and_the_applied_update():
+    """oracle.adjust_deltas hands out the adjust routine's scratch area (Appendix, adjust: the summed
+    changes before they are added to the store).  Pin: an independent loop written here, and the
+    update that adjust_rows applies from the same sums."""
+    rng = np.random.default_rng(17)
+    V, d, n, T = 23, 7, 160, 4
+    U, W = rand_model(rng, V, d)
+    in_idx = rng.integers(0, V - 2, n).astype(np.uint32)        # words V-2, V-1 are never inputs
+    rows = rng.integers(0, V, (n, T)).astype(np.uint32)
+    g = (rng.random((n, T)) * 2 - 1).astype(np.float32)
+    U_before, W_before = U.copy(), W.copy()
+    dU, dW = oracle.adjust_deltas(U, W, in_idx, rows, g)
+    assert np.array_equal(U, U_before) and np.array_equal(W, W_before)      # read-only
+    bU, bW = np.zeros((V, d)), np.zeros((V, d))
+    for p in range(n):
+        for j in range(T):
+            bU[in_idx[p]] += float(g[p, j]) * W[rows[p, j]].astype(np.float64)
+            bW[rows[p, j]] += float(g[p, j]) * U[in_idx[p]].astype(np.float64)
+    np.testing.assert_allclose(dU, bU, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dW, bW, rtol=0, atol=1e-12)
+    # a word the minibatch never names has a zero sum; a subset is the matching rows of the whole
+    unused = np.setdiff1d(np.arange(V), in_idx)
+    assert unused.size > 0 and not dU[unused].any()
+    sU, sW = oracle.adjust_deltas(U, W, in_idx, rows, g, want_u=[5, 0, 5], want_w=[22])
+    assert np.array_equal(sU, dU[[5, 0, 5]]) and np.array_equal(sW, dW[[22]])
+    # and these are the sums that adjust_rows adds: new = fl(old + alpha * sum)
+    alpha = np.float32(0.05)
+    U1, W1 = U.copy(), W.copy()
+    oracle.adjust_rows(U1, W1, in_idx, rows, g, alpha)
+    assert np.array_equal(U1, (U.astype(np.float64) + float(alpha) * dU).astype(np.float32))
+    assert np.array_equal(W1, (W.astype(np.float64) + float(alpha) * dW).astype(np.float32))
