@@ -103,6 +103,13 @@ uint32_t negative(uint64_t seed, uint32_t p, uint32_t j, uint32_t w_out, uint32_
 
 double sigmoid(double x) { return 1.0 / (1.0 + std::exp(-x)); }
 
+// log sigma(x), the term of the objective (Eq.1; log(1 - sigma(x)) is log sigma(-x)).  Written as
+// -log(1 + e^-x) on the side where e^-x is small and as x - log(1 + e^x) on the other, it is the
+// same function as log(sigmoid(x)) but stays finite and accurate when sigma saturates.
+double log_sigmoid(double x) {
+    return x >= 0.0 ? -std::log1p(std::exp(-x)) : x - std::log1p(std::exp(x));
+}
+
 }  // namespace
 
 extern "C" {
@@ -253,8 +260,8 @@ void orc_coeffs(const float* const* partial, uint32_t S, uint64_t n, uint32_t T,
             double f = 0.0;
             for (uint32_t s = 0; s < S; ++s) f += (double)partial[s][p * T + j];
             double sg = sigmoid(f);
-            if (j == 0) { coeffs[p * T + j] = (float)(1.0 - sg); total_loss -= std::log(sg); }
-            else        { coeffs[p * T + j] = (float)(-sg);      total_loss -= std::log(1.0 - sg); }
+            if (j == 0) { coeffs[p * T + j] = (float)(1.0 - sg); total_loss -= log_sigmoid(f); }
+            else        { coeffs[p * T + j] = (float)(-sg);      total_loss -= log_sigmoid(-f); }
         }
     }
     if (loss) *loss = total_loss;

@@ -14,7 +14,7 @@ import torch
 
 import oracle
 from paper_1606_08495_amd import w2v, workloads
-from util import dev, dot_error, vec_error
+from util import delta_error, dev, dot_error, vec_error, vec_error_elem
 
 pytestmark = pytest.mark.gpu
 TOL1 = 1e-5
@@ -47,7 +47,9 @@ def sample_rows(ids, n_hot, n_cold, rng):
 
 
 def check_sampled_update(sh, wl, in_idx, rows, coeffs, alpha, init_w, samp_u, samp_w):
-    """Oracle adjust on every pair touching a sampled row; compares those rows with the shard's."""
+    """Oracle adjust on every pair touching a sampled row; compares those rows with the shard's:
+    the updated rows, and the change itself ((after - before) / alpha against the oracle's summed
+    change; the shard started from the initial values, which the oracle reproduces bit for bit)."""
     sel = np.isin(in_idx, samp_u) | np.isin(rows, samp_w).any(axis=1)
     ii, rr = in_idx[sel], rows[sel]
     say("   sub-minibatch of", int(sel.sum()), "pairs for", samp_u.size, "+", samp_w.size, "rows")
@@ -56,11 +58,16 @@ def check_sampled_update(sh, wl, in_idx, rows, coeffs, alpha, init_w, samp_u, sa
         g = oracle.coeffs([oracle.dots(U, W, cin, cr)])
     else:
         g = coeffs[sel]
+    at_u, at_w = np.searchsorted(words_u, samp_u), np.searchsorted(words_w, samp_w)
+    dU, dW = oracle.adjust_deltas(U, W, cin, cr, g, want_u=at_u, want_w=at_w)
+    U0, W0 = U[at_u].copy(), W[at_w].copy()
     oracle.adjust_rows(U, W, cin, cr, g, alpha)
     gu = sh.get_rows(0, dev(samp_u)).cpu().numpy()
     gw = sh.get_rows(1, dev(samp_w)).cpu().numpy()
-    ru = U[np.searchsorted(words_u, samp_u)]
-    rw = W[np.searchsorted(words_w, samp_w)]
+    ru, rw = U[at_u], W[at_w]
+    du, dw = delta_error(gu, U0, alpha, dU), delta_error(gw, W0, alpha, dW)
+    say("   change of U", du, "of W", dw, "| element-relative", vec_error_elem(gu, ru), vec_error_elem(gw, rw))
+    assert du <= TOL1 and dw <= TOL1, (du, dw)
     return vec_error(gu, ru), vec_error(gw, rw)
 
 
@@ -225,11 +232,80 @@ def reduced_n_step(name, n, n_tokens):
     sh.destroy()
 
 
+def streamed_input_row_change(wl, in_idx, rows, word, chunk=1 << 15):
+    """The oracle's summed change (double) of input row `word`: every pair that names it as its input
+    word, handed to the oracle in chunks over a compacted copy of the output rows those pairs touch
+    (initial values from the counter-based recipe); the chunks' sums are added in double."""
+    sel = np.flatnonzero(in_idx == word)
+    U = oracle.init_rows(wl.seed, wl.d_total, wl.col_begin, wl.d_slice, 0, np.array([word], np.uint32))
+    total = np.zeros(wl.d_slice)
+    none = np.zeros(0, np.uint32)
+    for lo in range(0, sel.size, chunk):
+        rr = rows[sel[lo:lo + chunk]]
+        words_w, cr = np.unique(rr.ravel(), return_inverse=True)
+        W = oracle.init_rows(wl.seed, wl.d_total, wl.col_begin, wl.d_slice, 1, words_w.astype(np.uint32))
+        cr = cr.reshape(rr.shape).astype(np.uint32)
+        cin = np.zeros(rr.shape[0], np.uint32)
+        g = oracle.coeffs([oracle.dots(U, W, cin, cr)])
+        dU, _ = oracle.adjust_deltas(U, W, cin, cr, g, want_u=[0], want_w=none)
+        total += dU[0]
+    return total, sel.size
+
+
+def streamed_output_row_change(wl, in_idx, rows, word, chunk=1 << 17):
+    """The same for output row `word`: every SLOT that names it.  A slot in column 0 (the word as the
+    positive output word) goes to the oracle as a pair without negatives; a slot in a column j > 0
+    (the word as a negative) as a pair [its own positive word, `word`] with one negative, whose
+    second column carries the slot's coefficient -sigma and its change -- the positive word of such
+    a pair is never `word` itself (negatives differ from it), so nothing else lands in the row."""
+    total = np.zeros(wl.d_slice)
+    slots = 0
+    none = np.zeros(0, np.uint32)
+    for col0 in (True, False):
+        if col0:
+            pp = np.flatnonzero(rows[:, 0] == word)
+            sub_rows = np.full((pp.size, 1), word, np.uint32)
+        else:
+            pp, jj = np.nonzero(rows[:, 1:] == word)
+            assert not np.any(rows[pp, 0] == word)
+            sub_rows = np.stack([rows[pp, 0], np.full(pp.size, word, np.uint32)], axis=1)
+        slots += pp.size
+        for lo in range(0, pp.size, chunk):
+            ii, rr = in_idx[pp[lo:lo + chunk]], sub_rows[lo:lo + chunk]
+            words_u, cin = np.unique(ii, return_inverse=True)
+            words_w, cr = np.unique(rr.ravel(), return_inverse=True)
+            U = oracle.init_rows(wl.seed, wl.d_total, wl.col_begin, wl.d_slice, 0, words_u.astype(np.uint32))
+            W = oracle.init_rows(wl.seed, wl.d_total, wl.col_begin, wl.d_slice, 1, words_w.astype(np.uint32))
+            cr = cr.reshape(rr.shape).astype(np.uint32)
+            g = oracle.coeffs([oracle.dots(U, W, cin.astype(np.uint32), cr)])
+            at = np.searchsorted(words_w, [word])
+            _, dW = oracle.adjust_deltas(U, W, cin.astype(np.uint32), cr, g, want_u=none, want_w=at)
+            total += dW[0]
+    return total, slots
+
+
+def check_hottest_rows(sh, wl, in_idx, rows, alpha):
+    """The most frequent input word and the most frequently named output row of the minibatch --
+    the rows whose contributions pass through every level of the reduction -- against the oracle."""
+    for which, ids, fn in ((0, in_idx, streamed_input_row_change), (1, rows.ravel(), streamed_output_row_change)):
+        vals, cnt = np.unique(ids, return_counts=True)
+        word = int(vals[np.argmax(cnt)])
+        change, m = fn(wl, in_idx, rows, word)
+        before = oracle.init_rows(wl.seed, wl.d_total, wl.col_begin, wl.d_slice, which, np.array([word], np.uint32))
+        ref = (before.astype(np.float64) + float(np.float32(alpha)) * change[None]).astype(np.float32)
+        got = sh.get_rows(which, dev(np.array([word], np.uint32))).cpu().numpy()
+        e, de = vec_error(got, ref), delta_error(got, before, alpha, change[None])
+        say("   hottest", "input" if which == 0 else "output", "row: word", word, "with", m,
+            "contributions" if which else "pairs", "| row error", e, "| change", de)
+        assert e <= TOL1 and de <= TOL1, (which, word, e, de)
+
+
 def full_n_step(name, n_tokens):
     """The benchmark's own launch configuration (full vocabulary, dimension, k and n): pairs and
     negatives compared in full; updated rows compared on sampled rows that collect few
-    contributions (for those the oracle can be given every pair that touches them); the whole step
-    repeated on a fresh shard must give the same bits, hottest rows included."""
+    contributions (for those the oracle can be given every pair that touches them) and on the
+    hottest input row and the hottest output row (the oracle streams through every pair / slot that
+    names them); the whole step repeated on a fresh shard must give the same bits."""
     wl = workloads.WORKLOADS[name]
     n = wl.n_pairs
     rng = np.random.default_rng(23)
@@ -277,6 +353,7 @@ def full_n_step(name, n_tokens):
     eu, ew = check_sampled_update(sh, wl, in_idx, rows, None, wl.alpha, True, samp_u, samp_w)
     say("   U error", eu, "W error", ew)
     assert eu <= TOL1 and ew <= TOL1
+    check_hottest_rows(sh, wl, in_idx, rows, wl.alpha)
     hot_u = sample_rows(in_idx, 8, 100, rng)
     hot_w = sample_rows(out_idx, 8, 300, rng)
     keep = [sh.get_rows(0, dev(x)).cpu().numpy() for x in (samp_u, hot_u)] + \

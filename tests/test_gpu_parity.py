@@ -8,12 +8,34 @@ import torch
 
 import oracle
 from paper_1606_08495_amd import w2v, workloads
-from util import all_rows, dev, dot_error, set_all_rows, vec_error, zipf_counts
+from util import all_rows, delta_error, dev, dot_error, set_all_rows, vec_error, vec_error_elem, zipf_counts
 
 pytestmark = pytest.mark.gpu
 
 TOL1 = 1e-5
 TOL100 = 1e-3
+TOL_ELEM = 1e-4     # element-relative measure (floor 1e-2 of the row's largest): reported, loosely bounded
+
+
+def step_rows(out_idx, k, seed, th, al):
+    """[n][k+1] output rows of a minibatch: the positive word, then the oracle's negatives."""
+    return np.concatenate([out_idx[:, None], oracle.negatives(out_idx, k, seed, th, al)], axis=1)
+
+
+def oracle_step_deltas(U, W, in_idx, out_idx, k, seed, th, al):
+    """The summed changes (double) that one oracle training step would add, times 1/alpha."""
+    rows = step_rows(out_idx, k, seed, th, al)
+    g = oracle.coeffs([oracle.dots(U, W, in_idx, rows)])
+    return oracle.adjust_deltas(U, W, in_idx, rows, g)
+
+
+def safe_alpha(n, k, p_top, alpha_max=0.05):
+    """A learning rate under which one minibatch moves the most frequently named row by about a
+    tenth of itself at most (coefficients are about a half, vectors of about equal length), so that
+    small vocabularies do not diverge, and no smaller than that, so that updates stay far above the
+    tolerance."""
+    m_top = max(1.0, n * (k + 1) * p_top)
+    return float(min(alpha_max, 0.2 / m_top))
 
 
 def say(*a):
@@ -149,10 +171,17 @@ def run_adjust_case(V, d, n, k, in_idx, out_idx, seed=77, alpha=0.025, label="")
     U, W = oracle_state(V, d, 31)
     th, al = oracle.build_alias(counts)
     g = workloads.uniform_coeffs(n, k + 1, seed)
+    dU, dW = oracle.adjust_deltas(U, W, in_idx, step_rows(out_idx, k, seed, th, al), g)
+    U0, W0 = U.copy(), W.copy()
     sh.adjust(dev(in_idx), dev(out_idx), k, seed, torch.from_numpy(g).cuda(), alpha)
     oracle.adjust(U, W, in_idx, out_idx, k, seed, th, al, g, alpha)
-    eu, ew = vec_error(all_rows(sh, 0), U), vec_error(all_rows(sh, 1), W)
-    say("  adjust", label, "U error", eu, "W error", ew)
+    gU, gW = all_rows(sh, 0), all_rows(sh, 1)
+    eu, ew = vec_error(gU, U), vec_error(gW, W)
+    du, dw = delta_error(gU, U0, alpha, dU), delta_error(gW, W0, alpha, dW)
+    say("  adjust", label, "U error", eu, "W error", ew, "| change of U", du, "of W", dw,
+        "| element-relative", vec_error_elem(gU, U), vec_error_elem(gW, W))
+    assert du <= TOL1 and dw <= TOL1, (du, dw)
+    assert vec_error_elem(gU, U) <= TOL_ELEM and vec_error_elem(gW, W) <= TOL_ELEM
     sh.status()
     sh.destroy()
     return eu, ew
@@ -253,18 +282,28 @@ def test_train_minibatch_parity_one_shard(V, d, n, k, mode):
     U, W = oracle_state(V, d, 21, init_mode=mode)
     th, al = oracle.build_alias(counts)
     loss = torch.zeros(1, dtype=torch.float64, device="cuda")
-    alpha = 0.05 if V > 100 else 1e-5      # a handful of words hit 10^5 times each would diverge
+    # (a handful of words named 10^5 times each would diverge under the usual learning rate; a
+    # single pair must still move its rows by far more than the tolerance)
+    alpha = safe_alpha(n, k, 1.0 / V)
     for h in range(2):
         in_idx = rng.integers(0, V, n).astype(np.uint32)
         out_idx = rng.integers(0, V, n).astype(np.uint32)
         seed = w2v.minibatch_seed(5, h)
         assert seed == oracle.minibatch_seed(5, h)
+        gU0, gW0 = all_rows(sh, 0), all_rows(sh, 1)
+        dU, dW = oracle_step_deltas(U, W, in_idx, out_idx, k, seed, th, al)
         w2v.train_minibatch([sh], dev(in_idx), dev(out_idx), k, seed, alpha, loss=loss)
         ref_loss = oracle.train_minibatch([U], [W], in_idx, out_idx, k, seed, th, al, alpha)
         assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss)
-    eu, ew = vec_error(all_rows(sh, 0), U), vec_error(all_rows(sh, 1), W)
-    say("  errors", eu, ew)
+        # the change of this minibatch alone, from the shard's own rows before it
+        gU, gW = all_rows(sh, 0), all_rows(sh, 1)
+        du, dw = delta_error(gU, gU0, alpha, dU), delta_error(gW, gW0, alpha, dW)
+        say("  minibatch", h, "alpha", alpha, "change of U", du, "of W", dw)
+        assert du <= (h + 1) * TOL1 and dw <= (h + 1) * TOL1
+    eu, ew = vec_error(gU, U), vec_error(gW, W)
+    say("  errors", eu, ew, "element-relative", vec_error_elem(gU, U), vec_error_elem(gW, W))
     assert eu <= 2 * TOL1 and ew <= 2 * TOL1      # two minibatches
+    assert vec_error_elem(gU, U) <= TOL_ELEM and vec_error_elem(gW, W) <= TOL_ELEM
     sh.status()
     sh.destroy()
 
@@ -543,15 +582,20 @@ def test_random_shapes_skipgram_and_bag_of_words(case):
     dt = sum(widths)
     begins = np.concatenate([[0], np.cumsum(widths)[:-1]])
     cdf = workloads.zipf_cdf(V, skew)
-    alpha = 0.02 if V >= 100 else 1e-4
+    alpha = safe_alpha(n, k, float(cdf[0]), 0.02)
     for variant in ("sgns", "cbow"):
         shards = [make_shard(V, w, 31, counts, d_total=dt, col_begin=int(b)) for w, b in zip(widths, begins)]
         st = [oracle_state(V, w, 31, dt, int(b)) for w, b in zip(widths, begins)]
         Us, Ws = [a for a, _ in st], [b for _, b in st]
         out = workloads.zipf_draw(cdf, n, rng)
         loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+        deltas = None
         if variant == "sgns":
             inn = workloads.zipf_draw(cdf, n, rng)
+            rows = step_rows(out, k, 4242, th, al)
+            g = oracle.coeffs([oracle.dots(Us[s], Ws[s], inn, rows) for s in range(S)])
+            deltas = [oracle.adjust_deltas(Us[s], Ws[s], inn, rows, g) for s in range(S)]
+            before = [(Us[s].copy(), Ws[s].copy()) for s in range(S)]     # = the shards' initial rows
             w2v.train_minibatch(shards, dev(inn), dev(out), k, 4242, alpha, loss=loss)
             ref = oracle.train_minibatch(Us, Ws, inn, out, k, 4242, th, al, alpha)
         else:
@@ -562,8 +606,13 @@ def test_random_shapes_skipgram_and_bag_of_words(case):
             ref = oracle.cbow_train_minibatch(Us, Ws, off, ctx, out, k, 4242, th, al, alpha)
         assert abs(loss.item() - ref) <= 1e-5 * abs(ref) + 1e-12
         for s in range(S):
-            eu, ew = vec_error(all_rows(shards[s], 0), Us[s]), vec_error(all_rows(shards[s], 1), Ws[s])
+            gU, gW = all_rows(shards[s], 0), all_rows(shards[s], 1)
+            eu, ew = vec_error(gU, Us[s]), vec_error(gW, Ws[s])
             assert eu <= TOL1 and ew <= TOL1, (variant, s, eu, ew)
+            if deltas is not None:
+                du = delta_error(gU, before[s][0], alpha, deltas[s][0])
+                dw = delta_error(gW, before[s][1], alpha, deltas[s][1])
+                assert du <= TOL1 and dw <= TOL1, (variant, s, du, dw)
             shards[s].status()
             shards[s].destroy()
 

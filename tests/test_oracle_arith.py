@@ -335,6 +335,23 @@ def test_coefficients_are_label_minus_sigmoid_of_the_summed_partials():
     assert np.all(np.isfinite(c)) and c[0, 0] >= 0 and c[0, 1] == -1.0 and c[1, 0] == 1.0
 
 
+def test_loss_stays_finite_and_exact_when_sigma_saturates():
+    """-log sigma(x) = log(1 + e^-x): for x = -60 that is 60 + e^-60, for x = +60 it is
+    log1p(e^-60) = e^-60 to first order (e^-60 = 8.7565107626965203e-27); a negative slot's term
+    -log(1 - sigma(x)) is the same function of -x."""
+    tiny = 8.7565107626965203e-27
+    for x, slot, want in ((-60.0, 0, 60.0), (60.0, 0, tiny), (60.0, 1, 60.0), (-60.0, 1, tiny),
+                          (-700.0, 0, 700.0), (800.0, 1, 800.0), (0.0, 0, math.log(2.0))):
+        if slot == 0:                               # a pair without negatives: the loss is the term
+            _, loss = oracle.coeffs([np.full((1, 1), x, np.float32)], want_loss=True)
+            assert abs(loss - want) <= 1e-12 * want, (x, loss)
+        else:                                       # the positive slot's zero dot adds log 2
+            f = np.zeros((1, 2), np.float32)
+            f[0, 1] = x
+            _, loss = oracle.coeffs([f], want_loss=True)
+            assert math.isfinite(loss) and abs((loss - math.log(2.0)) - want) <= 1e-12 * max(want, 1.0), (x, loss)
+
+
 def test_sequential_float_mode_differs_only_by_rounding():
     rng = np.random.default_rng(15)
     V, d, n, k = 12, 6, 400, 2
