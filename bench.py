@@ -96,6 +96,38 @@ class PairStream:
         return self.a[self.pos:self.pos + n], self.b[self.pos:self.pos + n]
 
 
+def host_cpu():
+    """CPU model, sockets and cores of the box the oracle is timed on (from /proc/cpuinfo)."""
+    model, phys, cores_per, logical = "unknown", set(), {}, 0
+    try:
+        cur = None
+        for line in open("/proc/cpuinfo"):
+            key, _, val = line.partition(":")
+            key, val = key.strip(), val.strip()
+            if key == "processor":
+                logical += 1
+            elif key == "model name":
+                model = val
+            elif key == "physical id":
+                cur = val
+                phys.add(val)
+            elif key == "cpu cores" and cur is not None:
+                cores_per[cur] = int(val)
+    except OSError:
+        pass
+    sockets = max(1, len(phys))
+    cores = sum(cores_per.values()) if cores_per else logical
+    return {"model": model, "sockets": sockets, "cores_total": cores, "logical_cpus": logical,
+            "visible_to_process": len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else logical}
+
+
+def step_time_stats(torch, events):
+    """Median, minimum and mean of the per-step times between consecutive events (ms)."""
+    ms = [events[i].elapsed_time(events[i + 1]) for i in range(len(events) - 1)]
+    return {"ms_per_step_median": float(np.median(ms)), "ms_per_step_min": float(np.min(ms)),
+            "ms_per_step_mean_events": float(np.mean(ms))}
+
+
 def cpu_baseline_full(wl, counts, in_idx, out_idx, seed, sample_pairs):
     import oracle
     th, al = oracle.build_alias(counts)
@@ -105,7 +137,7 @@ def cpu_baseline_full(wl, counts, in_idx, out_idx, seed, sample_pairs):
     lazy.train_minibatch(in_idx[:m], out_idx[:m], wl.k, seed, th, al, wl.alpha)
     dt = time.perf_counter() - t0
     lazy.close()
-    return {"value": m / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle",
+    return {"value": m / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle", "host": host_cpu(),
             "sample": "first %d pairs of minibatch 0 of workload %s, oracle train_minibatch on "
                       "lazily initialised rows, %.1f s" % (m, wl.name, dt)}
 
@@ -128,7 +160,7 @@ def cpu_baseline_slice(wl, counts, in_idx, out_idx, coeffs, seed, sample_pairs):
     oracle.negatives(oo, wl.k, seed, th, al)
     oracle.adjust_rows(U, W, ci, cr, coeffs[:m], wl.alpha)
     dt = time.perf_counter() - t0
-    return {"value": m / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle",
+    return {"value": m / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle", "host": host_cpu(),
             "sample": "first %d pairs of the minibatch of workload %s, oracle dotprod + adjust on "
                       "the touched rows, %.1f s" % (m, wl.name, dt)}
 
@@ -349,6 +381,7 @@ def run_cbow(args, torch, w2v, workloads):
         oracle.cbow_adjust_rows(U, W, co, cc, cr, g, wl.alpha)
         dtc = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": e / dtc, "unit": "examples/s", "cores": 1, "kind": "oracle",
+                               "host": host_cpu(),
                                "sample": "first %d examples of minibatch 0, oracle cbow dots + "
                                          "coefficients + adjust on the touched rows, %.1f s" % (e, dtc)}
     sh.destroy()
@@ -403,6 +436,7 @@ def run_topk(args, torch, w2v, workloads):
         dtc = time.perf_counter() - t0
         gi = w2v.index_to_numpy(out[0][:m])
         res["cpu_baseline"] = {"value": m / dtc, "unit": "queries/s", "cores": 1, "kind": "oracle",
+                               "host": host_cpu(),
                                "sample": "first %d queries against all %d candidates, %.1f s; %d of %d "
                                          "indices equal the GPU's" % (m, N, dtc, int((gi == oi).sum()), m * K)}
     print(json.dumps(res), flush=True)
@@ -564,12 +598,16 @@ def main():
         sh.timing_enable(True)
         sh.timing_read()
         torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
         t0 = time.perf_counter()
+        marks[0].record()
         last = None
         for h in range(Wm, total_steps):
             last = step(h)
+            marks[h - Wm + 1].record()      # every stream of the step has joined the caller's by now
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        result_extra.update(step_time_stats(torch, marks))
         phases = sh.timing_read()
         sh.timing_enable(False)
         sh.status()
@@ -606,11 +644,15 @@ def main():
         sh.timing_enable(True)
         sh.timing_read()
         torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
         t0 = time.perf_counter()
+        marks[0].record()
         for h in range(Wm, total_steps):
             step(h)
+            marks[h - Wm + 1].record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        result_extra.update(step_time_stats(torch, marks))
         phases = sh.timing_read()
         sh.timing_enable(False)
         sh.status()
@@ -639,6 +681,19 @@ def main():
         "uside": n * (T + (1 if fused else 0)) * R + 8 * M + 8 * n + du * R + single * R,
         "wside": (M - single) * R + 12 * M + 2 * (dw - single) * R,
     }
+    # ---- compulsory bytes: what a launch would move if every DISTINCT row crossed the memory
+    # interface once per direction (no re-read of a row named several times is counted; index and
+    # coefficient arrays are streamed once either way).  A lower bound on the HBM traffic of the
+    # launch; the logical figure above is what the kernel asks of the memory system, caches included.
+    #   dot   : the distinct input and output rows, read
+    #   uside : the distinct output rows (+ the distinct input rows when fused), read; one delta row
+    #           per distinct input row and the rows named once, written
+    #   wside : the distinct input rows, read; every other distinct output row read and written
+    compulsory = {
+        "dot": (du + dw) * R + 8 * M,
+        "uside": (dw + (du if fused else 0)) * R + (du + single) * R + 8 * M + 8 * n,
+        "wside": du * R + 2 * (dw - single) * R + 12 * M,
+    }
     per_phase = {}
     for name, (ms, cnt) in phases.items():
         if cnt:
@@ -647,14 +702,22 @@ def main():
               per_phase[p]["launches"])
     dom_ms = per_phase[dom]["ms_per_launch"]
     achieved = algo[dom] / (dom_ms * 1e-3) / 1e9
-    traffic = None          # L2<->fabric bytes per launch, from the committed rocprofv3 counter summary
+    compulsory_gbs = compulsory[dom] / (dom_ms * 1e-3) / 1e9
+    # L2<->fabric bytes per launch: NOT measured in this run -- read from the committed rocprofv3
+    # counter summary of the same command (counters and timing cannot share a run)
+    traffic, traffic_source = None, None
     tfile = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % wl.name)
     if os.path.exists(tfile):
         for line in open(tfile):
             parts = line.split()
             if len(parts) == 3 and parts[0] == "traffic" and parts[1] == dom:
                 traffic = float(parts[2])
+                traffic_source = "profiles/%s_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE " \
+                                 "of this command in a run of its own; L2<->fabric, an upper bound on " \
+                                 "HBM bytes)" % wl.name
     step_algo = 3 * (wl.k + 2) * R * n      # the paper-style logical figure: 3 (k+2) rows per pair
+    # the whole step at its least: every distinct row of either matrix read once and written once
+    step_compulsory = 2 * (du + dw) * R + 8 * n + (4 * M if not fused else 0)
     out = {
         "metric": "SGNS training pairs/s (k negatives incl.) on 1 MI355X",
         "value": pairs_per_s,
@@ -678,8 +741,17 @@ def main():
         "roofline": {"bound": "hbm", "kernel": KERNEL_OF_PHASE.get(dom, dom), "phase": dom,
                      "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": algo[dom], "ms_per_launch": dom_ms},
+                     "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": algo[dom], "ms_per_launch": dom_ms,
+                     "compulsory_bytes_per_launch": compulsory[dom],
+                     "compulsory_GBps": compulsory_gbs,
+                     "compulsory_frac": compulsory_gbs / HBM_PEAK_GBS,
+                     "hbm_frac_bracket": [compulsory_gbs / HBM_PEAK_GBS,
+                                          (traffic / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if traffic
+                                          else achieved / HBM_PEAK_GBS]},
         "step_logical_GBps": step_algo / (ms_per_step * 1e-3) / 1e9,
+        "step_compulsory_GBps": step_compulsory / (ms_per_step * 1e-3) / 1e9,
+        "step_compulsory_frac": step_compulsory / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "phases": per_phase,
     }
     out.update(result_extra)

@@ -90,8 +90,8 @@ int w2v_shard_get_rows(w2v_shard* shard, int which, const uint32_t* rows_dev, ui
 int w2v_shard_set_rows(w2v_shard* shard, int which, const uint32_t* rows_dev, uint32_t m,
                        const float* src_dev, void* stream);
 
-/* Waits for `stream`, then reports and clears the sticky bad-index flag (W2V_ERR_INDEX) or a pending
- * HIP error. */
+/* Waits for `stream` and for the shard's own streams (announced minibatches are checked there), then
+ * reports and clears the sticky bad-index flag (W2V_ERR_INDEX) or a pending HIP error. */
 int w2v_shard_status(w2v_shard* shard, void* stream);
 
 /* ---- negatives (Appendix, dotprod / adjust: N word indices other than the positive output word) -
@@ -169,9 +169,19 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
  * arrays): keep them allocated and unchanged until the call that uses the prepared work has been
  * queued on `stream`, or, if no such call follows, until the device has been synchronised.
  * Two minibatches can be held ahead (a third look-ahead replaces the older one); each keeps its own
- * device buffers (about 20 (k+2) n bytes, allocated on first use and reused). */
+ * device buffers (about 20 (k+2) n bytes, allocated on first use and reused).  An announcement serves
+ * one of the next two update calls on the shard; after that it is void (w2v_prefetch_cancel). */
 int w2v_prefetch_minibatch(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
                            uint32_t n, uint32_t k, uint64_t seed, void* stream);
+
+/* Drops every announcement of either kind (w2v_prefetch_minibatch, w2v_cbow_prefetch_minibatch) that
+ * has not been used, after waiting for the shard's look-ahead stream: on return the announced index
+ * arrays are no longer read and may be changed or freed.  An announcement is matched by the
+ * addresses of its arrays, so call this (or synchronise and never pass those addresses again)
+ * before reusing an announced array's memory for other indices under the same n, k and seed.
+ * Independently of this call, an announcement that the next two update calls on the shard
+ * (w2v_adjust, w2v_train_minibatch and their bag-of-words forms) do not use is void. */
+int w2v_prefetch_cancel(w2v_shard* shard);
 
 /* ---- interleaved minibatch formation (Section 5.1, last paragraph) -------------------------------
  * Same arguments and the same set of pairs as w2v_make_pairs, in another order: the centers are

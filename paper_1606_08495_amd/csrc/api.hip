@@ -66,6 +66,7 @@ struct IndexSet {
 
 struct Prepared {
     bool valid = false; int set = 0; bool own_rows = false;
+    uint64_t born = 0;              // value of the shard's update counter at the announcement
     const uint32_t* in_idx = nullptr; const uint32_t* out_idx = nullptr;
     uint32_t n = 0, k = 0; uint64_t seed = 0;
 };
@@ -84,6 +85,7 @@ struct CbowSet {
 
 struct CbowPrepared {
     bool valid = false; bool own_rows = false;
+    uint64_t born = 0;
     const uint32_t* ctx_off = nullptr; const uint32_t* ctx_idx = nullptr; const uint32_t* out_idx = nullptr;
     uint32_t n = 0, k = 0, m = 0; uint64_t seed = 0;
 };
@@ -101,6 +103,7 @@ struct w2v_shard {
     bool has_tables = false;
     uint64_t table_tag = 0;         // checksum of the noise table, to compare shards
     uint32_t* err = nullptr;        // sticky device flag
+    uint64_t updates = 0;           // update calls seen (adjust / train_minibatch, either variant)
     // scratch: one region, carved per call
     char* ws = nullptr;
     size_t ws_cap = 0;
@@ -413,16 +416,22 @@ int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
     HIP_TRY(hipGetLastError());
     Prepared& pr = sh->prep[which];
     pr = want;
-    pr.valid = true; pr.set = which; pr.own_rows = marks;
+    pr.valid = true; pr.set = which; pr.own_rows = marks; pr.born = sh->updates;
     sh->next_set = which ^ 1;
     return W2V_OK;
 }
 
 // The set that w2v_prefetch_minibatch filled for exactly this minibatch, or -1.
-int find_prepared(const w2v_shard* sh, const uint32_t* in_idx, const uint32_t* out_idx, uint32_t n,
+// An announcement is good for the next PREP_MAX_AGE update calls on the shard (two minibatches can
+// be held ahead); an older one is void, so that a forgotten set cannot be matched much later by
+// arrays that happen to live at the same addresses.
+constexpr uint64_t PREP_MAX_AGE = 2;
+
+int find_prepared(w2v_shard* sh, const uint32_t* in_idx, const uint32_t* out_idx, uint32_t n,
                   uint32_t k, uint64_t seed) {
     for (int i = 0; i < 2; ++i) {
-        const Prepared& pr = sh->prep[i];
+        Prepared& pr = sh->prep[i];
+        if (pr.valid && sh->updates - pr.born >= PREP_MAX_AGE) pr.valid = false;
         if (pr.valid && pr.in_idx == in_idx && pr.out_idx == out_idx && pr.n == n && pr.k == k &&
             pr.seed == seed)
             return i;
@@ -445,6 +454,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
                   const uint32_t* perm, const uint32_t* skw, const uint32_t* sidx,
                   const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
                   double* loss_out, hipStream_t st) {
+    // (loss_out: fused form only; the dots it is formed from go to p.dots)
     const bool two = ws_owner->overlap && ws_owner->side;
     hipStream_t side = two ? ws_owner->side : st;
     {
@@ -452,7 +462,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         USideArgs a{};
         a.U = sh->U; a.W = sh->W; a.g = sh->g; a.skey = sku; a.perm = perm; a.keys = p.keys;
         a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
-        a.dots_out = nullptr; a.delta = p.delta; a.dkey = p.dkey;
+        a.dots_out = (fused && loss_out) ? p.dots : nullptr; a.delta = p.delta; a.dkey = p.dkey;
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
         if (p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
         launch_useg(a, st);
@@ -463,9 +473,9 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         (void)hipEventRecord(ws_owner->ev_coeffs, st);
         (void)hipStreamWaitEvent(side, ws_owner->ev_coeffs, 0);
     }
-    if (loss_out) {
+    if (loss_out && fused) {
         Phase ph(ws_owner, W2V_PH_COEFF, side);
-        launch_loss_from_coeffs(fused ? coeffs_out : coeffs_in, p.n, p.T, p.loss_tmp, loss_out, side);
+        launch_loss_from_dots(p.dots, p.n, p.T, p.loss_tmp, loss_out, side);
     }
     {
         Phase ph(ws_owner, W2V_PH_APPLY, side);
@@ -698,6 +708,10 @@ extern "C" int w2v_shard_status(w2v_shard* sh, void* stream) {
     int rc = check_device(sh);
     if (rc) return rc;
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    // announced minibatches are checked on the shard's own streams, which join the caller's stream
+    // only when the set is used: wait for them too, so that a bad index announced just now is seen
+    if (sh->ahead) HIP_TRY(hipStreamSynchronize(sh->ahead));
+    if (sh->side) HIP_TRY(hipStreamSynchronize(sh->side));
     uint32_t flag = 0;
     HIP_TRY(hipMemcpy(&flag, sh->err, sizeof(flag), hipMemcpyDeviceToHost));
     if (flag) {
@@ -807,6 +821,7 @@ extern "C" int w2v_adjust(w2v_shard* sh, const uint32_t* in_idx, const uint32_t*
     uint32_t *sku, *perm, *skw, *sidx;
     sh->last_update_fused = false;
     const int ahead = find_prepared(sh, in_idx, out_idx, n, k, seed);
+    sh->updates++;
     if (ahead >= 0) {
         IndexSet& x = sh->sets[ahead];
         sh->prep[ahead].valid = false;                   // a set serves one update
@@ -848,19 +863,21 @@ extern "C" int w2v_train_minibatch(w2v_shard* const* shards, uint32_t S, const u
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (n == 0) {
-        if (loss) launch_loss_from_coeffs(nullptr, 0, k + 1, nullptr, loss, st);
+        if (loss) launch_loss_from_dots(nullptr, 0, k + 1, nullptr, loss, st);
         return W2V_OK;
     }
     const bool fused = (S == 1);
     const uint32_t own = (fused && s0->own_rows) ? s0->V : 0u;
-    Plan sz = make_plan(nullptr, n, k, stride_max, fused ? 0 : S, true, true, own);
+    const uint32_t S_dots = fused ? (loss ? 1u : 0u) : S;    // fused: the dots are kept for the loss only
+    Plan sz = make_plan(nullptr, n, k, stride_max, S_dots, true, true, own);
     rc = ensure_ws(s0, sz.bytes);
     if (rc) return rc;
-    Plan p = make_plan(s0->ws, n, k, stride_max, fused ? 0 : S, true, true, own);
+    Plan p = make_plan(s0->ws, n, k, stride_max, S_dots, true, true, own);
     uint32_t *sku, *perm, *skw, *sidx;
     // a set computed by w2v_prefetch_minibatch on shard 0 (every shard holds the same noise table)
     s0->last_update_fused = fused;
     const int ahead = find_prepared(s0, in_idx, out_idx, n, k, seed);
+    s0->updates++;
     if (ahead >= 0) {
         IndexSet& x = s0->sets[ahead];
         s0->prep[ahead].valid = false;                   // a set serves one update
@@ -910,6 +927,18 @@ extern "C" int w2v_prefetch_minibatch(w2v_shard* sh, const uint32_t* in_idx, con
     // (Queued behind that call's input-side kernel instead, it left the benchmark step unchanged but
     // did not fit beside the output-side kernel alone when k is large: the next step then waited.)
     return run_prefetch_chain(sh, want, st);
+}
+
+extern "C" int w2v_prefetch_cancel(w2v_shard* sh) {
+    if (!sh) return fail(W2V_ERR_NULL, "shard is NULL");
+    int rc = check_device(sh);
+    if (rc) return rc;
+    // the chains may still be reading the caller's arrays: wait for them before the caller is told
+    // that the arrays are its own again
+    if (sh->ahead) HIP_TRY(hipStreamSynchronize(sh->ahead));
+    sh->prep[0].valid = sh->prep[1].valid = false;
+    sh->cprep[0].valid = sh->cprep[1].valid = false;
+    return W2V_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1045,14 +1074,14 @@ void queue_cbow_hidden(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
 // there, behind its sort, the output side on the caller's stream.
 void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint32_t* skw,
                        const uint32_t* sidx, const uint32_t* skc, const uint32_t* cidx,
-                       const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
-                       bool join_sorts, hipStream_t st) {
+                       const float* coeffs_in, float* coeffs_out, float* dots_out, bool fused,
+                       float alpha, bool join_sorts, hipStream_t st) {
     {
         Phase ph(owner, W2V_PH_USIDE, st);
         USideArgs a{};
         a.U = p.H; a.W = sh->W; a.g = sh->g; a.skey = p.iota; a.perm = p.iota; a.keys = p.keys;
         a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
-        a.dots_out = nullptr; a.delta = p.E; a.dkey = p.dkey;
+        a.dots_out = fused ? dots_out : nullptr; a.delta = p.E; a.dkey = p.dkey;
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
         if (fused && p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }   // source: the hidden vector
         launch_useg(a, st);
@@ -1146,16 +1175,17 @@ int run_cbow_prefetch_chain(w2v_shard* sh, const CbowPrepared& want, hipStream_t
     HIP_TRY(hipGetLastError());
     CbowPrepared& pr = sh->cprep[which];
     pr = want;
-    pr.valid = true; pr.own_rows = sh->own_rows;
+    pr.valid = true; pr.own_rows = sh->own_rows; pr.born = sh->updates;
     sh->next_cset = which ^ 1;
     return W2V_OK;
 }
 
 // The set that w2v_cbow_prefetch_minibatch filled for exactly this minibatch, or -1.
-int find_cbow_prepared(const w2v_shard* sh, const uint32_t* ctx_off, const uint32_t* ctx_idx,
+int find_cbow_prepared(w2v_shard* sh, const uint32_t* ctx_off, const uint32_t* ctx_idx,
                        uint32_t m, const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed) {
     for (int i = 0; i < 2; ++i) {
-        const CbowPrepared& pr = sh->cprep[i];
+        CbowPrepared& pr = sh->cprep[i];
+        if (pr.valid && sh->updates - pr.born >= PREP_MAX_AGE) pr.valid = false;
         if (pr.valid && pr.ctx_off == ctx_off && pr.ctx_idx == ctx_idx && pr.out_idx == out_idx &&
             pr.n == n && pr.k == k && pr.m == m && pr.seed == seed)
             return i;
@@ -1181,6 +1211,7 @@ int cbow_indices(w2v_shard* sh, CbowPlan& p, const uint32_t* ctx_off, const uint
                  bool sorts, bool spend, bool fused, uint32_t** skw, uint32_t** sidx, uint32_t** skc,
                  uint32_t** cidx, bool* prepared, hipStream_t st) {
     const int ahead = find_cbow_prepared(sh, ctx_off, ctx_idx, m, out_idx, n, k, seed);
+    if (spend) sh->updates++;                             // an update call
     *prepared = ahead >= 0;
     if (ahead >= 0) return use_cbow_prepared(sh, ahead, p, spend, fused, skw, sidx, skc, cidx, st);
     return queue_cbow_indices(sh, p, ctx_off, ctx_idx, out_idx, k, seed, sorts, skw, sidx, skc, cidx, st);
@@ -1244,7 +1275,7 @@ extern "C" int w2v_cbow_adjust(w2v_shard* sh, const uint32_t* ctx_off, const uin
     if (rc) return rc;
     queue_cbow_hidden(sh, sh, p, ctx_off, st);
     if (!prepared) cbow_wait_keys(sh, st);
-    queue_cbow_adjust(sh, sh, p, skw, sidx, skc, cidx, coeffs, nullptr, false, alpha, !prepared, st);
+    queue_cbow_adjust(sh, sh, p, skw, sidx, skc, cidx, coeffs, nullptr, nullptr, false, alpha, !prepared, st);
     HIP_TRY(hipGetLastError());
     return W2V_OK;
 }
@@ -1272,14 +1303,15 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (n == 0) {
-        if (loss) launch_loss_from_coeffs(nullptr, 0, k + 1, nullptr, loss, st);
+        if (loss) launch_loss_from_dots(nullptr, 0, k + 1, nullptr, loss, st);
         return W2V_OK;
     }
     const bool fused = (S == 1);
-    CbowPlan sz = make_cbow_plan(nullptr, n, k, m, stride_max, fused ? 0 : S, true, true);
+    const uint32_t S_dots = fused ? (loss ? 1u : 0u) : S;    // fused: the dots are kept for the loss only
+    CbowPlan sz = make_cbow_plan(nullptr, n, k, m, stride_max, S_dots, true, true);
     rc = ensure_ws(s0, sz.bytes);
     if (rc) return rc;
-    CbowPlan p = make_cbow_plan(s0->ws, n, k, m, stride_max, fused ? 0 : S, true, true);
+    CbowPlan p = make_cbow_plan(s0->ws, n, k, m, stride_max, S_dots, true, true);
     p.own_rows = fused && s0->own_rows;
     uint32_t *skw, *sidx, *skc, *cidx;
     bool prepared = false;
@@ -1289,10 +1321,11 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
     if (fused) {
         queue_cbow_hidden(s0, s0, p, ctx_off, st);
         if (!prepared) cbow_wait_keys(s0, st);
-        queue_cbow_adjust(s0, s0, p, skw, sidx, skc, cidx, nullptr, p.coeffs, true, alpha, !prepared, st);
+        queue_cbow_adjust(s0, s0, p, skw, sidx, skc, cidx, nullptr, p.coeffs, loss ? p.dots : nullptr, true,
+                          alpha, !prepared, st);
         if (loss) {
             Phase ph(s0, W2V_PH_COEFF, st);
-            launch_loss_from_coeffs(p.coeffs, n, p.T, p.loss_tmp, loss, st);
+            launch_loss_from_dots(p.dots, n, p.T, p.loss_tmp, loss, st);
         }
     } else {
         // As in the two-call protocol, every shard forms its hidden vectors once for the dots and
@@ -1312,8 +1345,8 @@ extern "C" int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S,
         }
         for (uint32_t s = 0; s < S; ++s) {
             queue_cbow_hidden(s0, shards[s], p, ctx_off, st);
-            queue_cbow_adjust(s0, shards[s], p, skw, sidx, skc, cidx, p.coeffs, nullptr, false, alpha,
-                              !prepared, st);
+            queue_cbow_adjust(s0, shards[s], p, skw, sidx, skc, cidx, p.coeffs, nullptr, nullptr, false,
+                              alpha, !prepared, st);
         }
     }
     HIP_TRY(hipGetLastError());

@@ -121,11 +121,10 @@ struct USideArgs {
     float* W_update; float alpha;
 };
 void launch_useg(const USideArgs& a, hipStream_t st);
-// Minibatch loss from the coefficients alone: a slot with coefficient g contributes
-// -log(1 - |g|), which is -log sigma(f) for the positive slot and -log(1 - sigma(f)) for a
-// negative one.  tmp holds coeffs_loss_scratch_doubles(n, T) doubles.
-void launch_loss_from_coeffs(const float* coeffs, uint32_t n, uint32_t T, double* tmp,
-                             double* loss_out, hipStream_t st);
+// Minibatch loss from the dots of the fused step: slot 0 of a pair contributes softplus(-f), the
+// others softplus(f).  tmp holds coeffs_loss_scratch_doubles(n, T) doubles.
+void launch_loss_from_dots(const float* dots, uint32_t n, uint32_t T, double* tmp, double* loss_out,
+                           hipStream_t st);
 
 // Output-vector side, level 1.  Sorted contributions i = 0..M-1 with destination skey[i] and
 // original slot sidx[i] = p*T + j: adds alpha * sum coeffs[sidx] * U[in_idx[p]] to W[skey] for runs

@@ -340,13 +340,19 @@ void launch_coeffs(PartialPtrs parts, uint32_t S, uint32_t n, uint32_t T, float*
     if (loss_out) launch_sum_doubles(block_loss, nb, block_loss + nb, loss_out, st);
 }
 
-__global__ __launch_bounds__(256) void loss_from_coeffs_kernel(const float* __restrict__ coeffs,
-                                                               uint32_t total,
-                                                               double* __restrict__ block_loss) {
+// Minibatch loss of the fused step, from the dots the input-side kernel leaves behind: the same
+// softplus terms as coeffs_kernel, so that the fused and the unfused form of a step report the
+// same loss, finite however far sigma saturates.
+__global__ __launch_bounds__(256) void loss_from_dots_kernel(const float* __restrict__ dots,
+                                                             uint32_t total, uint32_t T,
+                                                             double* __restrict__ block_loss) {
     __shared__ double red[256];
     uint32_t i = blockIdx.x * 256 + threadIdx.x;
     double term = 0.0;
-    if (i < total) term = -(double)log1pf(-fabsf(coeffs[i]));
+    if (i < total) {
+        const float f = dots[i];
+        term = (double)((i % T) == 0 ? softplus(-f) : softplus(f));
+    }
     red[threadIdx.x] = term;
     __syncthreads();
     for (int s = 128; s >= 1; s >>= 1) {
@@ -356,12 +362,12 @@ __global__ __launch_bounds__(256) void loss_from_coeffs_kernel(const float* __re
     if (threadIdx.x == 0) block_loss[blockIdx.x] = red[0];
 }
 
-void launch_loss_from_coeffs(const float* coeffs, uint32_t n, uint32_t T, double* tmp,
-                             double* loss_out, hipStream_t st) {
+void launch_loss_from_dots(const float* dots, uint32_t n, uint32_t T, double* tmp, double* loss_out,
+                           hipStream_t st) {
     uint32_t total = n * T;
     if (total == 0) { launch_sum_doubles(nullptr, 0, nullptr, loss_out, st); return; }
     unsigned nb = blocks_for(total, 256);
-    hipLaunchKernelGGL(loss_from_coeffs_kernel, dim3(nb), dim3(256), 0, st, coeffs, total, tmp);
+    hipLaunchKernelGGL(loss_from_dots_kernel, dim3(nb), dim3(256), 0, st, dots, total, T, tmp);
     launch_sum_doubles(tmp, nb, tmp + nb, loss_out, st);
 }
 

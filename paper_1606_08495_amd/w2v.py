@@ -32,6 +32,7 @@ _SIGNATURES = {
     "w2v_shard_status": (ctypes.c_int, [c_vp, c_vp]),
     "w2v_negatives": (ctypes.c_int, [c_vp, c_vp, c_u32, c_u32, c_u64, c_vp, c_vp]),
     "w2v_dotprod": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp, c_vp]),
+    "w2v_prefetch_cancel": (ctypes.c_int, [c_vp]),
     "w2v_coeffs": (ctypes.c_int, [c_vp, ctypes.POINTER(c_vp), c_u32, c_u32, c_u32, c_vp, c_vp, c_vp]),
     "w2v_adjust": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp, ctypes.c_float, c_vp]),
     "w2v_train_minibatch": (ctypes.c_int, [ctypes.POINTER(c_vp), c_u32, c_vp, c_vp, c_u32, c_u32,
@@ -193,6 +194,9 @@ class Shard:
                                  n, int(k), int(seed), _dev(out, torch.float32, "partial_dots"),
                                  _stream(stream)))
         return out
+
+    def prefetch_cancel(self):
+        _check(lib().w2v_prefetch_cancel(self.h))
 
     def coeffs(self, partials, k, want_loss=False, out=None, stream=None):
         S = len(partials)

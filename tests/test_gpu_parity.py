@@ -163,6 +163,50 @@ def test_coeffs_parity():
     sh.destroy()
 
 
+def test_loss_with_saturated_sigmoids_is_finite_and_the_same_in_both_forms():
+    """Dots far out on either side (rows set by hand): the minibatch loss of the fused single-shard
+    step, of the step over two column shards and of the client call must all be finite and agree
+    with the oracle, whose loss term is log(1 + e^-x) evaluated without cancellation."""
+    V, d, k = 64, 64, 3
+    rng = np.random.default_rng(21)
+    counts = np.ones(V, np.uint64)
+    th, al = oracle.build_alias(counts)
+    U = np.zeros((V, d), np.float32)
+    W = np.zeros((V, d), np.float32)
+    scale = np.linspace(-9.0, 9.0, V).astype(np.float32)       # dots u_a . v_b = scale_a * scale_b
+    U[:, 0] = scale
+    W[:, 0] = scale
+    U[:, 1:] = (rng.random((V, d - 1), dtype=np.float32) - 0.5) * 1e-3
+    W[:, 1:] = (rng.random((V, d - 1), dtype=np.float32) - 0.5) * 1e-3
+    n = 3000
+    in_idx = rng.integers(0, V, n).astype(np.uint32)
+    out_idx = rng.integers(0, V, n).astype(np.uint32)
+    seed = 5
+    one = make_shard(V, d, 1, counts)
+    halves = [make_shard(V, 32, 1, counts, d_total=d, col_begin=0),
+              make_shard(V, 32, 1, counts, d_total=d, col_begin=32)]
+    set_all_rows(one, 0, U); set_all_rows(one, 1, W)
+    for s, sh in enumerate(halves):
+        set_all_rows(sh, 0, U[:, 32 * s:32 * s + 32]); set_all_rows(sh, 1, W[:, 32 * s:32 * s + 32])
+    ref_dots = oracle.dotprod(U, W, in_idx, out_idx, k, seed, th, al)
+    assert np.abs(ref_dots).max() > 70 and np.abs(ref_dots).min() < 1     # both regimes present
+    _, ref_loss = oracle.coeffs([ref_dots], want_loss=True)
+    assert np.isfinite(ref_loss)
+    a, b = dev(in_idx), dev(out_idx)
+    dots = one.dotprod(a, b, k, seed)
+    _, client_loss = one.coeffs([dots], k, want_loss=True)
+    l1 = torch.zeros(1, dtype=torch.float64, device="cuda")
+    l2 = torch.zeros(1, dtype=torch.float64, device="cuda")
+    w2v.train_minibatch([one], a, b, k, seed, 0.0, loss=l1)
+    w2v.train_minibatch(halves, a, b, k, seed, 0.0, loss=l2)
+    say("  saturated loss: oracle", ref_loss, "client", client_loss.item(), "fused", l1.item(), "two shards", l2.item())
+    for got in (client_loss.item(), l1.item(), l2.item()):
+        assert np.isfinite(got) and abs(got - ref_loss) <= 1e-5 * ref_loss
+    for sh in [one] + halves:
+        sh.status()
+        sh.destroy()
+
+
 # --- adjust ------------------------------------------------------------------------------------------
 
 def run_adjust_case(V, d, n, k, in_idx, out_idx, seed=77, alpha=0.025, label=""):
@@ -761,6 +805,51 @@ def test_announced_step_over_column_shards_gives_the_same_bits():
     for s in told + plain:
         s.status()
         s.destroy()
+
+
+def test_cancelled_and_stale_announcements_are_not_used():
+    """An announcement is matched by the addresses of its arrays.  After w2v_prefetch_cancel, or
+    once two update calls have gone by without using it, new contents at the same addresses must be
+    trained as what they are."""
+    V, d, n, k = 900, 60, 2000, 5
+    rng = np.random.default_rng(41)
+    counts = zipf_counts(V)
+    a, b = dev(rng.integers(0, V, n)), dev(rng.integers(0, V, n))
+    a2, b2 = dev(rng.integers(0, V, n)), dev(rng.integers(0, V, n))
+    x, y = dev(rng.integers(0, V, n)), dev(rng.integers(0, V, n))
+    for mode in ("cancel", "stale"):
+        told, plain = make_shard(V, d, 2, counts), make_shard(V, d, 2, counts)
+        buf_in, buf_out = a.clone(), b.clone()
+        told.prefetch_minibatch(buf_in, buf_out, k, 11)
+        if mode == "cancel":
+            told.prefetch_cancel()
+        else:                                   # two other updates go by: the announcement is void
+            torch.cuda.synchronize()
+            for sh in (told, plain):
+                w2v.train_minibatch([sh], x, y, k, 7, 0.05)
+                w2v.train_minibatch([sh], y, x, k, 8, 0.05)
+        torch.cuda.synchronize()
+        buf_in.copy_(a2); buf_out.copy_(b2)     # same addresses, same n, k, seed -- other words
+        w2v.train_minibatch([told], buf_in, buf_out, k, 11, 0.05)
+        w2v.train_minibatch([plain], a2, b2, k, 11, 0.05)
+        for which in (0, 1):
+            assert np.array_equal(all_rows(told, which), all_rows(plain, which)), mode
+        for sh in (told, plain):
+            sh.status()
+            sh.destroy()
+
+
+def test_status_sees_a_bad_index_in_an_announcement_at_once():
+    sh = make_shard(100, 60, 1, np.ones(100, np.uint64))
+    good = dev(np.arange(50, dtype=np.uint32))
+    bad = dev(np.full(50, 100, np.uint32))
+    sh.prefetch_minibatch(bad, good, 5, 1)
+    with pytest.raises(w2v.W2VError) as e:
+        sh.status()                             # no training call in between
+    assert e.value.code == -6
+    sh.prefetch_cancel()
+    sh.status()
+    sh.destroy()
 
 
 def test_new_counts_void_an_announced_minibatch():
