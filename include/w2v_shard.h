@@ -107,6 +107,21 @@ int w2v_negatives(w2v_shard* shard, const uint32_t* out_idx_dev, uint32_t n, uin
 int w2v_dotprod(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
                 uint32_t n, uint32_t k, uint64_t seed, float* partial_dots_dev, void* stream);
 
+/* ---- w2v_dotprod for callers that cannot allocate ------------------------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid allocation: the
+ * same operation, arguments, results (bit for bit) and errors as w2v_dotprod, but the call never
+ * allocates or frees memory -- its scratch (the checked input words and the regenerated negatives)
+ * lives in a fixed array of W2V_NOALLOC_SCRATCH_U32 uint32 (8 MiB) that is part of the library's
+ * device code, one copy per GPU, held until the process ends.  A minibatch needs
+ * roundup64(n*(k+1)) + n entries; larger ones are refused with W2V_ERR_ARG (use w2v_dotprod).
+ * Every call on a GPU, from any shard, uses that GPU's one array: calls that may overlap on one
+ * GPU (different streams, different threads) race and must be ordered by the caller.  Nothing in
+ * the array needs to start at zero; it keeps the last call's contents.  Announced minibatches
+ * (w2v_prefetch_minibatch) are not consulted, and no timing spans are recorded. */
+#define W2V_NOALLOC_SCRATCH_U32 (1u << 21)
+int w2v_dotprod_noalloc(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
+                        uint32_t n, uint32_t k, uint64_t seed, float* partial_dots_dev, void* stream);
+
 /* ---- client aggregation (Appendix, "Grid based word2vec": F = sum_s F_s, then G+ and G-) ----------
  * partials_host[S] are S device arrays [n][k+1].  coeffs[p][0] = 1 - sigma(f), coeffs[p][j>0] =
  * -sigma(f), f the sum over shards in shard order.  The learning rate is NOT folded in; adjust takes

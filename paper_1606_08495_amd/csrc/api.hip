@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -45,6 +46,34 @@ static int fail(int code, const char* fmt, ...) {
     } while (0)
 
 extern "C" const char* w2v_last_error(void) { return g_last_error.c_str(); }
+
+// ---------------------------------------------------------------------------------------------
+// Scratch of w2v_dotprod_noalloc: one array per GPU, part of the loaded code object, so the entry
+// point never allocates.  In host code the array's name is only a handle for hipGetSymbolAddress;
+// the device address it yields (one per device) is what kernels and copies are given.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) uint32_t scratch[W2V_NOALLOC_SCRATCH_U32];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+uint32_t* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+
+// Device address of `scratch` on the CURRENT device (which must be `device`), resolved once.
+int static_scratch(int device, uint32_t** out) {
+    if (device < 0 || device >= MAX_DEVICES)
+        return -1;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) { (void)hipGetLastError(); return -1; }
+        g_scratch_ptr[device] = (uint32_t*)ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return 0;
+}
+}  // namespace
 
 // ---------------------------------------------------------------------------------------------
 // shard object
@@ -103,6 +132,7 @@ struct w2v_shard {
     bool has_tables = false;
     uint64_t table_tag = 0;         // checksum of the noise table, to compare shards
     uint32_t* err = nullptr;        // sticky device flag
+    uint32_t* static_ws = nullptr;  // this device's copy of the no-allocation scratch array
     uint64_t updates = 0;           // update calls seen (adjust / train_minibatch, either variant)
     // scratch: one region, carved per call
     char* ws = nullptr;
@@ -567,6 +597,13 @@ extern "C" int w2v_shard_create_ex(uint32_t V, uint32_t d_total, uint32_t col_be
         delete sh;
         return rc;
     }
+    if (static_scratch(sh->device, &sh->static_ws) != 0) {
+        int rc = fail(W2V_ERR_HIP, "hipGetSymbolAddress of the static scratch array failed on device %d",
+                      sh->device);
+        (void)hipFree(sh->U); (void)hipFree(sh->W); (void)hipFree(sh->err);
+        delete sh;
+        return rc;
+    }
     launch_init(sh->U, V, sh->g, d_slice, d_total, col_begin, seed, 0, false, nullptr);
     launch_init(sh->W, V, sh->g, d_slice, d_total, col_begin, seed, 1, init_mode == 0, nullptr);
     hipError_t le = hipGetLastError();
@@ -774,6 +811,35 @@ extern "C" int w2v_dotprod(w2v_shard* sh, const uint32_t* in_idx, const uint32_t
         Phase ph(sh, W2V_PH_DOT, st);
         launch_dots(sh->U, sh->W, sh->g, p.in_safe, p.keys, n, p.T, partial_dots, st);
     }
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+// w2v_dotprod without any allocation: the checked input words and the destination keys go to this
+// device's static scratch array instead of the shard's growable region; same kernels.  No timing
+// spans either (they take events from a pool that may have to grow).
+extern "C" int w2v_dotprod_noalloc(w2v_shard* sh, const uint32_t* in_idx, const uint32_t* out_idx,
+                                   uint32_t n, uint32_t k, uint64_t seed, float* partial_dots,
+                                   void* stream) {
+    if (!sh || (n && (!in_idx || !out_idx || !partial_dots)))
+        return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_device(sh);
+    if (!rc) rc = check_batch(sh, n, k, true);
+    if (rc) return rc;
+    if (n == 0) return W2V_OK;
+    const uint64_t M = (uint64_t)n * (k + 1);
+    const uint64_t keys_u32 = (M + 63) & ~(uint64_t)63;           // keeps the second array 256-byte aligned
+    if (keys_u32 + n > (uint64_t)W2V_NOALLOC_SCRATCH_U32)
+        return fail(W2V_ERR_ARG, "n*(k+2) = %llu exceeds the %u entries of the static scratch array "
+                    "(W2V_NOALLOC_SCRATCH_U32); use w2v_dotprod for larger minibatches",
+                    (unsigned long long)(M + n), (unsigned)W2V_NOALLOC_SCRATCH_U32);
+    if (!sh->static_ws) return fail(W2V_ERR_STATE, "the static scratch array was not resolved");
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t* keys = sh->static_ws;
+    uint32_t* in_safe = sh->static_ws + keys_u32;
+    launch_check_inputs(in_idx, n, sh->V, in_safe, sh->err, st);
+    launch_dest_keys(NoiseTable{sh->bins, sh->V}, out_idx, n, k, seed, keys, sh->err, st);
+    launch_dots(sh->U, sh->W, sh->g, in_safe, keys, n, k + 1, partial_dots, st);
     HIP_TRY(hipGetLastError());
     return W2V_OK;
 }

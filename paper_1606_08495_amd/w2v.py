@@ -16,6 +16,7 @@ _lib = None
 
 PHASES = ["neg", "dot", "coeff", "sort", "uside", "wside", "apply", "pairs"]
 K_MAX, D_MAX, S_MAX = 64, 1024, 32
+NOALLOC_SCRATCH_U32 = 1 << 21
 
 c_u32, c_u64, c_vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_void_p
 
@@ -32,6 +33,7 @@ _SIGNATURES = {
     "w2v_shard_status": (ctypes.c_int, [c_vp, c_vp]),
     "w2v_negatives": (ctypes.c_int, [c_vp, c_vp, c_u32, c_u32, c_u64, c_vp, c_vp]),
     "w2v_dotprod": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp, c_vp]),
+    "w2v_dotprod_noalloc": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp, c_vp]),
     "w2v_prefetch_cancel": (ctypes.c_int, [c_vp]),
     "w2v_coeffs": (ctypes.c_int, [c_vp, ctypes.POINTER(c_vp), c_u32, c_u32, c_u32, c_vp, c_vp, c_vp]),
     "w2v_adjust": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp, ctypes.c_float, c_vp]),
@@ -193,6 +195,14 @@ class Shard:
         _check(lib().w2v_dotprod(self.h, _dev(in_idx, IDX, "in_idx"), _dev(out_idx, IDX, "out_idx"),
                                  n, int(k), int(seed), _dev(out, torch.float32, "partial_dots"),
                                  _stream(stream)))
+        return out
+
+    def dotprod_noalloc(self, in_idx, out_idx, k, seed, out, stream=None):
+        """w2v_dotprod_noalloc: `out` ([n, k+1] float32) must be given; the library allocates nothing."""
+        _check(lib().w2v_dotprod_noalloc(self.h, _dev(in_idx, IDX, "in_idx"),
+                                         _dev(out_idx, IDX, "out_idx"), in_idx.numel(), int(k),
+                                         int(seed), _dev(out, torch.float32, "partial_dots"),
+                                         _stream(stream)))
         return out
 
     def prefetch_cancel(self):
