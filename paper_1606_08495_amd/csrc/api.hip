@@ -86,9 +86,9 @@ struct TimedSpan { int phase; hipEvent_t a, b; };
 struct IndexSet {
     char* base = nullptr; size_t cap = 0;
     uint32_t *keys = nullptr, *in_safe = nullptr;
-    uint32_t *uk0 = nullptr, *uv0 = nullptr, *uk1 = nullptr, *uv1 = nullptr;
-    uint32_t *wk0 = nullptr, *wv0 = nullptr, *wk1 = nullptr, *wv1 = nullptr;
-    uint32_t *sort_tmp = nullptr, *sort_tmp_u = nullptr;
+    uint2 *ub0 = nullptr, *ub1 = nullptr;       // sort buffers, input side (n)
+    uint2 *wb0 = nullptr, *wb1 = nullptr;       // sort buffers, output side (M)
+    uint32_t *sort_tmp = nullptr;               // of the joint sort of both sides
     uint32_t *sku = nullptr, *perm = nullptr, *skw = nullptr, *sidx = nullptr;   // sorted results
     hipEvent_t ready = nullptr;
 };
@@ -106,8 +106,9 @@ struct CbowSet {
     char* base = nullptr; size_t cap = 0;
     uint32_t *keys = nullptr, *ctx_safe = nullptr, *ex_of = nullptr, *iota = nullptr;
     float* weight = nullptr;
-    uint32_t *wk0 = nullptr, *wv0 = nullptr, *wk1 = nullptr, *wv1 = nullptr, *sort_tmp_w = nullptr;
-    uint32_t *ck0 = nullptr, *cv0 = nullptr, *ck1 = nullptr, *cv1 = nullptr, *sort_tmp_c = nullptr;
+    uint2 *wb0 = nullptr, *wb1 = nullptr;       // sort buffers of the M destinations
+    uint2 *cb0 = nullptr, *cb1 = nullptr;       // sort buffers of the m context entries
+    uint32_t *sort_tmp = nullptr;               // of the joint sort of both
     uint32_t *skw = nullptr, *sidx = nullptr, *skc = nullptr, *cidx = nullptr;   // sorted results
     hipEvent_t ready = nullptr;
 };
@@ -260,8 +261,8 @@ struct Plan {
     uint32_t n, T, M;
     uint32_t* keys; uint32_t* in_safe;
     bool own_rows;                         // fused step: singly named output rows go to the input side
-    uint32_t *uk0, *uv0, *uk1, *uv1;       // sort buffers, input side (n)
-    uint32_t *wk0, *wv0, *wk1, *wv1;       // sort buffers, output side (M)
+    uint2 *ub0, *ub1;                      // sort buffers, input side (n)
+    uint2 *wb0, *wb1;                      // sort buffers, output side (M)
     uint32_t* sort_tmp; uint32_t* sort_tmp_u;
     float* coeffs; float* dots; double* loss_tmp;
     float* delta; uint32_t* dkey;
@@ -285,12 +286,10 @@ Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_
     if (S_dots) p.dots = c.take<float>((size_t)S_dots * p.M);
     p.loss_tmp = c.take<double>(coeffs_loss_scratch_doubles(n, p.T));
     if (want_adjust) {
-        p.uk0 = c.take<uint32_t>(n); p.uv0 = c.take<uint32_t>(n);
-        p.uk1 = c.take<uint32_t>(n); p.uv1 = c.take<uint32_t>(n);
-        p.wk0 = c.take<uint32_t>(p.M); p.wv0 = c.take<uint32_t>(p.M);
-        p.wk1 = c.take<uint32_t>(p.M); p.wv1 = c.take<uint32_t>(p.M);
-        p.sort_tmp = c.take<uint32_t>(sort_scratch_u32(p.M ? p.M : 1));
-        p.sort_tmp_u = c.take<uint32_t>(sort_scratch_u32(n ? n : 1));
+        p.ub0 = c.take<uint2>(n); p.ub1 = c.take<uint2>(n);
+        p.wb0 = c.take<uint2>(p.M); p.wb1 = c.take<uint2>(p.M);
+        p.sort_tmp = c.take<uint32_t>(sort_scratch_u32(p.M));
+        p.sort_tmp_u = c.take<uint32_t>(sort_scratch_u32(n));
         const size_t row = (size_t)stride4_max * 4;
         p.delta = c.take<float>((size_t)n * row);
         p.dkey = c.take<uint32_t>(n);
@@ -346,12 +345,9 @@ int ensure_set(w2v_shard* sh, IndexSet& x, uint32_t n, uint32_t M) {
         Carver c(pass ? x.base : nullptr);
         uint32_t* keys = c.take<uint32_t>(M);
         uint32_t* in_safe = c.take<uint32_t>(n);
-        uint32_t* uk0 = c.take<uint32_t>(n); uint32_t* uv0 = c.take<uint32_t>(n);
-        uint32_t* uk1 = c.take<uint32_t>(n); uint32_t* uv1 = c.take<uint32_t>(n);
-        uint32_t* wk0 = c.take<uint32_t>(M); uint32_t* wv0 = c.take<uint32_t>(M);
-        uint32_t* wk1 = c.take<uint32_t>(M); uint32_t* wv1 = c.take<uint32_t>(M);
-        uint32_t* tw = c.take<uint32_t>(sort_scratch_u32(M ? M : 1));
-        uint32_t* tu = c.take<uint32_t>(sort_scratch_u32(n ? n : 1));
+        uint2* ub0 = c.take<uint2>(n); uint2* ub1 = c.take<uint2>(n);
+        uint2* wb0 = c.take<uint2>(M); uint2* wb1 = c.take<uint2>(M);
+        uint32_t* tw = c.take<uint32_t>(sort_scratch_u32(M, n));
         const size_t need = c.off + 256;
         if (pass == 0) {
             if (need > x.cap) {
@@ -365,8 +361,8 @@ int ensure_set(w2v_shard* sh, IndexSet& x, uint32_t n, uint32_t M) {
                 x.cap = need;
             }
         } else {
-            x.keys = keys; x.in_safe = in_safe; x.uk0 = uk0; x.uv0 = uv0; x.uk1 = uk1; x.uv1 = uv1;
-            x.wk0 = wk0; x.wv0 = wv0; x.wk1 = wk1; x.wv1 = wv1; x.sort_tmp = tw; x.sort_tmp_u = tu;
+            x.keys = keys; x.in_safe = in_safe; x.ub0 = ub0; x.ub1 = ub1;
+            x.wb0 = wb0; x.wb1 = wb1; x.sort_tmp = tw;
         }
     }
     if (!x.ready) HIP_TRY(hipEventCreateWithFlags(&x.ready, hipEventDisableTiming));
@@ -402,7 +398,7 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
     if (sh->overlap) HIP_TRY(hipEventRecord(sh->ev_keys, sh->side));
     {
         Phase ph(sh, W2V_PH_SORT, wst);
-        launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp, skw, sidx, wst);
+        launch_sort_pairs(p.keys, p.wb0, p.wb1, p.M, bits, p.sort_tmp, skw, sidx, sh->err, wst);
         // fused single-shard step: output rows named by one slot only are updated by the
         // input-side kernel (which then has to wait for this sort) and skipped by the output side
         if (p.own_rows) launch_mark_alone(*skw, *sidx, p.M, p.keys, wst);
@@ -411,7 +407,7 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
     {
         Phase ph(sh, W2V_PH_SORT, st);
         launch_check_inputs(in_idx, p.n, sh->V, p.in_safe, sh->err, st);
-        launch_sort_pairs(p.in_safe, p.uk0, p.uv0, p.uk1, p.uv1, p.n, bits, p.sort_tmp_u, sku, perm, st);
+        launch_sort_pairs(p.in_safe, p.ub0, p.ub1, p.n, bits, p.sort_tmp_u, sku, perm, sh->err, st);
     }
     if (sh->overlap) HIP_TRY(hipStreamWaitEvent(st, p.own_rows ? sh->ev_join : sh->ev_keys, 0));
     return W2V_OK;
@@ -437,10 +433,12 @@ int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
     }
     {
         Phase ph(sh, W2V_PH_SORT, side);
-        launch_sort_pairs(x.keys, x.wk0, x.wv0, x.wk1, x.wv1, M, bits, x.sort_tmp, &x.skw, &x.sidx, side);
-        if (marks) launch_mark_alone(x.skw, x.sidx, M, x.keys, side);
         launch_check_inputs(want.in_idx, n, sh->V, x.in_safe, sh->err, side);
-        launch_sort_pairs(x.in_safe, x.uk0, x.uv0, x.uk1, x.uv1, n, bits, x.sort_tmp_u, &x.sku, &x.perm, side);
+        // both sides' keys in the same launches: the small input-side sort rides along
+        const SortJob jobs[2] = {{x.keys, M, x.wb0, x.wb1, &x.skw, &x.sidx},
+                                 {x.in_safe, n, x.ub0, x.ub1, &x.sku, &x.perm}};
+        launch_sort_jobs(jobs, 2, bits, x.sort_tmp, sh->err, side);
+        if (marks) launch_mark_alone(x.skw, x.sidx, M, x.keys, side);
     }
     HIP_TRY(hipEventRecord(x.ready, side));
     HIP_TRY(hipGetLastError());
@@ -754,6 +752,9 @@ extern "C" int w2v_shard_status(w2v_shard* sh, void* stream) {
     if (flag) {
         uint32_t zero = 0;
         HIP_TRY(hipMemcpy(sh->err, &zero, sizeof(zero), hipMemcpyHostToDevice));
+        if (flag & 2u)
+            return fail(W2V_ERR_HIP, "a bounded wait inside the key sort ran out (device stalled?): "
+                        "the vectors of that minibatch are not to be trusted");
         return fail(W2V_ERR_INDEX, "a word index >= V = %u was passed to an earlier call", sh->V);
     }
     return W2V_OK;
@@ -1021,8 +1022,8 @@ struct CbowPlan {
     uint32_t* iota;                                  // [n] 0, 1, 2, ...
     float* H; float* E; uint32_t* dkey;              // [n] rows: hidden vectors, summed output rows
     float* coeffs; float* dots; double* loss_tmp;
-    uint32_t *wk0, *wv0, *wk1, *wv1, *sort_tmp_w;    // sort of the M destinations
-    uint32_t *ck0, *cv0, *ck1, *cv1, *sort_tmp_c;    // sort of the m context entries
+    uint2 *wb0, *wb1; uint32_t* sort_tmp_w;          // sort of the M destinations
+    uint2 *cb0, *cb1; uint32_t* sort_tmp_c;          // sort of the m context entries
     float* pa_rows; uint32_t* pa_keys;               // unused slots of the per-example pass
     float* pb_rows; uint32_t* pb_keys;               // output side, level 1
     float* pd_rows; uint32_t* pd_keys;               // input side, level 1
@@ -1048,12 +1049,10 @@ CbowPlan make_cbow_plan(char* base, uint32_t n, uint32_t k, uint32_t m, uint32_t
     if (want_adjust) {
         p.E = c.take<float>((size_t)n * row);
         p.dkey = c.take<uint32_t>(n);
-        p.wk0 = c.take<uint32_t>(p.M); p.wv0 = c.take<uint32_t>(p.M);
-        p.wk1 = c.take<uint32_t>(p.M); p.wv1 = c.take<uint32_t>(p.M);
-        p.sort_tmp_w = c.take<uint32_t>(sort_scratch_u32(p.M ? p.M : 1));
-        p.ck0 = c.take<uint32_t>(m); p.cv0 = c.take<uint32_t>(m);
-        p.ck1 = c.take<uint32_t>(m); p.cv1 = c.take<uint32_t>(m);
-        p.sort_tmp_c = c.take<uint32_t>(sort_scratch_u32(m ? m : 1));
+        p.wb0 = c.take<uint2>(p.M); p.wb1 = c.take<uint2>(p.M);
+        p.sort_tmp_w = c.take<uint32_t>(sort_scratch_u32(p.M));
+        p.cb0 = c.take<uint2>(m); p.cb1 = c.take<uint2>(m);
+        p.sort_tmp_c = c.take<uint32_t>(sort_scratch_u32(m));
         p.slots_a = slots_after(n, useg_pairs_per_chunk(p.T, 1));
         p.slots_w1 = slots_after(p.M, wseg_entries_per_chunk());
         p.slots_c1 = slots_after(m, wseg_entries_per_chunk());
@@ -1109,12 +1108,12 @@ int queue_cbow_indices(w2v_shard* sh, CbowPlan& p, const uint32_t* ctx_off, cons
     {
         Phase ph(sh, W2V_PH_SORT, wst);
         const uint32_t bits = key_bits(sh->V);
-        launch_sort_pairs(p.keys, p.wk0, p.wv0, p.wk1, p.wv1, p.M, bits, p.sort_tmp_w, skw, sidx, wst);
+        launch_sort_pairs(p.keys, p.wb0, p.wb1, p.M, bits, p.sort_tmp_w, skw, sidx, sh->err, wst);
         if (p.own_rows) {           // the per-example pass needs the marks: "keys ready" moves here
             launch_mark_alone(*skw, *sidx, p.M, p.keys, wst);
             if (two) HIP_TRY(hipEventRecord(sh->ev_keys, wst));
         }
-        launch_sort_pairs(p.ctx_safe, p.ck0, p.cv0, p.ck1, p.cv1, p.m, bits, p.sort_tmp_c, skc, cidx, wst);
+        launch_sort_pairs(p.ctx_safe, p.cb0, p.cb1, p.m, bits, p.sort_tmp_c, skc, cidx, sh->err, wst);
     }
     if (two) HIP_TRY(hipEventRecord(sh->ev_join, wst));
     return W2V_OK;
@@ -1190,20 +1189,16 @@ int ensure_cset(w2v_shard* sh, CbowSet& x, uint32_t n, uint32_t M, uint32_t m) {
         uint32_t* ctx_safe = c.take<uint32_t>(m); uint32_t* ex_of = c.take<uint32_t>(m);
         float* weight = c.take<float>(m);
         uint32_t* iota = c.take<uint32_t>(n);
-        uint32_t* wk0 = c.take<uint32_t>(M); uint32_t* wv0 = c.take<uint32_t>(M);
-        uint32_t* wk1 = c.take<uint32_t>(M); uint32_t* wv1 = c.take<uint32_t>(M);
-        uint32_t* tw = c.take<uint32_t>(sort_scratch_u32(M ? M : 1));
-        uint32_t* ck0 = c.take<uint32_t>(m); uint32_t* cv0 = c.take<uint32_t>(m);
-        uint32_t* ck1 = c.take<uint32_t>(m); uint32_t* cv1 = c.take<uint32_t>(m);
-        uint32_t* tc = c.take<uint32_t>(sort_scratch_u32(m ? m : 1));
+        uint2* wb0 = c.take<uint2>(M); uint2* wb1 = c.take<uint2>(M);
+        uint2* cb0 = c.take<uint2>(m); uint2* cb1 = c.take<uint2>(m);
+        uint32_t* tw = c.take<uint32_t>(sort_scratch_u32(M, m));
         const size_t need = c.off + 256;
         if (pass == 0) {
             int rc = ensure_region(x.base, x.cap, need);
             if (rc) return rc;
         } else {
             x.keys = keys; x.ctx_safe = ctx_safe; x.ex_of = ex_of; x.weight = weight; x.iota = iota;
-            x.wk0 = wk0; x.wv0 = wv0; x.wk1 = wk1; x.wv1 = wv1; x.sort_tmp_w = tw;
-            x.ck0 = ck0; x.cv0 = cv0; x.ck1 = ck1; x.cv1 = cv1; x.sort_tmp_c = tc;
+            x.wb0 = wb0; x.wb1 = wb1; x.cb0 = cb0; x.cb1 = cb1; x.sort_tmp = tw;
         }
     }
     if (!x.ready) HIP_TRY(hipEventCreateWithFlags(&x.ready, hipEventDisableTiming));
@@ -1233,9 +1228,10 @@ int run_cbow_prefetch_chain(w2v_shard* sh, const CbowPrepared& want, hipStream_t
     }
     {
         Phase ph(sh, W2V_PH_SORT, ah);
-        launch_sort_pairs(x.keys, x.wk0, x.wv0, x.wk1, x.wv1, M, bits, x.sort_tmp_w, &x.skw, &x.sidx, ah);
+        const SortJob jobs[2] = {{x.keys, M, x.wb0, x.wb1, &x.skw, &x.sidx},
+                                 {x.ctx_safe, m, x.cb0, x.cb1, &x.skc, &x.cidx}};
+        launch_sort_jobs(jobs, 2, bits, x.sort_tmp, sh->err, ah);
         if (sh->own_rows) launch_mark_alone(x.skw, x.sidx, M, x.keys, ah);
-        launch_sort_pairs(x.ctx_safe, x.ck0, x.cv0, x.ck1, x.cv1, m, bits, x.sort_tmp_c, &x.skc, &x.cidx, ah);
     }
     HIP_TRY(hipEventRecord(x.ready, ah));
     HIP_TRY(hipGetLastError());

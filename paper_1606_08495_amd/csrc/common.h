@@ -81,12 +81,23 @@ void launch_coeffs(PartialPtrs parts, uint32_t S, uint32_t n, uint32_t T, float*
 size_t coeffs_loss_scratch_doubles(uint32_t n, uint32_t T);
 
 // Stable least-significant-digit radix sort of (keys_in[i], i) on `bits` key bits.  keys_in is
-// only read; the passes ping-pong between (k0, v0) and (k1, v1), n uint32 each, and the result is
-// in the pair returned through out_keys/out_vals.  tmp holds sort_scratch_u32(n) uint32.
-size_t sort_scratch_u32(uint32_t n);
-void launch_sort_pairs(const uint32_t* keys_in, uint32_t* k0, uint32_t* v0, uint32_t* k1,
-                       uint32_t* v1, uint32_t n, uint32_t bits, uint32_t* tmp,
-                       uint32_t** out_keys, uint32_t** out_vals, hipStream_t st);
+// only read; the passes ping-pong between buf0 and buf1 (n 8-byte words each, 8-byte aligned), and
+// the sorted keys and indices end up as two arrays of n uint32 inside one of the two buffers,
+// returned through out_keys/out_vals.  tmp holds sort_scratch_u32(n0, n1) uint32 (8-byte aligned).
+// launch_sort_jobs sorts one or two independent arrays with the same launches (the second rides
+// along with the first: no launches of its own).  err: sticky flag, bit 1 is raised if a bounded
+// wait inside the sort runs out (cannot happen unless the device stalls a running block for about
+// a second); may be null.
+struct SortJob {
+    const uint32_t* keys_in; uint32_t n; uint2* buf0; uint2* buf1;
+    uint32_t** out_keys; uint32_t** out_vals;
+};
+size_t sort_scratch_u32(uint32_t n0, uint32_t n1 = 0);
+void launch_sort_jobs(const SortJob* jobs, int njobs, uint32_t bits, uint32_t* tmp, uint32_t* err,
+                      hipStream_t st);
+void launch_sort_pairs(const uint32_t* keys_in, uint2* buf0, uint2* buf1, uint32_t n, uint32_t bits,
+                       uint32_t* tmp, uint32_t** out_keys, uint32_t** out_vals, uint32_t* err,
+                       hipStream_t st);
 
 // Exclusive prefix sum of n uint32 (in place allowed); total (may be null) gets the sum.
 size_t scan_scratch_u32(uint32_t n);

@@ -113,11 +113,11 @@ __global__ __launch_bounds__(256) void emit_pairs_kernel(const uint32_t* __restr
 }
 
 // scratch layout (uint32): flag[n+1] kpos[n+1] width[n] kword[n] klo[n] khi[n] kcnt[n] poff[n]
-// n_kept[8] scan_tmp[...]; interleaved order adds kj[n] cs[n] k0[n] v0[n] k1[n] v1[n] sort_tmp[...]
+// n_kept[8] scan_tmp[...]; interleaved order adds kj[n] cs[n] b0[2n] b1[2n] sort_tmp[...]
 size_t pairs_scratch_u32(uint32_t n_tokens, bool interleave) {
     size_t n = n_tokens;
     size_t base = 2 * (n + 1) + 6 * n + 8 + scan_scratch_u32(n_tokens + 1);
-    if (interleave) base += 6 * n + sort_scratch_u32(n_tokens ? n_tokens : 1);
+    if (interleave) base += 6 * n + 4 + sort_scratch_u32(n_tokens);
     return base;
 }
 
@@ -136,7 +136,11 @@ void launch_make_pairs(const PairArgs& a, hipStream_t st) {
     uint32_t* extra = scan_tmp + scan_scratch_u32(n + 1);
     uint32_t* kj = a.interleave ? extra : nullptr;
     uint32_t* cs = extra + n;
-    uint32_t *k0 = cs + n, *v0 = k0 + n, *k1 = v0 + n, *v1 = k1 + n, *sort_tmp = v1 + n;
+    // sort buffers (8-byte words) and sort scratch start on 8-byte boundaries
+    uint32_t* after_cs = cs + n;
+    after_cs += ((uintptr_t)after_cs & 4) ? 1 : 0;
+    uint2 *b0 = (uint2*)after_cs, *b1 = b0 + n;
+    uint32_t* sort_tmp = (uint32_t*)(b1 + n);
     hipLaunchKernelGGL(token_draws_kernel, dim3(blocks_for((uint64_t)n + 1, 256)), dim3(256), 0, st,
                        a.tokens, n, a.token_base, a.epoch, (uint32_t)a.seed,
                        (uint32_t)(a.seed >> 32), a.B, a.keep, a.V, flag, width, a.err);
@@ -169,7 +173,7 @@ void launch_make_pairs(const PairArgs& a, hipStream_t st) {
     uint32_t bits = 1;
     while (bits < 32 && (1ull << bits) <= (uint64_t)n) ++bits;
     uint32_t *sk = nullptr, *perm = nullptr;
-    launch_sort_pairs(kj, k0, v0, k1, v1, n, bits, sort_tmp, &sk, &perm, st);
+    launch_sort_pairs(kj, b0, b1, n, bits, sort_tmp, &sk, &perm, a.err, st);
     hipLaunchKernelGGL(permuted_counts_kernel, grid, block, 0, st, kcnt, perm, n_kept, n, cs);
     launch_exclusive_scan(cs, poff, n, scan_tmp, a.total_pairs, st);
     hipLaunchKernelGGL(emit_pairs_kernel, grid, block, 0, st, kword, klo, khi, poff, n_kept,
