@@ -83,17 +83,19 @@ class PairStream:
     def next(self):
         """The current minibatch; the one after it is formed as well (see peek)."""
         n = self.wl.n_pairs
-        while self.have - self.pos < 2 * n:
+        while self.have - self.pos < 3 * n:
             self._more()
         a = self.a[self.pos:self.pos + n]
         b = self.b[self.pos:self.pos + n]
         self.pos += n
         return a, b
 
-    def peek(self):
-        """The minibatch the following next() will return (same device addresses)."""
+    def peek(self, ahead=0):
+        """The minibatch the following next() will return (same device addresses); ahead = 1: the
+        one after that."""
         n = self.wl.n_pairs
-        return self.a[self.pos:self.pos + n], self.b[self.pos:self.pos + n]
+        lo = self.pos + ahead * n
+        return self.a[lo:lo + n], self.b[lo:lo + n]
 
 
 def host_cpu():
@@ -516,6 +518,9 @@ def main():
                     help="form the pairs on the training stream instead of a stream of their own")
     ap.add_argument("--no-prefetch", action="store_true",
                     help="do not announce the next minibatch to the shard (w2v_prefetch_minibatch)")
+    ap.add_argument("--prefetch-depth", type=int, default=1, choices=[1, 2],
+                    help="text workloads: announce minibatch h+1 before step h (1) or minibatch h+2 "
+                         "after step h (2)")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates HBM counters)")
     args = ap.parse_args()
@@ -573,11 +578,21 @@ def main():
             tokens, off = workloads.corpus(wl, n_tok, cdf=cdf)
         del cdf
         stream = PairStream(sh, wl, tokens, off, block_tokens=min(tokens.size, 1 << 21), torch=torch,
-                            minibatches=total_steps + 1, own_stream=not args.pairs_on_main_stream)
+                            minibatches=total_steps + 2, own_stream=not args.pairs_on_main_stream)
         H = max(1, wl.corpus_tokens * 4 // wl.n_pairs)     # minibatches in the nominal corpus
 
         def step(h):
             a, b = stream.next()
+            if args.prefetch_depth == 2:
+                # two ahead: minibatch h+2 is announced right after step h is queued, so its index
+                # work runs beside step h+1 and has until step h+2 to finish
+                if h == 0:
+                    sh.prefetch_minibatch(a, b, wl.k, w2v.minibatch_seed(wl.seed, 0))
+                    sh.prefetch_minibatch(*stream.peek(), wl.k, w2v.minibatch_seed(wl.seed, 1))
+                w2v.train_minibatch([sh], a, b, wl.k, w2v.minibatch_seed(wl.seed, h),
+                                    workloads.alpha_schedule(wl, h, H), loss=loss)
+                sh.prefetch_minibatch(*stream.peek(1), wl.k, w2v.minibatch_seed(wl.seed, h + 2))
+                return a, b
             if not args.no_prefetch:                       # the next minibatch's index work, ahead
                 na, nb = stream.peek()
                 sh.prefetch_minibatch(na, nb, wl.k, w2v.minibatch_seed(wl.seed, h + 1))
