@@ -518,6 +518,11 @@ def main():
                     help="form the pairs on the training stream instead of a stream of their own")
     ap.add_argument("--no-prefetch", action="store_true",
                     help="do not announce the next minibatch to the shard (w2v_prefetch_minibatch)")
+    ap.add_argument("--graph", action="store_true",
+                    help="text workloads: run every step as a replay of one captured step "
+                         "(w2v_step_graph), the form meant for small minibatches")
+    ap.add_argument("--pairs-per-minibatch", type=int, default=0,
+                    help="override the workload's minibatch size (pairs)")
     ap.add_argument("--prefetch-depth", type=int, default=1, choices=[1, 2],
                     help="text workloads: announce minibatch h+1 before step h (1) or minibatch h+2 "
                          "after step h (2)")
@@ -543,6 +548,9 @@ def main():
     if args.variant == "gather":
         return run_gather_probe(args, torch, w2v, workloads)
     wl = workloads.WORKLOADS[args.workload]
+    if args.pairs_per_minibatch:
+        import dataclasses
+        wl = dataclasses.replace(wl, n_pairs=args.pairs_per_minibatch)
     K, Wm = args.steps, args.warmup
     if not args.cpu_sample_pairs:
         args.cpu_sample_pairs = {"full300": 1 << 20, "slice60": 1 << 20, "tiny": 1 << 16,
@@ -581,8 +589,13 @@ def main():
                             minibatches=total_steps + 2, own_stream=not args.pairs_on_main_stream)
         H = max(1, wl.corpus_tokens * 4 // wl.n_pairs)     # minibatches in the nominal corpus
 
+        step_graph = w2v.StepGraph(sh, wl.n_pairs, wl.k, loss=loss) if args.graph else None
+
         def step(h):
             a, b = stream.next()
+            if step_graph is not None:          # one captured step, replayed (small minibatches)
+                step_graph.run(a, b, w2v.minibatch_seed(wl.seed, h), workloads.alpha_schedule(wl, h, H))
+                return a, b
             if args.prefetch_depth == 2:
                 # two ahead: minibatch h+2 is announced right after step h is queued, so its index
                 # work runs beside step h+1 and has until step h+2 to finish
@@ -713,9 +726,16 @@ def main():
     for name, (ms, cnt) in phases.items():
         if cnt:
             per_phase[name] = {"ms_per_launch": ms / cnt, "launches": cnt}
-    dom = max((p for p in per_phase if p in algo), key=lambda p: per_phase[p]["ms_per_launch"] *
-              per_phase[p]["launches"])
-    dom_ms = per_phase[dom]["ms_per_launch"]
+    timed = [p for p in per_phase if p in algo]
+    if timed:
+        dom = max(timed, key=lambda p: per_phase[p]["ms_per_launch"] * per_phase[p]["launches"])
+        dom_ms = per_phase[dom]["ms_per_launch"]
+    else:
+        # a captured step records no per-phase events: the roofline entry is the whole step's, its
+        # bytes the sum over the row kernels
+        dom, dom_ms = "step", ms_per_step
+        algo["step"] = algo["uside"] + algo["wside"] + (0 if fused else algo["dot"])
+        compulsory["step"] = 2 * (du + dw) * R + 8 * n
     achieved = algo[dom] / (dom_ms * 1e-3) / 1e9
     compulsory_gbs = compulsory[dom] / (dom_ms * 1e-3) / 1e9
     # L2<->fabric bytes per launch: NOT measured in this run -- read from the committed rocprofv3
@@ -752,7 +772,7 @@ def main():
                    "path": "make_pairs+train_minibatch" if fused else "dotprod+adjust",
                    "distinct_input_rows": du, "distinct_output_rows": dw,
                    "output_rows_named_once": single,
-                   "prefetch": not args.no_prefetch},
+                   "prefetch": not args.no_prefetch and not args.graph, "captured_step": bool(args.graph)},
         "roofline": {"bound": "hbm", "kernel": KERNEL_OF_PHASE.get(dom, dom), "phase": dom,
                      "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -165,6 +165,25 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
                    uint64_t corpus_seed, uint32_t B, uint32_t* in_idx_dev, uint32_t* out_idx_dev,
                    uint64_t capacity, uint64_t* n_pairs_host, void* stream);
 
+/* ---- a training step captured once and replayed (the paper's minibatch sizes) ----------------------
+ * Section 6.2 and Section 7.1 train with minibatches of 200, 50 or a single input word -- a few
+ * thousand pairs at most.  At that size a step is a chain of some thirty small kernels and its time
+ * is their launches.  w2v_step_graph_create captures w2v_train_minibatch(S = 1) for a fixed (n, k)
+ * on this shard into a HIP graph; w2v_step_graph_run copies the minibatch's indices, seed and
+ * learning rate into the graph's own staging block (one small kernel) and replays it on `stream`:
+ * the same kernels on the same data, hence the same bits as w2v_train_minibatch(in_idx, out_idx, n,
+ * k, seed, alpha, loss).  loss_dev (may be NULL) is fixed at creation and written by every run.
+ * The captured step runs on one stream and uses the shard's scratch like any other call: order it
+ * with other calls on the shard through `stream`.  Creating the graph allocates and synchronises;
+ * running it does neither.  Calls between creation and a run that need a larger scratch region
+ * (a larger n or k on the same shard) invalidate the graph: create it again. */
+typedef struct w2v_step_graph w2v_step_graph;
+int w2v_step_graph_create(w2v_shard* shard, uint32_t n, uint32_t k, double* loss_dev,
+                          w2v_step_graph** out);
+int w2v_step_graph_run(w2v_step_graph* graph, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
+                       uint64_t seed, float alpha, void* stream);
+int w2v_step_graph_destroy(w2v_step_graph* graph);
+
 /* Optional look-ahead for a training loop on one shard.  Everything w2v_train_minibatch derives from
  * the indices alone -- the negatives, and the grouping of the minibatch's input and output rows that
  * makes the update deterministic -- depends on neither the vectors nor earlier minibatches.  This call

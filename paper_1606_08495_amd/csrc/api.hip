@@ -135,6 +135,8 @@ struct w2v_shard {
     uint32_t* err = nullptr;        // sticky device flag
     uint32_t* static_ws = nullptr;  // this device's copy of the no-allocation scratch array
     uint64_t updates = 0;           // update calls seen (adjust / train_minibatch, either variant)
+    const CallScalars* call_dev = nullptr;   // set while a step is captured into a graph: the
+                                    // kernels then read seed and learning rate from device memory
     // scratch: one region, carved per call
     char* ws = nullptr;
     size_t ws_cap = 0;
@@ -288,12 +290,12 @@ Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_
     if (want_adjust) {
         p.ub0 = c.take<uint2>(n); p.ub1 = c.take<uint2>(n);
         p.wb0 = c.take<uint2>(p.M); p.wb1 = c.take<uint2>(p.M);
-        p.sort_tmp = c.take<uint32_t>(sort_scratch_u32(p.M));
+        p.sort_tmp = c.take<uint32_t>(sort_scratch_u32(p.M, n));     // (room for the joint sort)
         p.sort_tmp_u = c.take<uint32_t>(sort_scratch_u32(n));
         const size_t row = (size_t)stride4_max * 4;
         p.delta = c.take<float>((size_t)n * row);
         p.dkey = c.take<uint32_t>(n);
-        p.slots_u1 = slots_after(n, useg_pairs_per_chunk(p.T, 1));    // the most any shard needs
+        p.slots_u1 = slots_after(n, useg_pairs_per_chunk(p.T, 1, n));    // the most any shard needs
         p.slots_w1 = slots_after(p.M, wseg_entries_per_chunk());
         uint32_t s2u = slots_after(p.slots_u1, tail_entries_per_chunk());
         uint32_t s2w = slots_after(p.slots_w1, tail_entries_per_chunk());
@@ -312,13 +314,13 @@ Plan make_plan(char* base, uint32_t n, uint32_t k, uint32_t stride4_max, uint32_
 // need not wait for the output side to finish reading M.
 void run_tails(w2v_shard* sh, float* M, float alpha, float* rows_a, uint32_t* keys_a, uint32_t slots,
                float* rows_b, uint32_t* keys_b, hipStream_t st, float* defer_rows = nullptr,
-               uint32_t* defer_keys = nullptr, uint32_t cp = 0) {
+               uint32_t* defer_keys = nullptr, uint32_t cp = 0, const CallScalars* dev = nullptr) {
     float* src_rows = rows_a; uint32_t* src_keys = keys_a;
     float* dst_rows = rows_b; uint32_t* dst_keys = keys_b;
     uint32_t level = 0;
     while (slots > 0) {
         TailArgs t{M, sh->g, alpha, src_rows, src_keys, slots, dst_rows, dst_keys};
-        t.defer_rows = defer_rows; t.defer_keys = defer_keys; t.level = ++level; t.cp = cp;
+        t.defer_rows = defer_rows; t.defer_keys = defer_keys; t.level = ++level; t.cp = cp; t.dev = dev;
         launch_tail(t, st);
         slots = slots_after(slots, tail_entries_per_chunk());
         std::swap(src_rows, dst_rows);
@@ -383,6 +385,20 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
     const uint32_t bits = key_bits(sh->V);
 
     const NoiseTable nt{sh->bins, sh->V};
+    if (!sh->overlap) {
+        // one stream: the two sides' keys go through the same sort launches
+        {
+            Phase ph(sh, W2V_PH_NEG, st);
+            launch_dest_keys(nt, out_idx, p.n, k, seed, p.keys, sh->err, st, sh->call_dev);
+        }
+        Phase ph(sh, W2V_PH_SORT, st);
+        launch_check_inputs(in_idx, p.n, sh->V, p.in_safe, sh->err, st);
+        const SortJob jobs[2] = {{p.keys, p.M, p.wb0, p.wb1, skw, sidx},
+                                 {p.in_safe, p.n, p.ub0, p.ub1, sku, perm}};
+        launch_sort_jobs(jobs, 2, bits, p.sort_tmp, sh->err, st);
+        if (p.own_rows) launch_mark_alone(*skw, *sidx, p.M, p.keys, st);
+        return W2V_OK;
+    }
     hipStream_t wst = st;
     if (sh->overlap) {
         int rc = ensure_side_stream(sh);
@@ -393,7 +409,7 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
     }
     {
         Phase ph(sh, W2V_PH_NEG, wst);
-        launch_dest_keys(nt, out_idx, p.n, k, seed, p.keys, sh->err, wst);
+        launch_dest_keys(nt, out_idx, p.n, k, seed, p.keys, sh->err, wst, sh->call_dev);
     }
     if (sh->overlap) HIP_TRY(hipEventRecord(sh->ev_keys, sh->side));
     {
@@ -493,6 +509,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         a.dots_out = (fused && loss_out) ? p.dots : nullptr; a.delta = p.delta; a.dkey = p.dkey;
         a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
         if (p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
+        a.dev = ws_owner->call_dev;
         launch_useg(a, st);
     }
     // The input side's higher levels only touch its slots and the delta buffer, and the loss only
@@ -507,9 +524,9 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
     }
     {
         Phase ph(ws_owner, W2V_PH_APPLY, side);
-        const uint32_t cp = useg_pairs_per_chunk(p.T, sh->g.d4);      // this shard's chunk size
+        const uint32_t cp = useg_pairs_per_chunk(p.T, sh->g.d4, p.n);      // this shard's chunk size
         run_tails(sh, sh->U, alpha, p.pa_rows, p.pa_keys, slots_after(p.n, cp), p.pe_rows, p.pe_keys,
-                  side, p.delta, p.dkey, cp);
+                  side, p.delta, p.dkey, cp, ws_owner->call_dev);
     }
     join_output_sort(ws_owner, st);
     {
@@ -519,6 +536,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         w.in_idx = p.in_safe; w.coeffs = fused ? coeffs_out : coeffs_in; w.alpha = alpha;
         w.prows = p.pb_rows; w.pkeys = p.pb_keys;
         w.skip_alone = p.own_rows;
+        w.dev = ws_owner->call_dev;
         launch_wseg(w, st);
     }
     // After the output-side kernel: its higher levels stay on the caller's stream (no wait in
@@ -530,12 +548,13 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
     }
     {
         Phase ph(ws_owner, W2V_PH_APPLY, side);
-        launch_apply_delta(sh->U, sh->g, p.delta, p.dkey, p.n, alpha, side);
+        launch_apply_delta(sh->U, sh->g, p.delta, p.dkey, p.n, alpha, side, ws_owner->call_dev);
     }
     if (two) (void)hipEventRecord(ws_owner->ev_tails, side);
     {
         Phase ph(ws_owner, W2V_PH_APPLY, st);
-        run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st);
+        run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st, nullptr,
+                  nullptr, 0, ws_owner->call_dev);
     }
     if (two) (void)hipStreamWaitEvent(st, ws_owner->ev_tails, 0);
 }
@@ -1009,6 +1028,121 @@ extern "C" int w2v_prefetch_cancel(w2v_shard* sh) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// a training step captured once and replayed (small minibatches are bound by launches, not bytes)
+// ---------------------------------------------------------------------------------------------
+struct w2v_step_graph {
+    w2v_shard* sh = nullptr;
+    uint32_t n = 0, k = 0;
+    uint32_t* in_stage = nullptr;       // the captured kernels read the minibatch from here
+    uint32_t* out_stage = nullptr;
+    CallScalars* scalars = nullptr;     // ... and its seed and learning rate from here
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+
+__global__ __launch_bounds__(256) void stage_step_kernel(const uint32_t* __restrict__ in_idx,
+                                                         const uint32_t* __restrict__ out_idx,
+                                                         uint32_t n, uint32_t* __restrict__ in_stage,
+                                                         uint32_t* __restrict__ out_stage,
+                                                         CallScalars* __restrict__ scalars,
+                                                         uint32_t seed_lo, uint32_t seed_hi,
+                                                         float alpha) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) { in_stage[i] = in_idx[i]; out_stage[i] = out_idx[i]; }
+    if (i == 0) { scalars->seed_lo = seed_lo; scalars->seed_hi = seed_hi; scalars->alpha = alpha; }
+}
+
+static void free_step_graph(w2v_step_graph* g) {
+    if (!g) return;
+    if (g->exec) (void)hipGraphExecDestroy(g->exec);
+    if (g->graph) (void)hipGraphDestroy(g->graph);
+    if (g->in_stage) (void)hipFree(g->in_stage);
+    if (g->out_stage) (void)hipFree(g->out_stage);
+    if (g->scalars) (void)hipFree(g->scalars);
+    delete g;
+}
+
+extern "C" int w2v_step_graph_create(w2v_shard* sh, uint32_t n, uint32_t k, double* loss,
+                                     w2v_step_graph** out) {
+    if (!sh || !out) return fail(W2V_ERR_NULL, "NULL argument");
+    *out = nullptr;
+    int rc = check_device(sh);
+    if (!rc) rc = check_batch(sh, n, k, true);
+    if (rc) return rc;
+    if (n == 0) return fail(W2V_ERR_ARG, "a captured step needs at least one pair");
+    w2v_step_graph* g = new (std::nothrow) w2v_step_graph();
+    if (!g) return fail(W2V_ERR_ALLOC, "host allocation failed");
+    g->sh = sh; g->n = n; g->k = k;
+    hipStream_t cap = nullptr;
+    auto bail = [&](int code) { if (cap) (void)hipStreamDestroy(cap); free_step_graph(g); return code; };
+    hipError_t e = hipMalloc((void**)&g->in_stage, sizeof(uint32_t) * (size_t)n);
+    if (e == hipSuccess) e = hipMalloc((void**)&g->out_stage, sizeof(uint32_t) * (size_t)n);
+    if (e == hipSuccess) e = hipMalloc((void**)&g->scalars, 256);
+    if (e == hipSuccess) e = hipMemset(g->in_stage, 0, sizeof(uint32_t) * (size_t)n);
+    if (e == hipSuccess) e = hipMemset(g->out_stage, 0, sizeof(uint32_t) * (size_t)n);
+    if (e == hipSuccess) e = hipMemset(g->scalars, 0, 256);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return bail(fail(W2V_ERR_ALLOC, "allocating the staging buffers of a captured step failed: %s",
+                         hipGetErrorString(e)));
+    }
+    // everything the step allocates must exist before the capture begins: its scratch ...
+    const uint32_t own = sh->own_rows ? sh->V : 0u;
+    Plan sz = make_plan(nullptr, n, k, sh->g.stride4, loss ? 1u : 0u, true, true, own);
+    rc = ensure_ws(sh, sz.bytes);
+    if (rc) return bail(rc);
+    e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&cap, hipStreamNonBlocking);
+    if (e != hipSuccess) return bail(fail(W2V_ERR_HIP, "set-up of the capture failed: %s", hipGetErrorString(e)));
+    // ... and the capture runs the step on ONE stream, without timing spans and without looking at
+    // announced minibatches (none can match the staging buffers).  (Captured with its side stream,
+    // as parallel branches of the graph, a 4096-pair step replays in 0.176 ms instead of 0.115 ms:
+    // the two sorts are then separate chains of launches, and branches cost more than they hide.)
+    const bool overlap = sh->overlap, timing = sh->timing;
+    sh->overlap = false; sh->timing = false; sh->call_dev = g->scalars;
+    e = hipStreamBeginCapture(cap, hipStreamCaptureModeThreadLocal);
+    if (e == hipSuccess) {
+        w2v_shard* one[1] = {sh};
+        rc = w2v_train_minibatch(one, 1, g->in_stage, g->out_stage, n, k, 0, 0.f, loss, cap);
+        hipError_t e2 = hipStreamEndCapture(cap, &g->graph);
+        if (rc == W2V_OK && e2 != hipSuccess) e = e2;
+    }
+    sh->overlap = overlap; sh->timing = timing; sh->call_dev = nullptr;
+    if (rc) return bail(rc);
+    if (e == hipSuccess) e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return bail(fail(W2V_ERR_HIP, "capturing the step failed: %s", hipGetErrorString(e)));
+    }
+    (void)hipStreamDestroy(cap);
+    *out = g;
+    return W2V_OK;
+}
+
+extern "C" int w2v_step_graph_run(w2v_step_graph* g, const uint32_t* in_idx, const uint32_t* out_idx,
+                                  uint64_t seed, float alpha, void* stream) {
+    if (!g || !in_idx || !out_idx) return fail(W2V_ERR_NULL, "NULL argument");
+    int rc = check_device(g->sh);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(stage_step_kernel, dim3((g->n + 255) / 256), dim3(256), 0, st, in_idx, out_idx,
+                       g->n, g->in_stage, g->out_stage, g->scalars, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), alpha);
+    HIP_TRY(hipGraphLaunch(g->exec, st));
+    g->sh->updates++;
+    g->sh->last_update_fused = true;
+    HIP_TRY(hipGetLastError());
+    return W2V_OK;
+}
+
+extern "C" int w2v_step_graph_destroy(w2v_step_graph* g) {
+    if (!g) return W2V_OK;
+    (void)hipDeviceSynchronize();
+    free_step_graph(g);
+    return W2V_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // continuous bag of words (Section 5.1, footnote)
 // ---------------------------------------------------------------------------------------------
 namespace {
@@ -1053,7 +1187,7 @@ CbowPlan make_cbow_plan(char* base, uint32_t n, uint32_t k, uint32_t m, uint32_t
         p.sort_tmp_w = c.take<uint32_t>(sort_scratch_u32(p.M));
         p.cb0 = c.take<uint2>(m); p.cb1 = c.take<uint2>(m);
         p.sort_tmp_c = c.take<uint32_t>(sort_scratch_u32(m));
-        p.slots_a = slots_after(n, useg_pairs_per_chunk(p.T, 1));
+        p.slots_a = slots_after(n, useg_pairs_per_chunk(p.T, 1, n));
         p.slots_w1 = slots_after(p.M, wseg_entries_per_chunk());
         p.slots_c1 = slots_after(m, wseg_entries_per_chunk());
         p.slots_2 = std::max(slots_after(p.slots_w1, tail_entries_per_chunk()),

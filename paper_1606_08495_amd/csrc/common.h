@@ -49,6 +49,11 @@ constexpr uint32_t KEY_ZERO = 0x80000000u;   // flag: slot belongs to the row bu
 constexpr uint32_t KEY_MASK = 0x7FFFFFFFu;
 constexpr uint32_t KEY_ALONE = 0x80000000u;  // slot-ordered keys: no other slot names this row
 
+// The per-call scalars a captured graph cannot take as kernel arguments (those are fixed when the
+// graph is captured): where a `dev` pointer is given, the kernels read the minibatch seed and the
+// learning rate from this block in device memory instead of from their arguments.
+struct CallScalars { uint32_t seed_lo, seed_hi; float alpha; uint32_t reserved; };
+
 // ---- launch wrappers (defined in the .hip files) -------------------------------------------------
 struct NoiseTable { const uint2* bins; uint32_t V; };   // {keep threshold, alias} per word
 
@@ -63,7 +68,8 @@ void launch_scatter_rows(float* M, RowGeom g, uint32_t d_slice, const uint32_t* 
 // replaced by 0.  in_safe[p] (launch_check_inputs) is the checked copy of in_idx[p] that every
 // later kernel uses.
 void launch_dest_keys(NoiseTable nt, const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed,
-                      uint32_t* keys, uint32_t* err, hipStream_t st);
+                      uint32_t* keys, uint32_t* err, hipStream_t st,
+                      const CallScalars* dev = nullptr);
 // keys[sidx[i]] |= KEY_ALONE for every sorted entry i whose neighbours carry other keys.
 void launch_mark_alone(const uint32_t* skey, const uint32_t* sidx, uint32_t M, uint32_t* keys,
                        hipStream_t st);
@@ -106,7 +112,7 @@ void launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32
 
 // ---- adjust ------------------------------------------------------------------------------------
 // Chunk sizes of the segmented reductions (entries per lane group).
-uint32_t useg_pairs_per_chunk(uint32_t T, uint32_t d4);   // by slots per pair and row geometry;
+uint32_t useg_pairs_per_chunk(uint32_t T, uint32_t d4, uint32_t n);   // by slots per pair, row geometry and minibatch size;
                                                           // smallest for the narrowest rows (d4 = 1)
 uint32_t wseg_entries_per_chunk();
 uint32_t tail_entries_per_chunk();
@@ -130,6 +136,7 @@ struct USideArgs {
     // of the minibatch names; the kernel then writes W[row] += alpha * g * u itself (nobody else
     // reads or writes that row in this minibatch) and the output side must leave those slots out.
     float* W_update; float alpha;
+    const CallScalars* dev;      // optional: the learning rate is read from here
 };
 void launch_useg(const USideArgs& a, hipStream_t st);
 // Minibatch loss from the dots of the fused step: slot 0 of a pair contributes softplus(-f), the
@@ -146,6 +153,7 @@ struct WSideArgs {
     bool skip_alone;             // entries whose neighbours carry other keys are handled elsewhere
     const uint32_t* in_idx; const float* coeffs; float alpha;
     float* prows; uint32_t* pkeys;
+    const CallScalars* dev;      // optional: the learning rate is read from here
 };
 void launch_wseg(const WSideArgs& a, hipStream_t st);
 
@@ -158,12 +166,13 @@ struct TailArgs {
     // input side only: finished sums go to the delta buffer (rows, keys) instead of into M;
     // level = 1 for the first pass over the input-side kernel's slots, cp = its pairs per chunk
     float* defer_rows = nullptr; uint32_t* defer_keys = nullptr; uint32_t level = 0, cp = 0;
+    const CallScalars* dev = nullptr;      // optional: the learning rate is read from here
 };
 void launch_tail(const TailArgs& a, hipStream_t st);
 
 // U[dkey[ps]] += alpha * delta[ps] wherever dkey[ps] != KEY_NONE.
 void launch_apply_delta(float* U, RowGeom g, const float* delta, const uint32_t* dkey, uint32_t n,
-                        float alpha, hipStream_t st);
+                        float alpha, hipStream_t st, const CallScalars* dev = nullptr);
 
 // ---- pair formation ------------------------------------------------------------------------------
 struct PairArgs {

@@ -38,11 +38,17 @@ constexpr int useg_maxp(int G) { return G == 16 ? 16 : 32; }            // pairs
 constexpr int useg_maxe(int G) {                 // entries, at most: c T < E + T, and 2 T, T <= 65
     return useg_e(G) + 66 < 136 ? 136 : useg_e(G) + 66;
 }
-uint32_t useg_pairs_per_chunk(uint32_t T, uint32_t d4) {
+// A lane group walks its chunk pair by pair, one memory round trip each, so a small minibatch cut
+// into long chunks leaves the chip to a handful of groups (4096 pairs in chunks of 32: 128 groups,
+// 109 us of row latency in a row): below USEG_MIN_CHUNKS chunks the chunks shrink, down to two pairs.
+constexpr uint32_t USEG_MIN_CHUNKS = 4096;
+uint32_t useg_pairs_per_chunk(uint32_t T, uint32_t d4, uint32_t n) {
     const int G = d4 <= 16 ? 16 : (d4 <= 32 ? 32 : 64);                 // as W2V_DISPATCH_GEOM
     uint32_t c = ((uint32_t)useg_e(G) + T - 1) / T;
     if (c < 2) c = 2;
     if (c > (uint32_t)useg_maxp(G)) c = useg_maxp(G);
+    const uint32_t fill = n / USEG_MIN_CHUNKS;                          // pairs per chunk that still give that many
+    if (c > fill) c = fill < 2 ? 2 : fill;
     return c;
 }
 
@@ -68,6 +74,7 @@ struct SegArgs {
     // DEFER: finished sums are not added to dst but parked in the input side's delta buffer
     float4* defer_rows; uint32_t* defer_keys;
     uint32_t level, cp;                // level of this pass (1 = first), pairs per input-side chunk
+    const CallScalars* dev;            // optional: the learning rate is read from here
 };
 
 // DEFER (higher levels of the input side): a run finished here must not touch the input matrix
@@ -80,6 +87,7 @@ struct SegArgs {
 template <int G, int NV, int C, int D, int SRC, bool DEFER = false>
 __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
     static_assert(C <= G && C % D == 0, "chunk must fit a lane group");
+    const float alpha = a.dev ? a.dev->alpha : a.alpha;
     const int l = threadIdx.x % G;
     const uint32_t c = (blockIdx.x * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
     const uint32_t nchunks = (a.entries + C - 1) / C;
@@ -178,10 +186,10 @@ __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
                     float4 out[NV];
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
-                        out[v].x = fmaf(a.alpha, acc[v].x, dstv[t][v].x);
-                        out[v].y = fmaf(a.alpha, acc[v].y, dstv[t][v].y);
-                        out[v].z = fmaf(a.alpha, acc[v].z, dstv[t][v].z);
-                        out[v].w = fmaf(a.alpha, acc[v].w, dstv[t][v].w);
+                        out[v].x = fmaf(alpha, acc[v].x, dstv[t][v].x);
+                        out[v].y = fmaf(alpha, acc[v].y, dstv[t][v].y);
+                        out[v].z = fmaf(alpha, acc[v].z, dstv[t][v].z);
+                        out[v].w = fmaf(alpha, acc[v].w, dstv[t][v].w);
                     }
                     store_row<G, NV>(a.dst + (uint64_t)dk * s4, d4, l, out);
                 } else if (ih && rl) {      // the run came in from the previous chunk and ends here
@@ -247,6 +255,7 @@ __global__ __launch_bounds__(wown_threads(G)) void wown_kernel(SegArgs a) {
     constexpr int GROUPS = WOWN_THREADS / G;
     constexpr int C = WOWN_C, L = WOWN_L;
     static_assert(L % C == 0 && C == 16 && G >= 16, "grid shapes");
+    const float alpha = a.dev ? a.dev->alpha : a.alpha;
     __shared__ uint32_t s_key[GROUPS][WOWN_WIN];
     __shared__ uint32_t s_srow[GROUPS][WOWN_E];
     __shared__ float s_coef[GROUPS][WOWN_E];
@@ -318,10 +327,10 @@ __global__ __launch_bounds__(wown_threads(G)) void wown_kernel(SegArgs a) {
         float4 out[NV];
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            out[v].x = fmaf(a.alpha, acc[v].x, old[v].x);
-            out[v].y = fmaf(a.alpha, acc[v].y, old[v].y);
-            out[v].z = fmaf(a.alpha, acc[v].z, old[v].z);
-            out[v].w = fmaf(a.alpha, acc[v].w, old[v].w);
+            out[v].x = fmaf(alpha, acc[v].x, old[v].x);
+            out[v].y = fmaf(alpha, acc[v].y, old[v].y);
+            out[v].z = fmaf(alpha, acc[v].z, old[v].z);
+            out[v].w = fmaf(alpha, acc[v].w, old[v].w);
         }
         store_row_nt<G, NV>(a.dst + (uint64_t)row * s4, d4, l, out);
     };
@@ -420,7 +429,7 @@ void launch_wseg(const WSideArgs& w, hipStream_t st) {
     SegArgs a{};
     a.src = (const float4*)w.U; a.dst = (float4*)w.W; a.g = w.g; a.skey = w.skey; a.sidx = w.sidx;
     a.in_idx = w.in_idx; a.coeffs = w.coeffs; a.entries = w.M; a.T = w.T;
-    a.alpha = w.alpha; a.prows = (float4*)w.prows; a.pkeys = w.pkeys;
+    a.alpha = w.alpha; a.prows = (float4*)w.prows; a.pkeys = w.pkeys; a.dev = w.dev;
     a.skip_alone = w.skip_alone;
     // border slots of the cells: only pieces of long runs write them
     uint32_t ncells = (w.M + WOWN_L - 1) / WOWN_L;
@@ -444,7 +453,7 @@ void launch_tail(const TailArgs& t, hipStream_t st) {
     a.src = (const float4*)t.src_rows; a.dst = (float4*)t.M; a.g = t.g; a.skey = t.src_keys;
     a.sidx = nullptr; a.in_idx = nullptr; a.coeffs = nullptr; a.entries = t.entries; a.T = 1;
     a.skip_alone = false;
-    a.alpha = t.alpha; a.prows = (float4*)t.prows; a.pkeys = t.pkeys;
+    a.alpha = t.alpha; a.prows = (float4*)t.prows; a.pkeys = t.pkeys; a.dev = t.dev;
     a.defer_rows = (float4*)t.defer_rows; a.defer_keys = t.defer_keys; a.level = t.level; a.cp = t.cp;
     uint32_t nchunks = (t.entries + TAIL_C - 1) / TAIL_C;
 #define CALL(G, NV)                                                                              \
@@ -478,6 +487,7 @@ __device__ __forceinline__ float sigmoid_of_minus(float x) { return 1.0f / (1.0f
 template <int G, int NV, int TB, bool FUSED, bool OWN>
 __global__ __launch_bounds__(USEG_THREADS) void useg_kernel(USideArgs a, uint32_t CP) {
     constexpr bool NEED_U = FUSED || OWN;      // the pair's input row: for the dots, for own rows
+    const float alpha = a.dev ? a.dev->alpha : a.alpha;
     constexpr int GROUPS = USEG_THREADS / G;
     // The chunk's indices are staged in LDS first (two dependent gathers for the whole chunk), so
     // that the row loads of the main loop depend on nothing but LDS reads.
@@ -582,10 +592,10 @@ __global__ __launch_bounds__(USEG_THREADS) void useg_kernel(USideArgs a, uint32_
                         float4 out[NV];
 #pragma unroll
                         for (int v = 0; v < NV; ++v) {
-                            out[v].x = fmaf(a.alpha, fmaf(gco[t], u[v].x, 0.f), w[t][v].x);
-                            out[v].y = fmaf(a.alpha, fmaf(gco[t], u[v].y, 0.f), w[t][v].y);
-                            out[v].z = fmaf(a.alpha, fmaf(gco[t], u[v].z, 0.f), w[t][v].z);
-                            out[v].w = fmaf(a.alpha, fmaf(gco[t], u[v].w, 0.f), w[t][v].w);
+                            out[v].x = fmaf(alpha, fmaf(gco[t], u[v].x, 0.f), w[t][v].x);
+                            out[v].y = fmaf(alpha, fmaf(gco[t], u[v].y, 0.f), w[t][v].y);
+                            out[v].z = fmaf(alpha, fmaf(gco[t], u[v].z, 0.f), w[t][v].z);
+                            out[v].w = fmaf(alpha, fmaf(gco[t], u[v].w, 0.f), w[t][v].w);
                         }
                         store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(rr & ~ALONE) * s4, d4, l, out);
                     }
@@ -646,6 +656,7 @@ __global__ __launch_bounds__(USEG_THREADS) void useg_kernel(USideArgs a, uint32_
 template <int G, int NV, int T, int PB, bool FUSED, bool OWN>
 __global__ __launch_bounds__(USEG_THREADS, 5) void useg_multi_kernel(USideArgs a, uint32_t CP) {
     constexpr bool NEED_U = FUSED || OWN;
+    const float alpha = a.dev ? a.dev->alpha : a.alpha;
     constexpr int GROUPS = USEG_THREADS / G;
     constexpr int MAXP = useg_maxp(G), MAXE = MAXP * T;
     __shared__ uint32_t s_key[GROUPS][MAXE];
@@ -750,10 +761,10 @@ __global__ __launch_bounds__(USEG_THREADS, 5) void useg_multi_kernel(USideArgs a
                             float4 out[NV];
 #pragma unroll
                             for (int v = 0; v < NV; ++v) {
-                                out[v].x = fmaf(a.alpha, fmaf(gco[j], u[b][v].x, 0.f), w[b][j][v].x);
-                                out[v].y = fmaf(a.alpha, fmaf(gco[j], u[b][v].y, 0.f), w[b][j][v].y);
-                                out[v].z = fmaf(a.alpha, fmaf(gco[j], u[b][v].z, 0.f), w[b][j][v].z);
-                                out[v].w = fmaf(a.alpha, fmaf(gco[j], u[b][v].w, 0.f), w[b][j][v].w);
+                                out[v].x = fmaf(alpha, fmaf(gco[j], u[b][v].x, 0.f), w[b][j][v].x);
+                                out[v].y = fmaf(alpha, fmaf(gco[j], u[b][v].y, 0.f), w[b][j][v].y);
+                                out[v].z = fmaf(alpha, fmaf(gco[j], u[b][v].z, 0.f), w[b][j][v].z);
+                                out[v].w = fmaf(alpha, fmaf(gco[j], u[b][v].w, 0.f), w[b][j][v].w);
                             }
                             store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(r & ~ALONE) * s4, d4,
                                                 l, out);
@@ -812,7 +823,7 @@ static void launch_useg_fixed(const USideArgs& a, uint32_t CP, dim3 grid, dim3 b
 
 template <int G, int NV>
 static void launch_useg_shape(const USideArgs& a, hipStream_t st) {
-    const uint32_t CP = useg_pairs_per_chunk(a.T, a.g.d4);
+    const uint32_t CP = useg_pairs_per_chunk(a.T, a.g.d4, a.n);
     const uint32_t nchunks = (a.n + CP - 1) / CP;
     dim3 grid(blocks_for((uint64_t)nchunks * G, USEG_THREADS)), block(USEG_THREADS);
     if constexpr (NV <= 2) {
@@ -844,7 +855,9 @@ template <int G, int NV>
 __global__ __launch_bounds__(ADJ_THREADS) void apply_delta_kernel(float4* __restrict__ U, RowGeom g,
                                                                   const float4* __restrict__ delta,
                                                                   const uint32_t* __restrict__ dkey,
-                                                                  uint32_t n, float alpha) {
+                                                                  uint32_t n, float alpha_arg,
+                                                                  const CallScalars* dev) {
+    const float alpha = dev ? dev->alpha : alpha_arg;
     const int l = threadIdx.x % G;
     const uint32_t grp = (blockIdx.x * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
     const uint32_t base = grp * (uint32_t)G;
@@ -869,11 +882,11 @@ __global__ __launch_bounds__(ADJ_THREADS) void apply_delta_kernel(float4* __rest
 }
 
 void launch_apply_delta(float* U, RowGeom g, const float* delta, const uint32_t* dkey, uint32_t n,
-                        float alpha, hipStream_t st) {
+                        float alpha, hipStream_t st, const CallScalars* dev) {
     if (n == 0) return;
 #define CALL(G, NV)                                                                              \
     hipLaunchKernelGGL((apply_delta_kernel<G, NV>), dim3(blocks_for(n, ADJ_THREADS)),            \
-                       dim3(ADJ_THREADS), 0, st, (float4*)U, g, (const float4*)delta, dkey, n, alpha)
+                       dim3(ADJ_THREADS), 0, st, (float4*)U, g, (const float4*)delta, dkey, n, alpha, dev)
     W2V_DISPATCH_GEOM(g.d4, CALL);
 #undef CALL
 }

@@ -108,11 +108,12 @@ void launch_scatter_rows(float* M, RowGeom g, uint32_t d_slice, const uint32_t* 
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void dest_keys_kernel(const uint2* __restrict__ bins, uint32_t V,
                                                         const uint32_t* __restrict__ out_idx,
-                                                        uint32_t n, uint32_t T, uint32_t k0,
-                                                        uint32_t k1, uint32_t* __restrict__ keys,
-                                                        uint32_t* err) {
+                                                        uint32_t n, uint32_t T, uint32_t k0_arg,
+                                                        uint32_t k1_arg, uint32_t* __restrict__ keys,
+                                                        uint32_t* err, const CallScalars* dev) {
     uint32_t i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n * T) return;
+    const uint32_t k0 = dev ? dev->seed_lo : k0_arg, k1 = dev ? dev->seed_hi : k1_arg;
     uint32_t p = i / T, j = i - p * T;
     uint32_t wo = out_idx[p];
     if (wo >= V) { wo = 0; if (j == 0) atomicOr(err, 1u); }
@@ -149,12 +150,12 @@ __global__ __launch_bounds__(256) void mark_alone_kernel(const uint32_t* __restr
 }
 
 void launch_dest_keys(NoiseTable nt, const uint32_t* out_idx, uint32_t n, uint32_t k, uint64_t seed,
-                      uint32_t* keys, uint32_t* err, hipStream_t st) {
+                      uint32_t* keys, uint32_t* err, hipStream_t st, const CallScalars* dev) {
     if (n == 0) return;
     uint32_t T = k + 1;
     hipLaunchKernelGGL(dest_keys_kernel, dim3(blocks_for((uint64_t)n * T, 256)), dim3(256), 0, st,
                        nt.bins, nt.V, out_idx, n, T, (uint32_t)seed, (uint32_t)(seed >> 32), keys,
-                       err);
+                       err, dev);
 }
 
 void launch_mark_alone(const uint32_t* skey, const uint32_t* sidx, uint32_t M, uint32_t* keys,

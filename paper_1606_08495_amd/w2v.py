@@ -39,6 +39,9 @@ _SIGNATURES = {
     "w2v_adjust": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp, ctypes.c_float, c_vp]),
     "w2v_train_minibatch": (ctypes.c_int, [ctypes.POINTER(c_vp), c_u32, c_vp, c_vp, c_u32, c_u32,
                                            c_u64, ctypes.c_float, c_vp, c_vp]),
+    "w2v_step_graph_create": (ctypes.c_int, [c_vp, c_u32, c_u32, c_vp, ctypes.POINTER(c_vp)]),
+    "w2v_step_graph_run": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u64, ctypes.c_float, c_vp]),
+    "w2v_step_graph_destroy": (ctypes.c_int, [c_vp]),
     "w2v_prefetch_minibatch": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u64, c_vp]),
     "w2v_cbow_prefetch_minibatch": (ctypes.c_int, [c_vp, c_vp, c_vp, c_u32, c_vp, c_u32, c_u32, c_u64,
                                                    c_vp]),
@@ -296,6 +299,34 @@ class Shard:
         cnt = np.zeros(len(PHASES), np.uint64)
         _check(lib().w2v_shard_timing_read(self.h, c_vp(ms.ctypes.data), c_vp(cnt.ctypes.data)))
         return {PHASES[i]: (float(ms[i]), int(cnt[i])) for i in range(len(PHASES))}
+
+
+class StepGraph:
+    """w2v_step_graph: w2v_train_minibatch on one shard for a fixed (n, k), captured once and replayed."""
+
+    def __init__(self, shard, n, k, loss=None):
+        self.n, self.k, self.shard, self.loss = int(n), int(k), shard, loss
+        h = c_vp(0)
+        _check(lib().w2v_step_graph_create(shard.h, self.n, self.k, _dev(loss, torch.float64, "loss"),
+                                           ctypes.byref(h)))
+        self.h = h
+
+    def run(self, in_idx, out_idx, seed, alpha, stream=None):
+        if in_idx.numel() != self.n or out_idx.numel() != self.n:
+            raise ValueError("the graph was captured for %d pairs" % self.n)
+        _check(lib().w2v_step_graph_run(self.h, _dev(in_idx, IDX, "in_idx"), _dev(out_idx, IDX, "out_idx"),
+                                        int(seed), float(alpha), _stream(stream)))
+
+    def destroy(self):
+        if getattr(self, "h", None):
+            lib().w2v_step_graph_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
 
 
 def train_minibatch(shards, in_idx, out_idx, k, seed, alpha, loss=None, stream=None):

@@ -440,6 +440,96 @@ def test_tiny_config_hundred_minibatches():
     sh.destroy()
 
 
+@pytest.mark.parametrize("V,d,n,k,mode", [(10_000, 100, 4096, 5, 0), (3000, 300, 1000, 5, 1),
+                                          (500, 60, 257, 10, 1), (40, 64, 1, 0, 1)])
+def test_captured_step_replays_give_the_same_bits_as_the_plain_call(V, d, n, k, mode):
+    """w2v_step_graph: every replay (different indices, seed and learning rate each time, eager
+    work and synchronisations in between) must leave the same bits as w2v_train_minibatch on a
+    shard that was never captured, the loss included -- and both agree with the oracle."""
+    say("captured step", V, d, n, k, mode)
+    rng = np.random.default_rng(V + n)
+    counts = zipf_counts(V)
+    cdf = workloads.zipf_cdf(V, 1.0)
+    plain = make_shard(V, d, 9, counts, init_mode=mode)
+    graphed = make_shard(V, d, 9, counts, init_mode=mode)
+    U, W = oracle_state(V, d, 9, init_mode=mode)
+    th, al = oracle.build_alias(counts)
+    la = torch.zeros(1, dtype=torch.float64, device="cuda")
+    lb = torch.zeros(1, dtype=torch.float64, device="cuda")
+    graph = w2v.StepGraph(graphed, n, k, loss=lb)
+    steps = 7
+    for h in range(steps):
+        in_idx, out_idx = workloads.zipf_draw(cdf, n, rng), workloads.zipf_draw(cdf, n, rng)
+        a, b = dev(in_idx), dev(out_idx)
+        seed, alpha = w2v.minibatch_seed(77, h), 0.05 / (1 + h)
+        w2v.train_minibatch([plain], a, b, k, seed, alpha, loss=la)
+        graph.run(a, b, seed, alpha)
+        if h % 2:                                # eager work on the captured shard between replays
+            assert np.array_equal(graphed.dotprod(a, b, k, seed).cpu().numpy(),
+                                  plain.dotprod(a, b, k, seed).cpu().numpy())
+        torch.cuda.synchronize()
+        assert la.item() == lb.item(), h
+        for which in (0, 1):
+            assert np.array_equal(all_rows(graphed, which), all_rows(plain, which)), (h, which)
+        ref_loss = oracle.train_minibatch([U], [W], in_idx, out_idx, k, seed, th, al, alpha)
+        assert abs(lb.item() - ref_loss) <= 1e-5 * abs(ref_loss) + 1e-12
+    assert vec_error(all_rows(graphed, 0), U) <= steps * TOL1
+    assert vec_error(all_rows(graphed, 1), W) <= steps * TOL1
+    # a plain call on the captured shard in between leaves the graph usable
+    a, b = dev(workloads.zipf_draw(cdf, n, rng)), dev(workloads.zipf_draw(cdf, n, rng))
+    w2v.train_minibatch([graphed], a, b, k, 5, 0.01)
+    w2v.train_minibatch([plain], a, b, k, 5, 0.01)
+    graph.run(b, a, 6, 0.02)
+    w2v.train_minibatch([plain], b, a, k, 6, 0.02, loss=la)
+    torch.cuda.synchronize()
+    assert la.item() == lb.item()
+    for which in (0, 1):
+        assert np.array_equal(all_rows(graphed, which), all_rows(plain, which))
+    with pytest.raises(ValueError):
+        graph.run(a[:-1], b[:-1], 1, 0.1) if n > 1 else graph.run(torch.cat([a, a]), torch.cat([b, b]), 1, 0.1)
+    graph.destroy()
+    for sh in (plain, graphed):
+        sh.status()
+        sh.destroy()
+
+
+def test_tiny_config_hundred_minibatches_through_the_captured_step():
+    # BASELINE config 1 again, every minibatch a replay of one captured step
+    wl = workloads.WORKLOADS["tiny"]
+    tokens, off = workloads.corpus(wl)
+    counts = workloads.counted(tokens, wl.V)
+    sh = make_shard(wl.V, wl.d_slice, wl.seed, counts, wl.subsample_t, init_mode=0)
+    U, W = oracle_state(wl.V, wl.d_slice, wl.seed, init_mode=0)
+    th, al = oracle.build_alias(counts)
+    kt = oracle.build_keep(counts, wl.subsample_t)
+    cap = tokens.size * 2 * wl.window
+    gi = torch.empty(cap, dtype=torch.int32, device="cuda")
+    go = torch.empty(cap, dtype=torch.int32, device="cuda")
+    cnt = sh.make_pairs(dev(tokens), torch.from_numpy(off.astype(np.int64)).cuda(), 0, 0, wl.seed,
+                        wl.window, gi, go)
+    oi, oo, ocnt = oracle.make_pairs(tokens, off, 0, 0, wl.seed, wl.window, kt)
+    assert cnt == ocnt and cnt // wl.n_pairs >= 100
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    graph = w2v.StepGraph(sh, wl.n_pairs, wl.k, loss=loss)
+    losses, ref_losses = [], []
+    for h in range(100):
+        a, b = h * wl.n_pairs, (h + 1) * wl.n_pairs
+        seed = w2v.minibatch_seed(wl.seed, h)
+        graph.run(gi[a:b], go[a:b], seed, wl.alpha)
+        losses.append(loss.item())
+        ref_losses.append(oracle.train_minibatch([U], [W], oi[a:b], oo[a:b], wl.k, seed, th, al, wl.alpha))
+        if h == 0:
+            e1 = max(vec_error(all_rows(sh, 0), U), vec_error(all_rows(sh, 1), W))
+            assert e1 <= TOL1
+    eu, ew = vec_error(all_rows(sh, 0), U), vec_error(all_rows(sh, 1), W)
+    say("  captured step, after 100 minibatches:", eu, ew, "loss", losses[0], "->", losses[-1])
+    assert eu <= TOL100 and ew <= TOL100
+    assert np.allclose(losses, ref_losses, rtol=1e-4)
+    graph.destroy()
+    sh.status()
+    sh.destroy()
+
+
 # --- pair formation: bit exact -------------------------------------------------------------------------
 
 @pytest.mark.parametrize("B,t", [(1, 0.0), (5, 1e-3), (10, 1e-2), (3, 1e9)])
