@@ -133,7 +133,7 @@ void launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32
 // next pass will use, so no pass starts on stale states and nothing is cleared between passes.
 // ---------------------------------------------------------------------------------------------
 constexpr int SORT_THREADS = 256;                    // of the totals kernel
-constexpr uint32_t SORT_SMALL_N = 1u << 21;
+constexpr uint32_t SORT_SMALL_N = 1u << 19;
 constexpr int SORT_MAX_PASSES = 4;
 constexpr uint32_t SORT_SPIN_LIMIT = 1u << 22;       // fruitless look-back polls before giving up (~ a second)
 constexpr int LB_WINDOW = 8;                         // tiles examined per look-back round
@@ -141,7 +141,8 @@ constexpr uint64_t ST_PARTIAL = 1ull << 62, ST_INCLUSIVE = 2ull << 62, ST_VALUE 
 // Tile shapes.  Large inputs: 512 threads x 16 elements = 8192 per tile -- with 256 digits a digit's
 // run in a tile is 32 elements, 256 bytes, on average (tiles of 4096 measured 15 % slower, and
 // 1024 threads x 8 or 512 x 8 slower still).  Below SORT_SMALL_N elements: 256 x 4, so that small
-// sorts still spread over the chip.
+// sorts still spread over the chip (2^18 keys: 51 us against 60; from 2^20 keys on the large shape
+// wins, 77 us against 123: fewer tiles, shorter look-back).
 static inline int sort_shape_for(uint64_t n) { return n < SORT_SMALL_N ? 0 : 1; }
 static inline uint32_t sort_tile_of(int shape) { return shape == 0 ? 1024u : 8192u; }
 
