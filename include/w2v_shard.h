@@ -175,8 +175,9 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
  * k, seed, alpha, loss).  loss_dev (may be NULL) is fixed at creation and written by every run.
  * The captured step runs on one stream and uses the shard's scratch like any other call: order it
  * with other calls on the shard through `stream`.  Creating the graph allocates and synchronises;
- * running it does neither.  Calls between creation and a run that need a larger scratch region
- * (a larger n or k on the same shard) invalidate the graph: create it again. */
+ * running it does neither.  A call between creation and a run that needs a larger scratch region
+ * (a larger n or k on the same shard) invalidates the graph: w2v_step_graph_run then returns
+ * W2V_ERR_STATE and the graph has to be created again. */
 typedef struct w2v_step_graph w2v_step_graph;
 int w2v_step_graph_create(w2v_shard* shard, uint32_t n, uint32_t k, double* loss_dev,
                           w2v_step_graph** out);

@@ -1036,6 +1036,7 @@ struct w2v_step_graph {
     uint32_t* in_stage = nullptr;       // the captured kernels read the minibatch from here
     uint32_t* out_stage = nullptr;
     CallScalars* scalars = nullptr;     // ... and its seed and learning rate from here
+    const char* ws_at_capture = nullptr; // the shard's scratch region the captured kernels point into
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
 };
@@ -1115,6 +1116,7 @@ extern "C" int w2v_step_graph_create(w2v_shard* sh, uint32_t n, uint32_t k, doub
         return bail(fail(W2V_ERR_HIP, "capturing the step failed: %s", hipGetErrorString(e)));
     }
     (void)hipStreamDestroy(cap);
+    g->ws_at_capture = sh->ws;
     *out = g;
     return W2V_OK;
 }
@@ -1124,6 +1126,9 @@ extern "C" int w2v_step_graph_run(w2v_step_graph* g, const uint32_t* in_idx, con
     if (!g || !in_idx || !out_idx) return fail(W2V_ERR_NULL, "NULL argument");
     int rc = check_device(g->sh);
     if (rc) return rc;
+    if (g->sh->ws != g->ws_at_capture)
+        return fail(W2V_ERR_STATE, "the shard's scratch region was reallocated by a larger call after this "
+                    "step was captured: create the graph again");
     hipStream_t st = (hipStream_t)stream;
     hipLaunchKernelGGL(stage_step_kernel, dim3((g->n + 255) / 256), dim3(256), 0, st, in_idx, out_idx,
                        g->n, g->in_stage, g->out_stage, g->scalars, (uint32_t)seed,

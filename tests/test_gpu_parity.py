@@ -487,6 +487,12 @@ def test_captured_step_replays_give_the_same_bits_as_the_plain_call(V, d, n, k, 
         assert np.array_equal(all_rows(graphed, which), all_rows(plain, which))
     with pytest.raises(ValueError):
         graph.run(a[:-1], b[:-1], 1, 0.1) if n > 1 else graph.run(torch.cat([a, a]), torch.cat([b, b]), 1, 0.1)
+    # a larger call moves the shard's scratch region: the captured step must refuse to run
+    big = dev(rng.integers(0, V, 8 * n + 4096))
+    w2v.train_minibatch([graphed], big, big, k, 9, 0.0)
+    with pytest.raises(w2v.W2VError) as e:
+        graph.run(a, b, 7, 0.01)
+    assert e.value.code == -5
     graph.destroy()
     for sh in (plain, graphed):
         sh.status()
