@@ -501,6 +501,9 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
     // (loss_out: fused form only; the dots it is formed from go to p.dots)
     const bool two = ws_owner->overlap && ws_owner->side;
     hipStream_t side = two ? ws_owner->side : st;
+    // the output-side kernel's border slots are cleared here, ahead of the input-side kernel, so
+    // that the two row kernels follow each other with nothing in between
+    launch_wseg_fill(p.pb_keys, p.M, st);
     {
         Phase ph(ws_owner, W2V_PH_USIDE, st);
         USideArgs a{};
@@ -537,7 +540,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         w.prows = p.pb_rows; w.pkeys = p.pb_keys;
         w.skip_alone = p.own_rows;
         w.dev = ws_owner->call_dev;
-        launch_wseg(w, st);
+        launch_wseg(w, st, true);
     }
     // After the output-side kernel: its higher levels stay on the caller's stream (no wait in
     // between), the write-back of the delta buffer goes to the second stream, behind the input
@@ -1280,6 +1283,10 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
                        const uint32_t* sidx, const uint32_t* skc, const uint32_t* cidx,
                        const float* coeffs_in, float* coeffs_out, float* dots_out, bool fused,
                        float alpha, bool join_sorts, hipStream_t st) {
+    // border slots of both write-back kernels, cleared ahead of the per-example pass (the second
+    // stream's kernel starts behind an event recorded after that pass)
+    launch_wseg_fill(p.pd_keys, p.m, st);
+    launch_wseg_fill(p.pb_keys, p.M, st);
     {
         Phase ph(owner, W2V_PH_USIDE, st);
         USideArgs a{};
@@ -1302,7 +1309,7 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
         u.U = p.E; u.W = sh->U; u.g = sh->g; u.skey = skc; u.sidx = cidx; u.M = p.m; u.T = 1;
         u.in_idx = p.ex_of; u.coeffs = p.weight; u.alpha = alpha;
         u.prows = p.pd_rows; u.pkeys = p.pd_keys;
-        launch_wseg(u, side);
+        launch_wseg(u, side, true);
         run_tails(sh, sh->U, alpha, p.pd_rows, p.pd_keys, p.slots_c1, p.pe_rows, p.pe_keys, side);
     }
     if (two) (void)hipEventRecord(owner->ev_tails, side);
@@ -1314,7 +1321,7 @@ void queue_cbow_adjust(w2v_shard* owner, w2v_shard* sh, CbowPlan& p, const uint3
         w.in_idx = p.iota; w.coeffs = fused ? coeffs_out : coeffs_in; w.alpha = alpha;
         w.prows = p.pb_rows; w.pkeys = p.pb_keys;
         w.skip_alone = fused && p.own_rows;
-        launch_wseg(w, st);
+        launch_wseg(w, st, true);
         run_tails(sh, sh->W, alpha, p.pb_rows, p.pb_keys, p.slots_w1, p.pc_rows, p.pc_keys, st);
     }
     if (two) (void)hipStreamWaitEvent(st, owner->ev_tails, 0);

@@ -155,7 +155,10 @@ struct WSideArgs {
     float* prows; uint32_t* pkeys;
     const CallScalars* dev;      // optional: the learning rate is read from here
 };
-void launch_wseg(const WSideArgs& a, hipStream_t st);
+// (the cells' border slots must read KEY_NONE when the kernel starts: launch_wseg_fill writes that;
+// launch_wseg does it itself unless told that the caller already has)
+void launch_wseg_fill(uint32_t* pkeys, uint32_t M, hipStream_t st);
+void launch_wseg(const WSideArgs& a, hipStream_t st, bool filled = false);
 
 // Higher levels (both sides): entries are partial rows src_rows[i] with destination src_keys[i]
 // (KEY_NONE = nothing, KEY_ZERO flag = belongs to the run but empty).

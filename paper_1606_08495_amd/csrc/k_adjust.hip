@@ -424,19 +424,24 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ x,
     if (i < n) x[i] = value;
 }
 
-void launch_wseg(const WSideArgs& w, hipStream_t st) {
+void launch_wseg_fill(uint32_t* pkeys, uint32_t M, hipStream_t st) {
+    if (M == 0) return;
+    // border slots of the cells: only pieces of long runs write them
+    uint32_t ncells = (M + WOWN_L - 1) / WOWN_L;
+    uint32_t slots = 2 * (ncells - 1);
+    if (slots)
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(slots, 256)), dim3(256), 0, st, pkeys,
+                           slots, KEY_NONE);
+}
+
+void launch_wseg(const WSideArgs& w, hipStream_t st, bool filled) {
     if (w.M == 0) return;
     SegArgs a{};
     a.src = (const float4*)w.U; a.dst = (float4*)w.W; a.g = w.g; a.skey = w.skey; a.sidx = w.sidx;
     a.in_idx = w.in_idx; a.coeffs = w.coeffs; a.entries = w.M; a.T = w.T;
     a.alpha = w.alpha; a.prows = (float4*)w.prows; a.pkeys = w.pkeys; a.dev = w.dev;
     a.skip_alone = w.skip_alone;
-    // border slots of the cells: only pieces of long runs write them
-    uint32_t ncells = (w.M + WOWN_L - 1) / WOWN_L;
-    uint32_t slots = 2 * (ncells - 1);
-    if (slots)
-        hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(slots, 256)), dim3(256), 0, st, w.pkeys,
-                           slots, KEY_NONE);
+    if (!filled) launch_wseg_fill(w.pkeys, w.M, st);
     uint32_t nchunks = (w.M + WOWN_C - 1) / WOWN_C;
 #define CALL(G, NV)                                                                              \
     hipLaunchKernelGGL((wown_kernel<G, NV, (NV <= 2 ? 4 : 2)>),                                   \
