@@ -167,12 +167,15 @@ int w2v_make_pairs(w2v_shard* shard, const uint32_t* tokens_dev, const uint64_t*
 
 /* ---- a training step captured once and replayed (the paper's minibatch sizes) ----------------------
  * Section 6.2 and Section 7.1 train with minibatches of 200, 50 or a single input word -- a few
- * thousand pairs at most.  At that size a step is a chain of some thirty small kernels and its time
+ * thousand pairs at most.  At that size a step is a chain of some twenty small kernels and its time
  * is their launches.  w2v_step_graph_create captures w2v_train_minibatch(S = 1) for a fixed (n, k)
- * on this shard into a HIP graph; w2v_step_graph_run copies the minibatch's indices, seed and
- * learning rate into the graph's own staging block (one small kernel) and replays it on `stream`:
- * the same kernels on the same data, hence the same bits as w2v_train_minibatch(in_idx, out_idx, n,
- * k, seed, alpha, loss).  loss_dev (may be NULL) is fixed at creation and written by every run.
+ * on this shard into a HIP graph, all but the step's first kernel, the only one that reads the
+ * caller's arrays (it forms the destination keys and the checked input words); w2v_step_graph_run
+ * queues that kernel on `stream` with this run's arrays, seed and learning rate (the last two it
+ * also leaves in device memory, where the captured kernels read them) and replays the graph behind
+ * it: the same kernels on the same data, hence the same bits as w2v_train_minibatch(in_idx, out_idx,
+ * n, k, seed, alpha, loss).  The two arrays are read only by work queued on `stream` during the
+ * call.  loss_dev (may be NULL) is fixed at creation and written by every run.
  * The captured step runs on one stream and uses the shard's scratch like any other call: order it
  * with other calls on the shard through `stream`.  Creating the graph allocates and synchronises;
  * running it does neither.  A call between creation and a run that needs a larger scratch region

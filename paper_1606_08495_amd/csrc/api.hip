@@ -135,6 +135,9 @@ struct w2v_shard {
     uint32_t* err = nullptr;        // sticky device flag
     uint32_t* static_ws = nullptr;  // this device's copy of the no-allocation scratch array
     uint64_t updates = 0;           // update calls seen (adjust / train_minibatch, either variant)
+    IndexPrologue* prologue_sink = nullptr;  // set while a step is captured: the first launch of the
+                                             // step is not queued but handed back (it takes the
+                                             // caller's arrays, which change from call to call)
     const CallScalars* call_dev = nullptr;   // set while a step is captured into a graph: the
                                     // kernels then read seed and learning rate from device memory
     // scratch: one region, carved per call
@@ -273,6 +276,7 @@ struct Plan {
     float* pc_rows; uint32_t* pc_keys;     // level 2 slots, output side
     float* pe_rows; uint32_t* pe_keys;     // level 2 slots, input side (the two sides' tails may overlap)
     uint32_t slots_u1, slots_w1, slots_2;
+    bool wfill_done;                       // the output side's border slots are cleared already
     size_t bytes;
 };
 
@@ -386,16 +390,25 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
 
     const NoiseTable nt{sh->bins, sh->V};
     if (!sh->overlap) {
-        // one stream: the two sides' keys go through the same sort launches
-        {
-            Phase ph(sh, W2V_PH_NEG, st);
-            launch_dest_keys(nt, out_idx, p.n, k, seed, p.keys, sh->err, st, sh->call_dev);
-        }
-        Phase ph(sh, W2V_PH_SORT, st);
-        launch_check_inputs(in_idx, p.n, sh->V, p.in_safe, sh->err, st);
+        // one stream: keys, checked inputs and both fills in one launch, then the two sides' keys
+        // through the same sort launches
         const SortJob jobs[2] = {{p.keys, p.M, p.wb0, p.wb1, skw, sidx},
                                  {p.in_safe, p.n, p.ub0, p.ub1, sku, perm}};
-        launch_sort_jobs(jobs, 2, bits, p.sort_tmp, sh->err, st);
+        {
+            Phase ph(sh, W2V_PH_NEG, st);
+            IndexPrologue pro{};
+            pro.nt = nt; pro.out_idx = out_idx; pro.n = p.n; pro.T = p.T;
+            pro.seed_lo = (uint32_t)seed; pro.seed_hi = (uint32_t)(seed >> 32);
+            pro.keys = p.keys; pro.dev = sh->call_dev; pro.in_idx = in_idx; pro.in_safe = p.in_safe;
+            pro.err = sh->err;
+            pro.fill[0] = sort_clear_job(jobs, 2, p.sort_tmp);
+            pro.fill[1] = wseg_fill_job(p.pb_keys, p.M);
+            p.wfill_done = true;
+            if (sh->prologue_sink) *sh->prologue_sink = pro;
+            else launch_index_prologue(pro, st);
+        }
+        Phase ph(sh, W2V_PH_SORT, st);
+        launch_sort_jobs(jobs, 2, bits, p.sort_tmp, sh->err, st, true);
         if (p.own_rows) launch_mark_alone(*skw, *sidx, p.M, p.keys, st);
         return W2V_OK;
     }
@@ -443,17 +456,21 @@ int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
     hipStream_t side = sh->ahead;
     const uint32_t bits = key_bits(sh->V);
     const bool marks = sh->own_rows && sh->last_update_fused;
+    // both sides' keys in the same launches: the small input-side sort rides along
+    const SortJob jobs[2] = {{x.keys, M, x.wb0, x.wb1, &x.skw, &x.sidx},
+                             {x.in_safe, n, x.ub0, x.ub1, &x.sku, &x.perm}};
     {
         Phase ph(sh, W2V_PH_NEG, side);
-        launch_dest_keys(NoiseTable{sh->bins, sh->V}, want.out_idx, n, k, want.seed, x.keys, sh->err, side);
+        IndexPrologue pro{};
+        pro.nt = NoiseTable{sh->bins, sh->V}; pro.out_idx = want.out_idx; pro.n = n; pro.T = k + 1;
+        pro.seed_lo = (uint32_t)want.seed; pro.seed_hi = (uint32_t)(want.seed >> 32);
+        pro.keys = x.keys; pro.in_idx = want.in_idx; pro.in_safe = x.in_safe; pro.err = sh->err;
+        pro.fill[0] = sort_clear_job(jobs, 2, x.sort_tmp);
+        launch_index_prologue(pro, side);
     }
     {
         Phase ph(sh, W2V_PH_SORT, side);
-        launch_check_inputs(want.in_idx, n, sh->V, x.in_safe, sh->err, side);
-        // both sides' keys in the same launches: the small input-side sort rides along
-        const SortJob jobs[2] = {{x.keys, M, x.wb0, x.wb1, &x.skw, &x.sidx},
-                                 {x.in_safe, n, x.ub0, x.ub1, &x.sku, &x.perm}};
-        launch_sort_jobs(jobs, 2, bits, x.sort_tmp, sh->err, side);
+        launch_sort_jobs(jobs, 2, bits, x.sort_tmp, sh->err, side, true);
         if (marks) launch_mark_alone(x.skw, x.sidx, M, x.keys, side);
     }
     HIP_TRY(hipEventRecord(x.ready, side));
@@ -503,7 +520,8 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
     hipStream_t side = two ? ws_owner->side : st;
     // the output-side kernel's border slots are cleared here, ahead of the input-side kernel, so
     // that the two row kernels follow each other with nothing in between
-    launch_wseg_fill(p.pb_keys, p.M, st);
+    if (p.wfill_done) p.wfill_done = false;          // (good for one shard's update)
+    else launch_wseg_fill(p.pb_keys, p.M, st);
     {
         Phase ph(ws_owner, W2V_PH_USIDE, st);
         USideArgs a{};
@@ -1036,32 +1054,18 @@ extern "C" int w2v_prefetch_cancel(w2v_shard* sh) {
 struct w2v_step_graph {
     w2v_shard* sh = nullptr;
     uint32_t n = 0, k = 0;
-    uint32_t* in_stage = nullptr;       // the captured kernels read the minibatch from here
-    uint32_t* out_stage = nullptr;
-    CallScalars* scalars = nullptr;     // ... and its seed and learning rate from here
+    IndexPrologue first{};              // the step's first launch: queued by every run, with that
+                                        // run's arrays and seed (not part of the graph)
+    CallScalars* scalars = nullptr;     // the captured kernels read seed and learning rate from here
     const char* ws_at_capture = nullptr; // the shard's scratch region the captured kernels point into
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
 };
 
-__global__ __launch_bounds__(256) void stage_step_kernel(const uint32_t* __restrict__ in_idx,
-                                                         const uint32_t* __restrict__ out_idx,
-                                                         uint32_t n, uint32_t* __restrict__ in_stage,
-                                                         uint32_t* __restrict__ out_stage,
-                                                         CallScalars* __restrict__ scalars,
-                                                         uint32_t seed_lo, uint32_t seed_hi,
-                                                         float alpha) {
-    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) { in_stage[i] = in_idx[i]; out_stage[i] = out_idx[i]; }
-    if (i == 0) { scalars->seed_lo = seed_lo; scalars->seed_hi = seed_hi; scalars->alpha = alpha; }
-}
-
 static void free_step_graph(w2v_step_graph* g) {
     if (!g) return;
     if (g->exec) (void)hipGraphExecDestroy(g->exec);
     if (g->graph) (void)hipGraphDestroy(g->graph);
-    if (g->in_stage) (void)hipFree(g->in_stage);
-    if (g->out_stage) (void)hipFree(g->out_stage);
     if (g->scalars) (void)hipFree(g->scalars);
     delete g;
 }
@@ -1079,15 +1083,11 @@ extern "C" int w2v_step_graph_create(w2v_shard* sh, uint32_t n, uint32_t k, doub
     g->sh = sh; g->n = n; g->k = k;
     hipStream_t cap = nullptr;
     auto bail = [&](int code) { if (cap) (void)hipStreamDestroy(cap); free_step_graph(g); return code; };
-    hipError_t e = hipMalloc((void**)&g->in_stage, sizeof(uint32_t) * (size_t)n);
-    if (e == hipSuccess) e = hipMalloc((void**)&g->out_stage, sizeof(uint32_t) * (size_t)n);
-    if (e == hipSuccess) e = hipMalloc((void**)&g->scalars, 256);
-    if (e == hipSuccess) e = hipMemset(g->in_stage, 0, sizeof(uint32_t) * (size_t)n);
-    if (e == hipSuccess) e = hipMemset(g->out_stage, 0, sizeof(uint32_t) * (size_t)n);
+    hipError_t e = hipMalloc((void**)&g->scalars, 256);
     if (e == hipSuccess) e = hipMemset(g->scalars, 0, 256);
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        return bail(fail(W2V_ERR_ALLOC, "allocating the staging buffers of a captured step failed: %s",
+        return bail(fail(W2V_ERR_ALLOC, "allocating the scalar block of a captured step failed: %s",
                          hipGetErrorString(e)));
     }
     // everything the step allocates must exist before the capture begins: its scratch ...
@@ -1099,19 +1099,24 @@ extern "C" int w2v_step_graph_create(w2v_shard* sh, uint32_t n, uint32_t k, doub
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&cap, hipStreamNonBlocking);
     if (e != hipSuccess) return bail(fail(W2V_ERR_HIP, "set-up of the capture failed: %s", hipGetErrorString(e)));
     // ... and the capture runs the step on ONE stream, without timing spans and without looking at
-    // announced minibatches (none can match the staging buffers).  (Captured with its side stream,
+    // announced minibatches (none can match the stand-in arrays).  The step's first launch -- keys,
+    // checked inputs, fills -- is the only one that reads the caller's arrays: it is handed back
+    // instead of captured, and every run queues it itself in front of the graph.  (Captured with its side stream,
     // as parallel branches of the graph, a 4096-pair step replays in 0.176 ms instead of 0.115 ms:
     // the two sorts are then separate chains of launches, and branches cost more than they hide.)
     const bool overlap = sh->overlap, timing = sh->timing;
-    sh->overlap = false; sh->timing = false; sh->call_dev = g->scalars;
+    sh->overlap = false; sh->timing = false; sh->call_dev = g->scalars; sh->prologue_sink = &g->first;
     e = hipStreamBeginCapture(cap, hipStreamCaptureModeThreadLocal);
     if (e == hipSuccess) {
         w2v_shard* one[1] = {sh};
-        rc = w2v_train_minibatch(one, 1, g->in_stage, g->out_stage, n, k, 0, 0.f, loss, cap);
+        const uint32_t* stand_in = (const uint32_t*)g->scalars;      // recorded, never read
+        rc = w2v_train_minibatch(one, 1, stand_in, stand_in, n, k, 0, 0.f, loss, cap);
         hipError_t e2 = hipStreamEndCapture(cap, &g->graph);
         if (rc == W2V_OK && e2 != hipSuccess) e = e2;
     }
-    sh->overlap = overlap; sh->timing = timing; sh->call_dev = nullptr;
+    sh->overlap = overlap; sh->timing = timing; sh->call_dev = nullptr; sh->prologue_sink = nullptr;
+    if (rc == W2V_OK && e == hipSuccess && g->first.keys == nullptr)
+        rc = fail(W2V_ERR_STATE, "the captured step did not hand back its first launch");
     if (rc) return bail(rc);
     if (e == hipSuccess) e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
     if (e != hipSuccess) {
@@ -1133,9 +1138,11 @@ extern "C" int w2v_step_graph_run(w2v_step_graph* g, const uint32_t* in_idx, con
         return fail(W2V_ERR_STATE, "the shard's scratch region was reallocated by a larger call after this "
                     "step was captured: create the graph again");
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(stage_step_kernel, dim3((g->n + 255) / 256), dim3(256), 0, st, in_idx, out_idx,
-                       g->n, g->in_stage, g->out_stage, g->scalars, (uint32_t)seed,
-                       (uint32_t)(seed >> 32), alpha);
+    IndexPrologue first = g->first;
+    first.in_idx = in_idx; first.out_idx = out_idx;
+    first.seed_lo = (uint32_t)seed; first.seed_hi = (uint32_t)(seed >> 32);
+    first.dev = nullptr; first.scalars_out = g->scalars; first.alpha = alpha;
+    launch_index_prologue(first, st);
     HIP_TRY(hipGraphLaunch(g->exec, st));
     g->sh->updates++;
     g->sh->last_update_fused = true;

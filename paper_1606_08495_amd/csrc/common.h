@@ -75,6 +75,20 @@ void launch_mark_alone(const uint32_t* skey, const uint32_t* sidx, uint32_t M, u
                        hipStream_t st);
 void launch_check_inputs(const uint32_t* in_idx, uint32_t n, uint32_t V, uint32_t* in_safe,
                          uint32_t* err, hipStream_t st);
+// launch_dest_keys + launch_check_inputs + two fills of 32-bit words in one launch (n pairs, T = k+1
+// slots each).  With `dev` the seed is read from device memory; with `scalars_out` the seed and the
+// learning rate given here are also written there, for the kernels that follow.
+struct FillJob { uint32_t* p; uint32_t count; uint32_t value; };
+struct IndexPrologue {
+    NoiseTable nt; const uint32_t* out_idx; uint32_t n, T; uint32_t seed_lo, seed_hi; uint32_t* keys;
+    const CallScalars* dev;
+    const uint32_t* in_idx; uint32_t* in_safe;
+    uint32_t* err;
+    FillJob fill[2];
+    CallScalars* scalars_out; float alpha;
+    uint32_t b_check, b_fill[2];        // first block of each part (set by the launcher)
+};
+void launch_index_prologue(IndexPrologue a, hipStream_t st);
 void launch_copy_negatives(const uint32_t* keys, uint32_t n, uint32_t k, uint32_t* neg,
                            hipStream_t st);
 
@@ -100,7 +114,10 @@ struct SortJob {
 };
 size_t sort_scratch_u32(uint32_t n0, uint32_t n1 = 0);
 void launch_sort_jobs(const SortJob* jobs, int njobs, uint32_t bits, uint32_t* tmp, uint32_t* err,
-                      hipStream_t st);
+                      hipStream_t st, bool cleared = false);
+// The part of tmp that must read zero when the sort starts (launch_sort_jobs clears it itself unless
+// told that the caller has).
+FillJob sort_clear_job(const SortJob* jobs, int njobs, uint32_t* tmp);
 void launch_sort_pairs(const uint32_t* keys_in, uint2* buf0, uint2* buf1, uint32_t n, uint32_t bits,
                        uint32_t* tmp, uint32_t** out_keys, uint32_t** out_vals, uint32_t* err,
                        hipStream_t st);
@@ -157,6 +174,7 @@ struct WSideArgs {
 };
 // (the cells' border slots must read KEY_NONE when the kernel starts: launch_wseg_fill writes that;
 // launch_wseg does it itself unless told that the caller already has)
+FillJob wseg_fill_job(uint32_t* pkeys, uint32_t M);
 void launch_wseg_fill(uint32_t* pkeys, uint32_t M, hipStream_t st);
 void launch_wseg(const WSideArgs& a, hipStream_t st, bool filled = false);
 

@@ -424,14 +424,17 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ x,
     if (i < n) x[i] = value;
 }
 
-void launch_wseg_fill(uint32_t* pkeys, uint32_t M, hipStream_t st) {
-    if (M == 0) return;
+FillJob wseg_fill_job(uint32_t* pkeys, uint32_t M) {
     // border slots of the cells: only pieces of long runs write them
-    uint32_t ncells = (M + WOWN_L - 1) / WOWN_L;
-    uint32_t slots = 2 * (ncells - 1);
-    if (slots)
-        hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(slots, 256)), dim3(256), 0, st, pkeys,
-                           slots, KEY_NONE);
+    const uint32_t ncells = (M + WOWN_L - 1) / WOWN_L;
+    return FillJob{pkeys, ncells ? 2 * (ncells - 1) : 0u, KEY_NONE};
+}
+
+void launch_wseg_fill(uint32_t* pkeys, uint32_t M, hipStream_t st) {
+    const FillJob f = wseg_fill_job(pkeys, M);
+    if (f.count)
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(f.count, 256)), dim3(256), 0, st, f.p,
+                           f.count, f.value);
 }
 
 void launch_wseg(const WSideArgs& w, hipStream_t st, bool filled) {

@@ -106,14 +106,11 @@ void launch_scatter_rows(float* M, RowGeom g, uint32_t d_slice, const uint32_t* 
 // that differs from the positive word; after 16 rejections it is the next word index, cyclically.
 // One thread per slot, so the generator runs with all 64 lanes busy.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void dest_keys_kernel(const uint2* __restrict__ bins, uint32_t V,
-                                                        const uint32_t* __restrict__ out_idx,
-                                                        uint32_t n, uint32_t T, uint32_t k0_arg,
-                                                        uint32_t k1_arg, uint32_t* __restrict__ keys,
-                                                        uint32_t* err, const CallScalars* dev) {
-    uint32_t i = blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void dest_key_item(const uint2* __restrict__ bins, uint32_t V,
+                                              const uint32_t* __restrict__ out_idx, uint32_t n,
+                                              uint32_t T, uint32_t k0, uint32_t k1,
+                                              uint32_t* __restrict__ keys, uint32_t* err, uint32_t i) {
     if (i >= n * T) return;
-    const uint32_t k0 = dev ? dev->seed_lo : k0_arg, k1 = dev ? dev->seed_hi : k1_arg;
     uint32_t p = i / T, j = i - p * T;
     uint32_t wo = out_idx[p];
     if (wo >= V) { wo = 0; if (j == 0) atomicOr(err, 1u); }
@@ -132,6 +129,15 @@ __global__ __launch_bounds__(256) void dest_keys_kernel(const uint2* __restrict_
         }
     }
     keys[i] = key;
+}
+
+__global__ __launch_bounds__(256) void dest_keys_kernel(const uint2* __restrict__ bins, uint32_t V,
+                                                        const uint32_t* __restrict__ out_idx,
+                                                        uint32_t n, uint32_t T, uint32_t k0_arg,
+                                                        uint32_t k1_arg, uint32_t* __restrict__ keys,
+                                                        uint32_t* err, const CallScalars* dev) {
+    const uint32_t k0 = dev ? dev->seed_lo : k0_arg, k1 = dev ? dev->seed_hi : k1_arg;
+    dest_key_item(bins, V, out_idx, n, T, k0, k1, keys, err, blockIdx.x * 256 + threadIdx.x);
 }
 
 // After the sort of the destination keys: an entry whose two neighbours carry other keys is the
@@ -167,15 +173,20 @@ void launch_mark_alone(const uint32_t* skey, const uint32_t* sidx, uint32_t M, u
 
 // Range-checked copy of the input words: an index >= V raises *err and is replaced by word 0, so no
 // later kernel can be sent outside the matrices.
-__global__ __launch_bounds__(256) void check_inputs_kernel(const uint32_t* __restrict__ in_idx,
-                                                           uint32_t n, uint32_t V,
-                                                           uint32_t* __restrict__ in_safe,
-                                                           uint32_t* err) {
-    uint32_t p = blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void check_input_item(const uint32_t* __restrict__ in_idx, uint32_t n,
+                                                 uint32_t V, uint32_t* __restrict__ in_safe,
+                                                 uint32_t* err, uint32_t p) {
     if (p >= n) return;
     uint32_t wi = in_idx[p];
     if (wi >= V) { atomicOr(err, 1u); wi = 0; }
     in_safe[p] = wi;
+}
+
+__global__ __launch_bounds__(256) void check_inputs_kernel(const uint32_t* __restrict__ in_idx,
+                                                           uint32_t n, uint32_t V,
+                                                           uint32_t* __restrict__ in_safe,
+                                                           uint32_t* err) {
+    check_input_item(in_idx, n, V, in_safe, err, blockIdx.x * 256 + threadIdx.x);
 }
 
 void launch_check_inputs(const uint32_t* in_idx, uint32_t n, uint32_t V, uint32_t* in_safe,
@@ -183,6 +194,39 @@ void launch_check_inputs(const uint32_t* in_idx, uint32_t n, uint32_t V, uint32_
     if (n == 0) return;
     hipLaunchKernelGGL(check_inputs_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, in_idx, n, V,
                        in_safe, err);
+}
+
+// The index work that depends on nothing but the call's arguments, in ONE launch: destination
+// keys, checked input words and up to two plain fills (the sort's counters, the output side's
+// border slots).  Each block does one part, told by its number.  A step of a few thousand pairs is
+// a chain of dependent launches of a few microseconds each, and these were four of them.
+__global__ __launch_bounds__(256) void index_prologue_kernel(IndexPrologue a) {
+    const uint32_t b = blockIdx.x;
+    if (b < a.b_check) {
+        const uint32_t k0 = a.dev ? a.dev->seed_lo : a.seed_lo, k1 = a.dev ? a.dev->seed_hi : a.seed_hi;
+        dest_key_item(a.nt.bins, a.nt.V, a.out_idx, a.n, a.T, k0, k1, a.keys, a.err,
+                      b * 256 + threadIdx.x);
+        if (a.scalars_out && b == 0 && threadIdx.x == 0) {
+            a.scalars_out->seed_lo = a.seed_lo; a.scalars_out->seed_hi = a.seed_hi;
+            a.scalars_out->alpha = a.alpha;
+        }
+    } else if (b < a.b_fill[0]) {
+        check_input_item(a.in_idx, a.n, a.nt.V, a.in_safe, a.err, (b - a.b_check) * 256 + threadIdx.x);
+    } else {
+        const int f = b < a.b_fill[1] ? 0 : 1;
+        const uint32_t i = (b - a.b_fill[f]) * 256 + threadIdx.x;
+        if (i < a.fill[f].count) a.fill[f].p[i] = a.fill[f].value;
+    }
+}
+
+void launch_index_prologue(IndexPrologue a, hipStream_t st) {
+    if (a.n == 0) { a.fill[0].count = 0; a.fill[1].count = 0; }   // (no pairs: nothing follows)
+    a.b_check = blocks_for((uint64_t)a.n * a.T, 256);
+    a.b_fill[0] = a.b_check + blocks_for(a.n, 256);
+    a.b_fill[1] = a.b_fill[0] + blocks_for(a.fill[0].count, 256);
+    const uint32_t blocks = a.b_fill[1] + blocks_for(a.fill[1].count, 256);
+    if (blocks == 0) return;
+    hipLaunchKernelGGL(index_prologue_kernel, dim3(blocks), dim3(256), 0, st, a);
 }
 
 __global__ __launch_bounds__(256) void copy_negatives_kernel(const uint32_t* __restrict__ keys,

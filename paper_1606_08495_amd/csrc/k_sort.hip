@@ -375,8 +375,24 @@ size_t sort_scratch_u32(uint32_t n0, uint32_t n1) {
     return 2 * SORT_MAX_PASSES * 256 + 8 + 2 * (size_t)(2 * tiles * 256) + 16;
 }
 
+// totals, tickets and the first state array: one stretch of 8-byte words at the start of tmp
+static uint64_t sort_clear_words64(uint32_t tiles) {
+    return (2 * SORT_MAX_PASSES * 256 + 8) / 2 + (uint64_t)tiles * 256;
+}
+
+FillJob sort_clear_job(const SortJob* jobs, int njobs, uint32_t* tmp) {
+    uint64_t n_all = 0;
+    for (int i = 0; i < njobs && i < 2; ++i) n_all += jobs[i].n;
+    if (n_all == 0) return FillJob{tmp, 0u, 0u};
+    const int shape = sort_shape_for(n_all);
+    uint32_t tiles = 0;
+    for (int i = 0; i < njobs && i < 2; ++i)
+        if (jobs[i].n) tiles += sort_tiles(jobs[i].n, shape);
+    return FillJob{tmp, (uint32_t)(2 * sort_clear_words64(tiles)), 0u};
+}
+
 void launch_sort_jobs(const SortJob* jobs, int njobs, uint32_t bits, uint32_t* tmp, uint32_t* err,
-                      hipStream_t st) {
+                      hipStream_t st, bool cleared) {
     if (bits == 0) bits = 1;
     if (bits > 32) bits = 32;
     SortArgs a{};
@@ -416,10 +432,11 @@ void launch_sort_jobs(const SortJob* jobs, int njobs, uint32_t bits, uint32_t* t
     a.state[0] = (uint64_t*)(tmp + 2 * SORT_MAX_PASSES * 256 + 8);
     a.state[1] = a.state[0] + (uint64_t)tiles * 256;
     a.err = err;
-    // totals, tickets and the first state array in one stretch of 8-byte words
-    const uint64_t clear64 = (2 * SORT_MAX_PASSES * 256 + 8) / 2 + (uint64_t)tiles * 256;
-    hipLaunchKernelGGL(sort_fill_kernel, dim3(blocks_for(clear64, 256)), dim3(256), 0, st,
-                       (uint64_t*)tmp, clear64);
+    if (!cleared) {
+        const uint64_t clear64 = sort_clear_words64(tiles);
+        hipLaunchKernelGGL(sort_fill_kernel, dim3(blocks_for(clear64, 256)), dim3(256), 0, st,
+                           (uint64_t*)tmp, clear64);
+    }
     const uint32_t blocks0 = blocks_for(a.job[0].n, SORT_THREADS * TOT_ITEMS);
     const uint32_t blocks1 = live > 1 ? blocks_for(a.job[1].n, SORT_THREADS * TOT_ITEMS) : 0u;
     hipLaunchKernelGGL(sort_totals_kernel, dim3(blocks0 + blocks1), dim3(SORT_THREADS), 0, st, a, blocks0);
