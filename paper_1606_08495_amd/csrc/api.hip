@@ -504,6 +504,81 @@ void join_output_sort(w2v_shard* sh, hipStream_t st) {
     if (sh->overlap && sh->side) (void)hipStreamWaitEvent(st, sh->ev_join, 0);
 }
 
+// The same update on ONE stream (a captured step, or a shard told not to use its second stream),
+// for the row geometries that have the joint launch: after the input-side kernel, each launch
+// carries one walk of the output side together with one higher level of the input side and one
+// step of the loss, which depend on different things; the delta buffer is written back last.
+// Same kernels' code on the same data as queue_adjust below: the same bits.
+void queue_adjust_one_stream(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* sku,
+                             const uint32_t* perm, const uint32_t* skw, const uint32_t* sidx,
+                             const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
+                             double* loss_out, hipStream_t st) {
+    if (p.wfill_done) p.wfill_done = false;
+    else launch_wseg_fill(p.pb_keys, p.M, st);
+    {
+        Phase ph(ws_owner, W2V_PH_USIDE, st);
+        USideArgs a{};
+        a.U = sh->U; a.W = sh->W; a.g = sh->g; a.skey = sku; a.perm = perm; a.keys = p.keys;
+        a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
+        a.dots_out = (fused && loss_out) ? p.dots : nullptr; a.delta = p.delta; a.dkey = p.dkey;
+        a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
+        if (p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
+        a.dev = ws_owner->call_dev;
+        launch_useg(a, st);
+    }
+    const uint32_t cp = useg_pairs_per_chunk(p.T, sh->g.d4, p.n);
+    struct Side { float* src_rows; uint32_t* src_keys; float* dst_rows; uint32_t* dst_keys; uint32_t slots, level; };
+    Side us{p.pa_rows, p.pa_keys, p.pe_rows, p.pe_keys, slots_after(p.n, cp), 0u};
+    Side ws{p.pb_rows, p.pb_keys, p.pc_rows, p.pc_keys, p.slots_w1, 0u};
+    uint32_t loss_step = (loss_out && fused) ? 1u : 0u;
+    if (loss_step && (uint64_t)p.n * p.T > 256ull * adjust_stage_loss_blocks_max()) {
+        Phase ph(ws_owner, W2V_PH_COEFF, st);                 // too many terms for one final block
+        launch_loss_from_dots(p.dots, p.n, p.T, p.loss_tmp, loss_out, st);
+        loss_step = 0;
+    }
+    auto advance = [](Side& x) {
+        x.slots = slots_after(x.slots, tail_entries_per_chunk());
+        std::swap(x.src_rows, x.dst_rows);
+        std::swap(x.src_keys, x.dst_keys);
+    };
+    for (bool first = true; first || us.slots || ws.slots || loss_step; first = false) {
+        Phase ph(ws_owner, first ? W2V_PH_WSIDE : W2V_PH_APPLY, st);
+        AdjustStage x;
+        WSideArgs w{};
+        TailArgs wt{}, ut{};
+        const bool w_level = !first && ws.slots > 0, u_level = us.slots > 0;
+        if (first) {
+            w.U = sh->U; w.W = sh->W; w.g = sh->g; w.skey = skw; w.sidx = sidx; w.M = p.M; w.T = p.T;
+            w.in_idx = p.in_safe; w.coeffs = fused ? coeffs_out : coeffs_in; w.alpha = alpha;
+            w.prows = p.pb_rows; w.pkeys = p.pb_keys; w.skip_alone = p.own_rows;
+            w.dev = ws_owner->call_dev;
+            x.wfirst = &w;
+        } else if (w_level) {
+            wt = TailArgs{sh->W, sh->g, alpha, ws.src_rows, ws.src_keys, ws.slots, ws.dst_rows, ws.dst_keys};
+            wt.level = ++ws.level; wt.dev = ws_owner->call_dev;
+            x.wtail = &wt;
+        }
+        if (u_level) {
+            ut = TailArgs{sh->U, sh->g, alpha, us.src_rows, us.src_keys, us.slots, us.dst_rows, us.dst_keys};
+            ut.defer_rows = p.delta; ut.defer_keys = p.dkey; ut.level = ++us.level; ut.cp = cp;
+            ut.dev = ws_owner->call_dev;
+            x.utail = &ut;
+        }
+        if (loss_step) {
+            x.loss_step = loss_step; x.dots = p.dots; x.n = p.n; x.T = p.T;
+            x.loss_tmp = p.loss_tmp; x.loss_out = loss_out;
+            loss_step = loss_step == 1 ? 2u : 0u;
+        }
+        launch_adjust_stage(x, st);
+        if (w_level) advance(ws);
+        if (u_level) advance(us);
+    }
+    {
+        Phase ph(ws_owner, W2V_PH_APPLY, st);
+        launch_apply_delta(sh->U, sh->g, p.delta, p.dkey, p.n, alpha, st, ws_owner->call_dev);
+    }
+}
+
 // The update of one shard from given coefficients (or, fused, from its own dots).
 // After the input-side kernel the coefficients and the input side's partial sums exist, so the
 // minibatch loss (if asked for, fused form only) and the input side's higher reduction levels --
@@ -517,6 +592,9 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
                   double* loss_out, hipStream_t st) {
     // (loss_out: fused form only; the dots it is formed from go to p.dots)
     const bool two = ws_owner->overlap && ws_owner->side;
+    if (!two && adjust_stage_supported(sh->g.d4))
+        return queue_adjust_one_stream(ws_owner, sh, p, sku, perm, skw, sidx, coeffs_in, coeffs_out, fused,
+                                       alpha, loss_out, st);
     hipStream_t side = two ? ws_owner->side : st;
     // the output-side kernel's border slots are cleared here, ahead of the input-side kernel, so
     // that the two row kernels follow each other with nothing in between

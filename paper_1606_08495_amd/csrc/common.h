@@ -191,6 +191,21 @@ struct TailArgs {
 };
 void launch_tail(const TailArgs& a, hipStream_t st);
 
+// Parts of one update that do not depend on each other, in ONE launch (each may be absent): the
+// output side's level-1 kernel (wfirst; its border slots already cleared) or one of its higher
+// levels (wtail), one higher level of the input side (utail, with defer_rows), and one step of the
+// loss of the fused form (loss_step 1: dots -> block sums in loss_tmp, needs at most
+// adjust_stage_loss_blocks_max() blocks of 256 terms; 2: block sums -> *loss_out).  Same code and
+// same bits as the separate launches.  Only for the row geometries adjust_stage_supported names.
+struct AdjustStage {
+    const WSideArgs* wfirst = nullptr; const TailArgs* wtail = nullptr; const TailArgs* utail = nullptr;
+    uint32_t loss_step = 0; const float* dots = nullptr; uint32_t n = 0, T = 0;
+    double* loss_tmp = nullptr; double* loss_out = nullptr;
+};
+bool adjust_stage_supported(uint32_t d4);
+uint32_t adjust_stage_loss_blocks_max();
+void launch_adjust_stage(const AdjustStage& x, hipStream_t st);
+
 // U[dkey[ps]] += alpha * delta[ps] wherever dkey[ps] != KEY_NONE.
 void launch_apply_delta(float* U, RowGeom g, const float* delta, const uint32_t* dkey, uint32_t n,
                         float alpha, hipStream_t st, const CallScalars* dev = nullptr);

@@ -10,6 +10,7 @@
 // the result is bitwise reproducible, and a row that collects millions of contributions is spread
 // over as many groups as it has chunks.
 #include "rows.h"
+#include "loss.h"
 
 namespace w2v {
 
@@ -84,12 +85,14 @@ struct SegArgs {
 // input-side kernel's chunk grid; the pair position right after that border lies inside the run,
 // is not the run's first pair (the run was cut there), and so holds no sum of its own.  Runs are
 // disjoint ranges of pair positions, hence no two finished runs share a place.
+// (vb: the block's number among the blocks of this walk -- the kernel below passes blockIdx.x, a
+// launch that carries several walks the block's offset within its own)
 template <int G, int NV, int C, int D, int SRC, bool DEFER = false>
-__global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
+__device__ __forceinline__ void seg_body(const SegArgs& a, uint32_t vb) {
     static_assert(C <= G && C % D == 0, "chunk must fit a lane group");
     const float alpha = a.dev ? a.dev->alpha : a.alpha;
     const int l = threadIdx.x % G;
-    const uint32_t c = (blockIdx.x * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
+    const uint32_t c = (vb * (uint32_t)ADJ_THREADS + threadIdx.x) / G;
     const uint32_t nchunks = (a.entries + C - 1) / C;
     if (c >= nchunks) return;
     const uint32_t e0 = c * C;
@@ -225,6 +228,11 @@ __global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
     }
 }
 
+template <int G, int NV, int C, int D, int SRC, bool DEFER = false>
+__global__ __launch_bounds__(ADJ_THREADS) void seg_kernel(SegArgs a) {
+    seg_body<G, NV, C, D, SRC, DEFER>(a, blockIdx.x);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Output-vector side, level 1, with run ownership.  A grid of chunks of C entries only decides WHO
 // sums a run, not where it is cut:
@@ -250,7 +258,7 @@ enum : uint32_t { ACT_SKIP = 0, ACT_ADD = 1, ACT_COMPLETE = 2, ACT_HEAD = 3 };
 uint32_t wseg_entries_per_chunk() { return WOWN_L; }
 
 template <int G, int NV, int D>
-__global__ __launch_bounds__(wown_threads(G)) void wown_kernel(SegArgs a) {
+__device__ __forceinline__ void wown_body(const SegArgs& a, uint32_t vb) {
     constexpr int WOWN_THREADS = wown_threads(G);
     constexpr int GROUPS = WOWN_THREADS / G;
     constexpr int C = WOWN_C, L = WOWN_L;
@@ -262,7 +270,7 @@ __global__ __launch_bounds__(wown_threads(G)) void wown_kernel(SegArgs a) {
     __shared__ uint32_t s_act[GROUPS][WOWN_E];
     __shared__ uint32_t s_list[GROUPS][WOWN_E];
     const int l = threadIdx.x % G, grp = threadIdx.x / G;
-    const uint32_t c = blockIdx.x * (uint32_t)GROUPS + grp;
+    const uint32_t c = vb * (uint32_t)GROUPS + grp;
     const uint32_t nchunks = (a.entries + C - 1) / C;
     const bool active = c < nchunks;
     const int64_t base = (int64_t)c * C;
@@ -418,6 +426,11 @@ __global__ __launch_bounds__(wown_threads(G)) void wown_kernel(SegArgs a) {
     }
 }
 
+template <int G, int NV, int D>
+__global__ __launch_bounds__(wown_threads(G)) void wown_kernel(SegArgs a) {
+    wown_body<G, NV, D>(a, blockIdx.x);
+}
+
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ x, uint32_t n,
                                                        uint32_t value) {
     uint32_t i = blockIdx.x * 256 + threadIdx.x;
@@ -437,13 +450,28 @@ void launch_wseg_fill(uint32_t* pkeys, uint32_t M, hipStream_t st) {
                            f.count, f.value);
 }
 
-void launch_wseg(const WSideArgs& w, hipStream_t st, bool filled) {
-    if (w.M == 0) return;
+static SegArgs seg_args_of(const WSideArgs& w) {
     SegArgs a{};
     a.src = (const float4*)w.U; a.dst = (float4*)w.W; a.g = w.g; a.skey = w.skey; a.sidx = w.sidx;
     a.in_idx = w.in_idx; a.coeffs = w.coeffs; a.entries = w.M; a.T = w.T;
     a.alpha = w.alpha; a.prows = (float4*)w.prows; a.pkeys = w.pkeys; a.dev = w.dev;
     a.skip_alone = w.skip_alone;
+    return a;
+}
+
+static SegArgs seg_args_of(const TailArgs& t) {
+    SegArgs a{};
+    a.src = (const float4*)t.src_rows; a.dst = (float4*)t.M; a.g = t.g; a.skey = t.src_keys;
+    a.sidx = nullptr; a.in_idx = nullptr; a.coeffs = nullptr; a.entries = t.entries; a.T = 1;
+    a.skip_alone = false;
+    a.alpha = t.alpha; a.prows = (float4*)t.prows; a.pkeys = t.pkeys; a.dev = t.dev;
+    a.defer_rows = (float4*)t.defer_rows; a.defer_keys = t.defer_keys; a.level = t.level; a.cp = t.cp;
+    return a;
+}
+
+void launch_wseg(const WSideArgs& w, hipStream_t st, bool filled) {
+    if (w.M == 0) return;
+    const SegArgs a = seg_args_of(w);
     if (!filled) launch_wseg_fill(w.pkeys, w.M, st);
     uint32_t nchunks = (w.M + WOWN_C - 1) / WOWN_C;
 #define CALL(G, NV)                                                                              \
@@ -457,12 +485,7 @@ void launch_wseg(const WSideArgs& w, hipStream_t st, bool filled) {
 
 void launch_tail(const TailArgs& t, hipStream_t st) {
     if (t.entries == 0) return;
-    SegArgs a{};
-    a.src = (const float4*)t.src_rows; a.dst = (float4*)t.M; a.g = t.g; a.skey = t.src_keys;
-    a.sidx = nullptr; a.in_idx = nullptr; a.coeffs = nullptr; a.entries = t.entries; a.T = 1;
-    a.skip_alone = false;
-    a.alpha = t.alpha; a.prows = (float4*)t.prows; a.pkeys = t.pkeys; a.dev = t.dev;
-    a.defer_rows = (float4*)t.defer_rows; a.defer_keys = t.defer_keys; a.level = t.level; a.cp = t.cp;
+    const SegArgs a = seg_args_of(t);
     uint32_t nchunks = (t.entries + TAIL_C - 1) / TAIL_C;
 #define CALL(G, NV)                                                                              \
     do {                                                                                         \
@@ -476,6 +499,89 @@ void launch_tail(const TailArgs& t, hipStream_t st) {
                                dim3(ADJ_THREADS), 0, st, a);                                     \
     } while (0)
     W2V_DISPATCH_GEOM(t.g.d4, CALL);
+#undef CALL
+}
+
+// ---------------------------------------------------------------------------------------------
+// One launch for parts of the update that do not depend on each other: a walk of the output side
+// (its level-1 kernel when FIRST, else one of its higher levels), one higher level of the input
+// side (which parks its sums in the delta buffer), and one step of the loss.  Each block does one
+// part, told by its number, with the same code as the kernels above, so the bits are the same.
+// On one stream a step of a few thousand pairs is a chain of launches of a few microseconds each;
+// this takes the input side's levels and the loss out of that chain.
+// ---------------------------------------------------------------------------------------------
+struct StageDev {
+    SegArgs w, u;
+    uint32_t w_blocks, u_blocks;
+    uint32_t loss_step;              // 0 none, 1 terms -> block sums, 2 block sums -> loss
+    const float* dots; uint32_t total, T;
+    double* block_loss; uint32_t nb; double* loss_out;
+};
+
+template <int G, int NV, bool FIRST>
+__global__ __launch_bounds__(ADJ_THREADS) void adjust_stage_kernel(StageDev s) {
+    constexpr int D = NV <= 2 ? 4 : 2;
+    static_assert(wown_threads(G) == ADJ_THREADS, "the parts share one block size");
+    uint32_t b = blockIdx.x;
+    if (b < s.w_blocks) {
+        if (FIRST) wown_body<G, NV, D>(s.w, b);
+        else seg_body<G, NV, TAIL_C, D, 1, false>(s.w, b);
+        return;
+    }
+    b -= s.w_blocks;
+    if (b < s.u_blocks) {
+        seg_body<G, NV, TAIL_C, D, 1, true>(s.u, b);
+        return;
+    }
+    b -= s.u_blocks;
+    __shared__ double red[256];
+    if (s.loss_step == 1) loss_terms_block(s.dots, s.total, s.T, s.block_loss, b, red);
+    else sum_doubles_block(s.block_loss, s.nb, s.nb, s.loss_out, 0u, red);
+}
+
+bool adjust_stage_supported(uint32_t d4) { return d4 > 16; }    // (sixteen-lane groups use blocks of 128)
+uint32_t adjust_stage_loss_blocks_max() { return LOSS_SUM_SPAN; }
+
+template <int G, int NV>
+static void launch_stage_shape(StageDev s, uint32_t w_chunks, uint32_t u_chunks, uint32_t loss_blocks,
+                               bool first, hipStream_t st) {
+    if constexpr (G != 16) {
+        s.w_blocks = blocks_for((uint64_t)w_chunks * G, ADJ_THREADS);
+        s.u_blocks = blocks_for((uint64_t)u_chunks * G, ADJ_THREADS);
+        const dim3 grid(s.w_blocks + s.u_blocks + loss_blocks);
+        if (first)
+            hipLaunchKernelGGL((adjust_stage_kernel<G, NV, true>), grid, dim3(ADJ_THREADS), 0, st, s);
+        else
+            hipLaunchKernelGGL((adjust_stage_kernel<G, NV, false>), grid, dim3(ADJ_THREADS), 0, st, s);
+    }
+}
+
+void launch_adjust_stage(const AdjustStage& x, hipStream_t st) {
+    StageDev s{};
+    RowGeom g{};
+    uint32_t w_chunks = 0, u_chunks = 0, loss_blocks = 0;
+    const bool first = x.wfirst && x.wfirst->M;
+    if (first) {
+        s.w = seg_args_of(*x.wfirst); g = x.wfirst->g;
+        w_chunks = (x.wfirst->M + WOWN_C - 1) / WOWN_C;
+    } else if (x.wtail && x.wtail->entries) {
+        s.w = seg_args_of(*x.wtail); g = x.wtail->g;
+        w_chunks = (x.wtail->entries + TAIL_C - 1) / TAIL_C;
+    }
+    if (x.utail && x.utail->entries) {
+        s.u = seg_args_of(*x.utail); g = x.utail->g;
+        u_chunks = (x.utail->entries + TAIL_C - 1) / TAIL_C;
+    }
+    s.loss_step = x.loss_step;
+    if (x.loss_step) {
+        s.dots = x.dots; s.total = x.n * x.T; s.T = x.T; s.block_loss = x.loss_tmp;
+        s.nb = blocks_for(s.total, 256); s.loss_out = x.loss_out;
+        loss_blocks = x.loss_step == 1 ? s.nb : 1u;
+    }
+    if (!w_chunks && !u_chunks && !loss_blocks) return;
+    if (!w_chunks && !u_chunks) g.d4 = 17;        // (only the loss part runs: any supported shape)
+#define CALL(G, NV) launch_stage_shape<G, NV>(s, w_chunks, u_chunks, loss_blocks, first, st)
+    W2V_DISPATCH_GEOM(g.d4, CALL);
 #undef CALL
 }
 

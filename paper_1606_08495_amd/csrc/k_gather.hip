@@ -3,6 +3,7 @@
 #include <algorithm>
 
 #include "rows.h"
+#include "loss.h"
 
 namespace w2v {
 
@@ -300,9 +301,6 @@ void launch_dots(const float* U, const float* W, RowGeom g, const uint32_t* in_i
 // its relative accuracy when f is large.  Loss terms are softplus(-f) / softplus(f), summed per
 // block in double by a fixed tree, then over blocks in index order by one thread.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float softplus(float x) {
-    return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
-}
 
 __global__ __launch_bounds__(256) void coeffs_kernel(PartialPtrs parts, uint32_t S, uint32_t total,
                                                      uint32_t T, float* __restrict__ coeffs,
@@ -338,30 +336,19 @@ __global__ __launch_bounds__(256) void sum_doubles_kernel(const double* __restri
                                                           uint32_t span,
                                                           double* __restrict__ out) {
     __shared__ double red[256];
-    uint64_t lo = (uint64_t)blockIdx.x * span;
-    uint64_t hi = lo + span < n ? lo + span : n;
-    double s = 0.0;
-    for (uint64_t i = lo + threadIdx.x; i < hi; i += 256) s += x[i];
-    red[threadIdx.x] = s;
-    __syncthreads();
-    for (int h = 128; h >= 1; h >>= 1) {
-        if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) out[blockIdx.x] = red[0];
+    sum_doubles_block(x, n, span, out, blockIdx.x, red);
 }
 
-constexpr uint32_t SUM_SPAN = 4096;
 
-// x[n] -> *out, using tmp[ceil(n / SUM_SPAN)] doubles.
+// x[n] -> *out, using tmp[ceil(n / LOSS_SUM_SPAN)] doubles.
 static void launch_sum_doubles(const double* x, uint32_t n, double* tmp, double* out,
                                hipStream_t st) {
-    uint32_t nb = (n + SUM_SPAN - 1) / SUM_SPAN;
+    uint32_t nb = (n + LOSS_SUM_SPAN - 1) / LOSS_SUM_SPAN;
     if (nb <= 1) {
         hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st, x, n, n ? n : 1u, out);
         return;
     }
-    hipLaunchKernelGGL(sum_doubles_kernel, dim3(nb), dim3(256), 0, st, x, n, SUM_SPAN, tmp);
+    hipLaunchKernelGGL(sum_doubles_kernel, dim3(nb), dim3(256), 0, st, x, n, LOSS_SUM_SPAN, tmp);
     hipLaunchKernelGGL(sum_doubles_kernel, dim3(1), dim3(256), 0, st, (const double*)tmp, nb, nb,
                        out);
 }
@@ -369,7 +356,7 @@ static void launch_sum_doubles(const double* x, uint32_t n, double* tmp, double*
 // doubles of scratch for the loss: the per-block (or per-pair) terms plus the second-stage partials
 size_t coeffs_loss_scratch_doubles(uint32_t n, uint32_t T) {
     size_t terms = std::max<size_t>(blocks_for((uint64_t)n * T, 256), n);
-    return terms + (terms + SUM_SPAN - 1) / SUM_SPAN + 8;
+    return terms + (terms + LOSS_SUM_SPAN - 1) / LOSS_SUM_SPAN + 8;
 }
 
 void launch_coeffs(PartialPtrs parts, uint32_t S, uint32_t n, uint32_t T, float* coeffs,
@@ -392,19 +379,7 @@ __global__ __launch_bounds__(256) void loss_from_dots_kernel(const float* __rest
                                                              uint32_t total, uint32_t T,
                                                              double* __restrict__ block_loss) {
     __shared__ double red[256];
-    uint32_t i = blockIdx.x * 256 + threadIdx.x;
-    double term = 0.0;
-    if (i < total) {
-        const float f = dots[i];
-        term = (double)((i % T) == 0 ? softplus(-f) : softplus(f));
-    }
-    red[threadIdx.x] = term;
-    __syncthreads();
-    for (int s = 128; s >= 1; s >>= 1) {
-        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) block_loss[blockIdx.x] = red[0];
+    loss_terms_block(dots, total, T, block_loss, blockIdx.x, red);
 }
 
 void launch_loss_from_dots(const float* dots, uint32_t n, uint32_t T, double* tmp, double* loss_out,

@@ -499,6 +499,53 @@ def test_captured_step_replays_give_the_same_bits_as_the_plain_call(V, d, n, k, 
         sh.destroy()
 
 
+@pytest.mark.parametrize("V,d,n,k", [(3000, 100, 5000, 5), (40, 300, 20_000, 3), (5000, 72, 180_000, 5),
+                                     (300, 60, 3000, 5), (7, 520, 900, 2)])
+def test_a_shard_kept_on_one_stream_gives_the_same_bits(V, d, n, k, monkeypatch):
+    """A shard created with W2V_NO_OVERLAP=1 queues everything on the caller's stream; where the row
+    geometry allows it carries the output side's walks, the input side's higher levels and the loss
+    in joint launches.  Two-call form, fused step with loss, and a step over two column halves:
+    the same bits as a shard that spreads the work over its own streams (few words: rows that
+    collect thousands of contributions, several levels on both sides; 180 000 pairs: more loss terms
+    than the joint launch takes)."""
+    say("one stream", V, d, n, k)
+    rng = np.random.default_rng(V * 31 + n)
+    counts = zipf_counts(V)
+    cdf = workloads.zipf_cdf(V, 1.0)
+    half = (d // 2 + 3) // 4 * 4
+
+    def shards():
+        return (make_shard(V, d, 4, counts), make_shard(V, half, 4, counts, d_total=d),
+                make_shard(V, d - half, 4, counts, d_total=d, col_begin=half))
+
+    spread = shards()
+    monkeypatch.setenv("W2V_NO_OVERLAP", "1")
+    single = shards()
+    monkeypatch.delenv("W2V_NO_OVERLAP")
+    la = torch.zeros(1, dtype=torch.float64, device="cuda")
+    lb = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for h in range(3):
+        a, b = dev(workloads.zipf_draw(cdf, n, rng)), dev(workloads.zipf_draw(cdf, n, rng))
+        coeffs_ = torch.tensor(rng.uniform(-1, 1, n * (k + 1)).astype(np.float32), device="cuda")
+        seed, alpha = w2v.minibatch_seed(5, h), 0.03 / (1 + h)
+        for group, loss in ((spread, la), (single, lb)):
+            assert group[0].dotprod(a, b, k, seed).numel() == n * (k + 1)
+            group[0].adjust(a, b, k, seed, coeffs_, alpha)                       # two-call form
+            w2v.train_minibatch([group[0]], a, b, k, seed + 1, alpha, loss=loss)  # fused
+        torch.cuda.synchronize()
+        assert la.item() == lb.item(), h
+        for group, loss in ((spread, la), (single, lb)):
+            w2v.train_minibatch(list(group[1:]), a, b, k, seed + 2, alpha, loss=loss)   # S = 2
+        torch.cuda.synchronize()
+        assert la.item() == lb.item(), h
+        for x, y in zip(spread, single):
+            for which in (0, 1):
+                assert np.array_equal(all_rows(x, which), all_rows(y, which)), (h, which)
+    for sh in spread + single:
+        sh.status()
+        sh.destroy()
+
+
 def test_tiny_config_hundred_minibatches_through_the_captured_step():
     # BASELINE config 1 again, every minibatch a replay of one captured step
     wl = workloads.WORKLOADS["tiny"]
