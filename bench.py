@@ -597,14 +597,13 @@ def main():
                 step_graph.run(a, b, w2v.minibatch_seed(wl.seed, h), workloads.alpha_schedule(wl, h, H))
                 return a, b
             if args.prefetch_depth == 2:
-                # two ahead: minibatch h+2 is announced right after step h is queued, so its index
-                # work runs beside step h+1 and has until step h+2 to finish
+                # two ahead: minibatch h+2 is announced before step h is queued, so its index work
+                # starts beside step h and has until step h+2 to finish
                 if h == 0:
-                    sh.prefetch_minibatch(a, b, wl.k, w2v.minibatch_seed(wl.seed, 0))
                     sh.prefetch_minibatch(*stream.peek(), wl.k, w2v.minibatch_seed(wl.seed, 1))
+                sh.prefetch_minibatch(*stream.peek(1), wl.k, w2v.minibatch_seed(wl.seed, h + 2))
                 w2v.train_minibatch([sh], a, b, wl.k, w2v.minibatch_seed(wl.seed, h),
                                     workloads.alpha_schedule(wl, h, H), loss=loss)
-                sh.prefetch_minibatch(*stream.peek(1), wl.k, w2v.minibatch_seed(wl.seed, h + 2))
                 return a, b
             if not args.no_prefetch:                       # the next minibatch's index work, ahead
                 na, nb = stream.peek()
@@ -659,7 +658,12 @@ def main():
         def step(h):
             seed = w2v.minibatch_seed(wl.seed, h)
             if not args.no_prefetch:          # the next minibatch's index work, beside this one's rows
-                sh.prefetch_minibatch(a, b, wl.k, w2v.minibatch_seed(wl.seed, h + 1))
+                if args.prefetch_depth == 2:  # ... or that of the one after it as well
+                    if h == 0:
+                        sh.prefetch_minibatch(a, b, wl.k, w2v.minibatch_seed(wl.seed, 1))
+                    sh.prefetch_minibatch(a, b, wl.k, w2v.minibatch_seed(wl.seed, h + 2))
+                else:
+                    sh.prefetch_minibatch(a, b, wl.k, w2v.minibatch_seed(wl.seed, h + 1))
             sh.dotprod(a, b, wl.k, seed, out=dots)
             sh.adjust(a, b, wl.k, seed, gd, wl.alpha)
 

@@ -206,9 +206,11 @@ int w2v_step_graph_destroy(w2v_step_graph* graph);
  * (the one exception to the rule above that only work queued on `stream` touches the caller's
  * arrays): keep them allocated and unchanged until the call that uses the prepared work has been
  * queued on `stream`, or, if no such call follows, until the device has been synchronised.
- * Two minibatches can be held ahead (a third look-ahead replaces the older one); each keeps its own
- * device buffers (about 20 (k+2) n bytes, allocated on first use and reused).  An announcement serves
- * one of the next two update calls on the shard; after that it is void (w2v_prefetch_cancel). */
+ * Three announcements can be held at a time (a fourth replaces the oldest), so that a loop may run
+ * two minibatches ahead -- prefetch(h+2); train(h); prefetch(h+3); train(h+1); ... -- which gives the
+ * index work two steps to finish in where it does not fit beside one; each keeps its own device
+ * buffers (about 20 (k+2) n bytes, allocated on first use and reused).  An announcement serves one of
+ * the next three update calls on the shard; after that it is void (w2v_prefetch_cancel). */
 int w2v_prefetch_minibatch(w2v_shard* shard, const uint32_t* in_idx_dev, const uint32_t* out_idx_dev,
                            uint32_t n, uint32_t k, uint64_t seed, void* stream);
 
@@ -217,7 +219,7 @@ int w2v_prefetch_minibatch(w2v_shard* shard, const uint32_t* in_idx_dev, const u
  * arrays are no longer read and may be changed or freed.  An announcement is matched by the
  * addresses of its arrays, so call this (or synchronise and never pass those addresses again)
  * before reusing an announced array's memory for other indices under the same n, k and seed.
- * Independently of this call, an announcement that the next two update calls on the shard
+ * Independently of this call, an announcement that the next three update calls on the shard
  * (w2v_adjust, w2v_train_minibatch and their bag-of-words forms) do not use is void. */
 int w2v_prefetch_cancel(w2v_shard* shard);
 

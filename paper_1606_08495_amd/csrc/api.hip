@@ -159,9 +159,9 @@ struct w2v_shard {
     bool own_rows = true;           // fused step: singly named output rows updated by the input side
     bool last_update_fused = true;  // what the last update on this shard was: an announced minibatch
                                     // gets its rows-named-once marks only if the fused step is likely
-    IndexSet sets[2];
-    Prepared prep[2];               // what sets[i] holds
-    int next_set = 0;
+    static constexpr int N_SETS = 3;   // two announced minibatches besides the one in use
+    IndexSet sets[N_SETS];
+    Prepared prep[N_SETS];          // what sets[i] holds
     CbowSet csets[2];
     CbowPrepared cprep[2];
     int next_cset = 0;
@@ -445,7 +445,13 @@ int queue_keys_and_sorts(w2v_shard* sh, Plan& p, const uint32_t* in_idx, const u
 // The index work of a minibatch announced by w2v_prefetch_minibatch, queued on the second stream
 // behind everything queued on `st` so far.
 int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
-    const int which = sh->next_set;
+    // a set that holds no live announcement (its last user was queued on `st` before this call, and
+    // the chain waits for `st`), else the one announced longest ago
+    int which = 0;
+    for (int i = 0; i < w2v_shard::N_SETS; ++i) {
+        if (!sh->prep[i].valid) { which = i; break; }
+        if (sh->prep[i].born < sh->prep[which].born) which = i;
+    }
     IndexSet& x = sh->sets[which];
     sh->prep[which].valid = false;
     const uint32_t n = want.n, k = want.k, M = n * (k + 1);
@@ -478,19 +484,18 @@ int run_prefetch_chain(w2v_shard* sh, const Prepared& want, hipStream_t st) {
     Prepared& pr = sh->prep[which];
     pr = want;
     pr.valid = true; pr.set = which; pr.own_rows = marks; pr.born = sh->updates;
-    sh->next_set = which ^ 1;
     return W2V_OK;
 }
 
 // The set that w2v_prefetch_minibatch filled for exactly this minibatch, or -1.
-// An announcement is good for the next PREP_MAX_AGE update calls on the shard (two minibatches can
-// be held ahead); an older one is void, so that a forgotten set cannot be matched much later by
+// An announcement is good for the next PREP_MAX_AGE update calls on the shard (a loop may announce
+// two minibatches ahead of the one it trains); an older one is void, so that a forgotten set cannot be matched much later by
 // arrays that happen to live at the same addresses.
-constexpr uint64_t PREP_MAX_AGE = 2;
+constexpr uint64_t PREP_MAX_AGE = 3;
 
 int find_prepared(w2v_shard* sh, const uint32_t* in_idx, const uint32_t* out_idx, uint32_t n,
                   uint32_t k, uint64_t seed) {
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < w2v_shard::N_SETS; ++i) {
         Prepared& pr = sh->prep[i];
         if (pr.valid && sh->updates - pr.born >= PREP_MAX_AGE) pr.valid = false;
         if (pr.valid && pr.in_idx == in_idx && pr.out_idx == out_idx && pr.n == n && pr.k == k &&
@@ -805,7 +810,7 @@ extern "C" int w2v_shard_set_counts(w2v_shard* sh, const uint64_t* counts, doubl
     HIP_TRY(hipMemcpy(sh->keep, keep.data(), sizeof(uint64_t) * (size_t)V, hipMemcpyHostToDevice));
     sh->has_tables = true;
     sh->table_tag = tag;
-    sh->prep[0].valid = sh->prep[1].valid = false;   // negatives drawn from the old table are void
+    for (Prepared& pr : sh->prep) pr.valid = false;   // negatives drawn from the old table are void
     sh->cprep[0].valid = sh->cprep[1].valid = false;
     return W2V_OK;
 }
@@ -1121,7 +1126,7 @@ extern "C" int w2v_prefetch_cancel(w2v_shard* sh) {
     // the chains may still be reading the caller's arrays: wait for them before the caller is told
     // that the arrays are its own again
     if (sh->ahead) HIP_TRY(hipStreamSynchronize(sh->ahead));
-    sh->prep[0].valid = sh->prep[1].valid = false;
+    for (Prepared& pr : sh->prep) pr.valid = false;
     sh->cprep[0].valid = sh->cprep[1].valid = false;
     return W2V_OK;
 }

@@ -952,7 +952,7 @@ def test_announced_step_over_column_shards_gives_the_same_bits():
 
 def test_cancelled_and_stale_announcements_are_not_used():
     """An announcement is matched by the addresses of its arrays.  After w2v_prefetch_cancel, or
-    once two update calls have gone by without using it, new contents at the same addresses must be
+    once three update calls have gone by without using it, new contents at the same addresses must be
     trained as what they are."""
     V, d, n, k = 900, 60, 2000, 5
     rng = np.random.default_rng(41)
@@ -966,11 +966,12 @@ def test_cancelled_and_stale_announcements_are_not_used():
         told.prefetch_minibatch(buf_in, buf_out, k, 11)
         if mode == "cancel":
             told.prefetch_cancel()
-        else:                                   # two other updates go by: the announcement is void
+        else:                                   # three other updates go by: the announcement is void
             torch.cuda.synchronize()
             for sh in (told, plain):
                 w2v.train_minibatch([sh], x, y, k, 7, 0.05)
                 w2v.train_minibatch([sh], y, x, k, 8, 0.05)
+                w2v.train_minibatch([sh], x, x, k, 9, 0.05)
         torch.cuda.synchronize()
         buf_in.copy_(a2); buf_out.copy_(b2)     # same addresses, same n, k, seed -- other words
         w2v.train_minibatch([told], buf_in, buf_out, k, 11, 0.05)
