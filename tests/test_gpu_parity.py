@@ -1074,3 +1074,45 @@ def test_announced_edge_shapes_give_the_same_bits(V, d, n, k):
     for sh in (told, plain):
         sh.status()
         sh.destroy()
+
+
+@pytest.mark.parametrize("form", ["fused", "two calls"])
+def test_announcing_two_minibatches_ahead_gives_the_same_bits(form):
+    """prefetch(h+2); train(h); prefetch(h+3); train(h+1); ...: three announcements are alive at a
+    time, each in buffers of its own, and each serves the step it was made for.  A fourth
+    announcement in a row replaces the oldest, whose step then does its index work itself."""
+    V, d, n, k, steps = 3000, 100, 6000, 5, 7
+    rng = np.random.default_rng(17)
+    counts = zipf_counts(V)
+    cdf = workloads.zipf_cdf(V, 1.0)
+    told, plain = make_shard(V, d, 3, counts), make_shard(V, d, 3, counts)
+    batches = [(dev(workloads.zipf_draw(cdf, n, rng)), dev(workloads.zipf_draw(cdf, n, rng)))
+               for _ in range(steps + 3)]
+    coeffs_ = torch.tensor(rng.uniform(-1, 1, n * (k + 1)).astype(np.float32), device="cuda")
+    la, lb = (torch.zeros(1, dtype=torch.float64, device="cuda") for _ in range(2))
+
+    def step(sh, h, loss):
+        a, b = batches[h]
+        if form == "fused":
+            w2v.train_minibatch([sh], a, b, k, 100 + h, 0.02, loss=loss)
+        else:
+            sh.dotprod(a, b, k, 100 + h)
+            sh.adjust(a, b, k, 100 + h, coeffs_, 0.02)
+
+    told.prefetch_minibatch(*batches[0], k, 100)
+    told.prefetch_minibatch(*batches[1], k, 101)
+    for h in range(steps):
+        told.prefetch_minibatch(*batches[h + 2], k, 100 + h + 2)
+        if h == 3:                    # one announcement too many: the oldest (this step's) is dropped
+            told.prefetch_minibatch(*batches[h + 3], k, 100 + h + 3)
+        step(told, h, la)
+        step(plain, h, lb)
+        torch.cuda.synchronize()
+        if form == "fused":
+            assert la.item() == lb.item(), h
+        for which in (0, 1):
+            assert np.array_equal(all_rows(told, which), all_rows(plain, which)), (h, which)
+    for sh in (told, plain):
+        sh.prefetch_cancel()
+        sh.status()
+        sh.destroy()
