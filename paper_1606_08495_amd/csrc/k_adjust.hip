@@ -42,7 +42,9 @@ constexpr int useg_maxe(int G) {                 // entries, at most: c T < E + 
 // A lane group walks its chunk pair by pair, one memory round trip each, so a small minibatch cut
 // into long chunks leaves the chip to a handful of groups (4096 pairs in chunks of 32: 128 groups,
 // 109 us of row latency in a row): below USEG_MIN_CHUNKS chunks the chunks shrink, down to two pairs.
-constexpr uint32_t USEG_MIN_CHUNKS = 4096;
+// (32768: from 2^20 pairs on the long chunks stay; 2^18 pairs run 5 % faster per step than with
+// 4096, the 2^17 examples of a bag-of-words minibatch 4 %; 4096 pairs the same.)
+constexpr uint32_t USEG_MIN_CHUNKS = 32768;
 uint32_t useg_pairs_per_chunk(uint32_t T, uint32_t d4, uint32_t n) {
     const int G = d4 <= 16 ? 16 : (d4 <= 32 ? 32 : 64);                 // as W2V_DISPATCH_GEOM
     uint32_t c = ((uint32_t)useg_e(G) + T - 1) / T;
