@@ -269,7 +269,8 @@ int w2v_cbow_train_minibatch(w2v_shard* const* shards, uint32_t S, const uint32_
  * shard is this one, a w2v_cbow_dotprod or a w2v_cbow_adjust on this shard with the same three
  * index arrays (same pointers, contents unchanged in between), m, n, k and seed uses the prepared
  * work (the dotprod leaves it in place, an update consumes it); results are identical either way.
- * Two minibatches can be held ahead; w2v_shard_set_counts voids what was announced before it.
+ * Two announcements can be held at a time (each serves one of the next three update calls on the
+ * shard); w2v_shard_set_counts voids what was announced before it.
  * As there, the three index arrays are read on the shard's own stream: keep them allocated and
  * unchanged until the call that uses the prepared work has been queued (or the device synchronised). */
 int w2v_cbow_prefetch_minibatch(w2v_shard* shard, const uint32_t* ctx_off_dev,
