@@ -509,6 +509,26 @@ void join_output_sort(w2v_shard* sh, hipStream_t st) {
     if (sh->overlap && sh->side) (void)hipStreamWaitEvent(st, sh->ev_join, 0);
 }
 
+// First part of a shard's update, the same on one stream or several: the output-side kernel's border
+// slots are cleared here, ahead of the input-side kernel, so that the two row kernels follow each
+// other with nothing in between (unless the call's first launch has cleared them already: good for
+// one shard's update); then the input-side kernel.
+void queue_input_side(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* sku,
+                      const uint32_t* perm, const float* coeffs_in, float* coeffs_out, bool fused,
+                      float alpha, bool keep_dots, hipStream_t st) {
+    if (p.wfill_done) p.wfill_done = false;
+    else launch_wseg_fill(p.pb_keys, p.M, st);
+    Phase ph(ws_owner, W2V_PH_USIDE, st);
+    USideArgs a{};
+    a.U = sh->U; a.W = sh->W; a.g = sh->g; a.skey = sku; a.perm = perm; a.keys = p.keys;
+    a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
+    a.dots_out = (fused && keep_dots) ? p.dots : nullptr; a.delta = p.delta; a.dkey = p.dkey;
+    a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
+    if (p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
+    a.dev = ws_owner->call_dev;
+    launch_useg(a, st);
+}
+
 // The same update on ONE stream (a captured step, or a shard told not to use its second stream),
 // for the row geometries that have the joint launch: after the input-side kernel, each launch
 // carries one walk of the output side together with one higher level of the input side and one
@@ -518,19 +538,7 @@ void queue_adjust_one_stream(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const 
                              const uint32_t* perm, const uint32_t* skw, const uint32_t* sidx,
                              const float* coeffs_in, float* coeffs_out, bool fused, float alpha,
                              double* loss_out, hipStream_t st) {
-    if (p.wfill_done) p.wfill_done = false;
-    else launch_wseg_fill(p.pb_keys, p.M, st);
-    {
-        Phase ph(ws_owner, W2V_PH_USIDE, st);
-        USideArgs a{};
-        a.U = sh->U; a.W = sh->W; a.g = sh->g; a.skey = sku; a.perm = perm; a.keys = p.keys;
-        a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
-        a.dots_out = (fused && loss_out) ? p.dots : nullptr; a.delta = p.delta; a.dkey = p.dkey;
-        a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
-        if (p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
-        a.dev = ws_owner->call_dev;
-        launch_useg(a, st);
-    }
+    queue_input_side(ws_owner, sh, p, sku, perm, coeffs_in, coeffs_out, fused, alpha, loss_out != nullptr, st);
     const uint32_t cp = useg_pairs_per_chunk(p.T, sh->g.d4, p.n);
     struct Side { float* src_rows; uint32_t* src_keys; float* dst_rows; uint32_t* dst_keys; uint32_t slots, level; };
     Side us{p.pa_rows, p.pa_keys, p.pe_rows, p.pe_keys, slots_after(p.n, cp), 0u};
@@ -601,21 +609,7 @@ void queue_adjust(w2v_shard* ws_owner, w2v_shard* sh, Plan& p, const uint32_t* s
         return queue_adjust_one_stream(ws_owner, sh, p, sku, perm, skw, sidx, coeffs_in, coeffs_out, fused,
                                        alpha, loss_out, st);
     hipStream_t side = two ? ws_owner->side : st;
-    // the output-side kernel's border slots are cleared here, ahead of the input-side kernel, so
-    // that the two row kernels follow each other with nothing in between
-    if (p.wfill_done) p.wfill_done = false;          // (good for one shard's update)
-    else launch_wseg_fill(p.pb_keys, p.M, st);
-    {
-        Phase ph(ws_owner, W2V_PH_USIDE, st);
-        USideArgs a{};
-        a.U = sh->U; a.W = sh->W; a.g = sh->g; a.skey = sku; a.perm = perm; a.keys = p.keys;
-        a.n = p.n; a.T = p.T; a.coeffs_in = coeffs_in; a.coeffs_out = coeffs_out;
-        a.dots_out = (fused && loss_out) ? p.dots : nullptr; a.delta = p.delta; a.dkey = p.dkey;
-        a.prows = p.pa_rows; a.pkeys = p.pa_keys; a.fused = fused;
-        if (p.own_rows) { a.W_update = sh->W; a.alpha = alpha; }
-        a.dev = ws_owner->call_dev;
-        launch_useg(a, st);
-    }
+    queue_input_side(ws_owner, sh, p, sku, perm, coeffs_in, coeffs_out, fused, alpha, loss_out != nullptr, st);
     // The input side's higher levels only touch its slots and the delta buffer, and the loss only
     // reads the coefficients: both go to the second stream and run beside the output-side kernel.
     if (two) {
