@@ -681,12 +681,14 @@ extern "C" int w2v_shard_create_ex(uint32_t V, uint32_t d_total, uint32_t col_be
     sh->V = V; sh->d_total = d_total; sh->col_begin = col_begin; sh->d_slice = d_slice;
     sh->seed = seed; sh->init_mode = init_mode;
     sh->g.d4 = (d_slice + 3) / 4;
-    // Row stride.  A short row that straddles 128-byte lines costs a whole extra line per gather
-    // (a 240-byte row touches 2.75 lines on average, 2 when aligned), so rows under 512 bytes are
-    // padded to a multiple of 128 bytes when that adds at most an eighth; longer rows gain nothing
-    // measurable and stay dense.  W2V_ROW_ALIGN_FLOATS overrides the granularity (for experiments).
+    // Row stride.  A row that straddles 128-byte lines costs an extra line per gather (a 240-byte
+    // row touches 2.75 lines on average, 2 when aligned; a 1200-byte row 10.25 against 10) and
+    // its write-back leaves two lines partly written instead of one, so rows are padded to a
+    // multiple of 128 bytes when that adds at most an eighth (d = 60: +20 % gather rate; d = 300:
+    // the benchmark step 2.8 % shorter for 6.7 % more memory; d = 200: 2 % for 12 %).
+    // W2V_ROW_ALIGN_FLOATS overrides the granularity (for experiments).
     uint32_t align4 = 1;                     // row stride granularity in float4
-    if (sh->g.d4 < 32) {
+    {
         uint32_t padded = ((sh->g.d4 + 7) / 8) * 8;
         if ((padded - sh->g.d4) * 8 <= sh->g.d4) align4 = 8;
     }

@@ -196,7 +196,7 @@ __device__ __forceinline__ void seg_body(const SegArgs& a, uint32_t vb) {
                         out[v].z = fmaf(alpha, acc[v].z, dstv[t][v].z);
                         out[v].w = fmaf(alpha, acc[v].w, dstv[t][v].w);
                     }
-                    store_row<G, NV>(a.dst + (uint64_t)dk * s4, d4, l, out);
+                    store_row<G, NV>(a.dst + (uint64_t)dk * s4, (uint32_t)s4, l, out);
                 } else if (ih && rl) {      // the run came in from the previous chunk and ends here
                     store_row<G, NV>(a.prows + (uint64_t)head_slot * s4, d4, l, acc);
                     head_key = dk;
@@ -342,7 +342,7 @@ __device__ __forceinline__ void wown_body(const SegArgs& a, uint32_t vb) {
             out[v].z = fmaf(alpha, acc[v].z, old[v].z);
             out[v].w = fmaf(alpha, acc[v].w, old[v].w);
         }
-        store_row_nt<G, NV>(a.dst + (uint64_t)row * s4, d4, l, out);
+        store_row_nt<G, NV>(a.dst + (uint64_t)row * s4, (uint32_t)s4, l, out);
     };
     auto fetch = [&](int idx, float4 (&sv)[NV], float4 (&dv)[NV]) {
         const bool on = idx < count;
@@ -713,7 +713,7 @@ __global__ __launch_bounds__(USEG_THREADS) void useg_kernel(USideArgs a, uint32_
                             out[v].z = fmaf(alpha, fmaf(gco[t], u[v].z, 0.f), w[t][v].z);
                             out[v].w = fmaf(alpha, fmaf(gco[t], u[v].w, 0.f), w[t][v].w);
                         }
-                        store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(rr & ~ALONE) * s4, d4, l, out);
+                        store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(rr & ~ALONE) * s4, (uint32_t)s4, l, out);
                     }
                 }
                 // this register set is free again: fetch the matching row of the following batch
@@ -882,7 +882,7 @@ __global__ __launch_bounds__(USEG_THREADS, 5) void useg_multi_kernel(USideArgs a
                                 out[v].z = fmaf(alpha, fmaf(gco[j], u[b][v].z, 0.f), w[b][j][v].z);
                                 out[v].w = fmaf(alpha, fmaf(gco[j], u[b][v].w, 0.f), w[b][j][v].w);
                             }
-                            store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(r & ~ALONE) * s4, d4,
+                            store_row_nt<G, NV>((float4*)a.W_update + (uint64_t)(r & ~ALONE) * s4, (uint32_t)s4,
                                                 l, out);
                         }
                     }
@@ -993,7 +993,7 @@ __global__ __launch_bounds__(ADJ_THREADS) void apply_delta_kernel(float4* __rest
             uv[v].z = fmaf(alpha, dv[v].z, uv[v].z);
             uv[v].w = fmaf(alpha, dv[v].w, uv[v].w);
         }
-        store_row<G, NV>(U + (uint64_t)key * g.stride4, g.d4, l, uv);
+        store_row<G, NV>(U + (uint64_t)key * g.stride4, g.stride4, l, uv);
     }
 }
 
