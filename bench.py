@@ -505,8 +505,10 @@ def distinct_rows(torch, shard, in_idx, out_idx, k, seed):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: 1500 for the skip-gram run on full300 or slice60, a few "
+                         "seconds of device time; 20 otherwise)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before (default 20 / 5)")
     ap.add_argument("--workload", default="full300",
                     choices=["full300", "slice60", "tiny", "search200m", "stress25"])
     ap.add_argument("--variant", default="sgns", choices=["sgns", "cbow", "topk", "gather"],
@@ -538,6 +540,13 @@ def main():
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates HBM counters)")
     args = ap.parse_args()
+    # The default run lasts a few seconds on the device (long enough for an outside observer's
+    # utilisation sampler to see it); step time is the same over 20, 300 or 1500 steps.
+    long_run = args.variant == "sgns" and args.workload in ("full300", "slice60") and not args.graph
+    if args.steps is None:
+        args.steps = 1500 if long_run else 20
+    if args.warmup is None:
+        args.warmup = 20 if long_run else 5
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (a shard is one GPU's column slice); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
