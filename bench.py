@@ -301,8 +301,10 @@ def run_cbow(args, torch, w2v, workloads):
             first = tuple(w2v.index_to_numpy(x).copy() for x in e)
     Wm = max(Wm, 1)
     sh.status()
-    sh.timing_enable(True)
-    sh.timing_read()
+    # A bag-of-words step is about a millisecond and the host needs nearly as long to queue it, so
+    # the two event records per phase of the library's timing spans would cost the step 5 %: the K
+    # timed steps run without them, and the phase times come from a second run of up to 20 steps
+    # right after, with the spans on.
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ctx_total = 0
@@ -312,6 +314,14 @@ def run_cbow(args, torch, w2v, workloads):
     t_queued = time.perf_counter() - t0          # the host's share: all K steps are queued by now
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    K2 = min(K, 20)
+    sh.timing_enable(True)
+    sh.timing_read()
+    t2 = time.perf_counter()
+    for h in range(Wm + K, Wm + K + K2):
+        last = step(h)
+    torch.cuda.synchronize()
+    dt_spans = time.perf_counter() - t2
     phases = sh.timing_read()
     sh.timing_enable(False)
     sh.status()
@@ -340,7 +350,7 @@ def run_cbow(args, torch, w2v, workloads):
                  for name, (ms, cnt) in phases.items() if cnt}
     dom = max((p for p in per_phase if p in algo),
               key=lambda p: per_phase[p]["ms_per_launch"] * per_phase[p]["launches"])
-    launches_per_step = per_phase[dom]["launches"] / K
+    launches_per_step = per_phase[dom]["launches"] / K2
     dom_ms = per_phase[dom]["ms_per_launch"] * launches_per_step      # per minibatch
     achieved = algo[dom] / (dom_ms * 1e-3) / 1e9
     traffic = None          # L2<->fabric bytes per launch, from the committed rocprofv3 counter summary
@@ -354,6 +364,7 @@ def run_cbow(args, torch, w2v, workloads):
         "metric": "CBOW training examples/s (k negatives incl.) on 1 MI355X",
         "value": n * K / dt, "unit": "examples/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": dt * 1e3 / K, "host_queue_ms_per_step": t_queued * 1e3 / K,
+        "ms_per_step_with_phase_spans": dt_spans * 1e3 / K2, "steps_with_phase_spans": K2,
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name + "/cbow", "V": wl.V, "d_slice": wl.d_slice,
